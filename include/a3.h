@@ -1,0 +1,167 @@
+/*
+ * a3.h - C ABI of the per-layer A^3 KV-cache fusion path (arXiv 2511.17560) for one MI355X.
+ *
+ * The method (section "Attention-Aware Accurate Fusion") fuses per-chunk K/V caches that
+ * were precomputed chunk by chunk (Eq. 1) into the cache of the concatenated prompt
+ * X = (S, D_1 .. D_k, Q).  Per layer it
+ *   1. recovers positions: keys are re-rotated to their position in X        (Eq. 2)
+ *   2. scores every context token by the attention the question pays to it    (Eq. 3, first line)
+ *   3. keeps the top p = r*n tokens                                           (Eq. 3, second line)
+ *   4. recomputes Q/K/V of those tokens and of the question, attends over the
+ *      fused cache                                                            (Eq. 4, Eq. 5)
+ *   5. writes the fresh K/V back into the fused cache                         (Eq. 5, middle lines)
+ *
+ * Conventions shared by every entry point
+ *   - Pointers named in a3_layout and every tensor / index argument are DEVICE pointers unless
+ *     stated otherwise; the a3_layout struct itself lives in HOST memory.
+ *   - Everything is allocated and freed by the caller.  The library allocates nothing, keeps no
+ *     state between calls, and only enqueues kernels on `stream` (a hipStream_t, NULL = the
+ *     null stream).  No call synchronises with the host or copies between host and device.
+ *   - Tensors are dense row-major.  "packed rows": requests back to back, each request being
+ *     its context chunks followed by its question tokens.  T = total_tokens.
+ *       hidden            [T, hidden]
+ *       K / V caches      [T, n_kv_heads, head_dim]
+ *       Q / outputs       [n, n_q_heads, head_dim]
+ *     Element type is layout->dtype (A3_BF16: bfloat16, A3_F32: float) for all of them.
+ *     Every tensor base pointer must be 16-byte aligned.
+ *   - Return value: A3_OK or a negative a3_status.  Argument errors are found on the host before
+ *     anything is launched (message via a3_last_error()); a failed launch gives A3_ERR_HIP.
+ *     Contents of device index arrays cannot be checked on the host: they are preconditions.
+ *   - Same inputs give bit-identical outputs from run to run (no floating-point atomics).
+ *   - Supported shapes: head_dim 64 or 128, n_q_heads a multiple of n_kv_heads,
+ *     hidden a multiple of 32; A3_BF16 additionally needs head_dim 128 and hidden a multiple
+ *     of 64 (the MFMA kernels).
+ */
+#ifndef A3_H
+#define A3_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  A3_OK = 0,
+  A3_ERR_INVALID_ARG = -1,
+  A3_ERR_UNSUPPORTED = -2,
+  A3_ERR_WORKSPACE = -3,
+  A3_ERR_HIP = -4
+} a3_status;
+
+typedef enum { A3_F32 = 0, A3_BF16 = 1 } a3_dtype;
+
+/* Which coordinates form a rotated pair.  INTERLEAVED = (2i, 2i+1), the block-diagonal matrix
+ * printed in section "Position Recovery"; HALF = (i, i + head_dim/2). */
+typedef enum { A3_ROPE_INTERLEAVED = 0, A3_ROPE_HALF = 1 } a3_rope;
+
+typedef struct a3_layout {
+  /* ---- model (host scalars) ---- */
+  int dtype;            /* a3_dtype */
+  int n_q_heads;
+  int n_kv_heads;
+  int head_dim;
+  int hidden;
+  int rope_layout;      /* a3_rope */
+  double rope_base;     /* theta_i = rope_base^(-2i/head_dim) */
+  float sm_scale;       /* softmax scale; 0 means 1/sqrt(head_dim) */
+  /* ---- batch (host scalars) ---- */
+  int n_req;            /* requests in the batch */
+  int n_chunks;         /* context chunks over all requests */
+  int total_tokens;     /* T */
+  int max_ctx_len;      /* max over requests of the context length  */
+  int max_q_len;        /* max over requests of the question length */
+  /* ---- batch (device int32 arrays, caller fills them) ---- */
+  const int *seg_start;   /* [n_req+1] packed row of each request's first token; seg_start[n_req] = T */
+  const int *ctx_len;     /* [n_req] context tokens of the request (its chunks, back to back) */
+  const int *q_len;       /* [n_req] question tokens; seg_start[r+1]-seg_start[r] = ctx_len[r]+q_len[r] */
+  const int *chunk_start; /* [n_chunks] packed row of the chunk's first token, strictly ascending */
+  const int *chunk_len;   /* [n_chunks] */
+  const int *chunk_delta; /* [n_chunks] position of the chunk's first token inside its request:
+                             the amount its keys are rotated by in a3_rope_realign */
+  /* ---- derived tables (device, caller allocates, a3_layout_prepare fills) ---- */
+  int *tok_pos;           /* [T] position of the packed row inside its request */
+  int *tok_req;           /* [T] request of the packed row */
+  int *tok_chunk;         /* [T] chunk of a context row, -1 for a question row */
+  int *q_start;           /* [n_req+1] exclusive prefix sum of q_len: first row of the request in a
+                             [sum q_len, ...] question tensor */
+  float *rope_chunk_cs;   /* [n_chunks, head_dim/2, 2] (cos, sin) of chunk_delta * theta_i */
+  float *rope_pos_cs;     /* [max_ctx_len+max_q_len, head_dim/2, 2] (cos, sin) of p * theta_i */
+} a3_layout;
+
+/* Bytes of workspace that a3_question_scores / a3_topk_select / a3_fused_attention may need for
+ * this layout when at most max_active_rows rows are active.  Host call, no GPU work. */
+size_t a3_workspace_bytes(const a3_layout *layout, int max_active_rows);
+
+/* Fills tok_pos, tok_req, tok_chunk, q_start and both RoPE tables (angles formed and evaluated in
+ * double precision, stored as float).  Once per batch of requests; layer independent. */
+a3_status a3_layout_prepare(const a3_layout *layout, void *stream);
+
+/* Step 1, Eq. 2 (position recovery).  The cached keys carry RoPE of their chunk-local
+ * position; every context key of chunk c is rotated further by chunk_delta[c] so that it
+ * carries RoPE of its position in the concatenated prompt.  V is not touched.
+ * k_cat, k_fused: [T, n_kv_heads, head_dim].  k_fused may alias k_cat (in place); otherwise
+ * they must not overlap, and the question rows of k_fused are left unwritten. */
+a3_status a3_rope_realign(const a3_layout *layout, const void *k_cat, void *k_fused, void *stream);
+
+/* Step 2, Eq. 3 first line.  scores[t] = sum over query heads hq and question tokens j of
+ * softmax_t(q_{j,hq} . k'_{t, hq / (n_q_heads/n_kv_heads)} * sm_scale), the softmax taken over
+ * the context keys of the token's own request.  q_question: [sum q_len, n_q_heads, head_dim]
+ * in request order (RoPE already applied); k_fused: realigned cache; scores: float [T],
+ * question rows are set to -inf.  ws: at least a3_workspace_bytes() bytes. */
+a3_status a3_question_scores(const a3_layout *layout, const void *q_question, const void *k_fused,
+                             float *scores, void *ws, size_t ws_bytes, void *stream);
+
+/* Step 3, Eq. 3 second line (Re = top_p(s)).  For request r the k_r = sel_start[r+1] -
+ * sel_start[r] context rows with the largest scores; equal scores go to the lowest row;
+ * sel_idx[sel_start[r] .. sel_start[r+1]) receives packed rows in ascending order.
+ * scores: float [T]; sel_start: device int32 [n_req+1], sel_start[0] = 0, k_r <= ctx_len[r];
+ * total_k = sel_start[n_req] (host value); sel_idx: device int32 [total_k].
+ * NaN scores are not supported. */
+a3_status a3_topk_select(const a3_layout *layout, const float *scores, const int *sel_start,
+                         int total_k, int *sel_idx, void *ws, size_t ws_bytes, void *stream);
+
+/* Step 4 (projection part), Eq. 5 first lines.  For each listed packed row t:
+ *   Q = RoPE_p(x_t Wq^T + bq),  K = RoPE_p(x_t Wk^T + bk),  V = x_t Wv^T + bv,   p = tok_pos[t].
+ * hidden: [T, hidden]; row_idx: device int32 [n_rows] (NULL = rows 0..n_rows-1);
+ * wq: [n_q_heads*head_dim, hidden], wk, wv: [n_kv_heads*head_dim, hidden] (row-major [out, in]);
+ * bq, bk, bv: [out] or NULL.  q_out: [n_rows, n_q_heads, head_dim], k_out, v_out:
+ * [n_rows, n_kv_heads, head_dim], compact in list order; each may be NULL to skip it.
+ * Accumulation and RoPE in float, one rounding to the storage type on store. */
+a3_status a3_selected_qkv_proj(const a3_layout *layout, const void *hidden, const int *row_idx, int n_rows,
+                               const void *wq, const void *wk, const void *wv,
+                               const void *bq, const void *bk, const void *bv,
+                               void *q_out, void *k_out, void *v_out, void *stream);
+
+/* Step 5, Eq. 5 middle lines.  k_fused[row_idx[i]] <- k_new[i], v_fused[row_idx[i]] <- v_new[i].
+ * k_new, v_new: [n_rows, n_kv_heads, head_dim]; row_idx: device int32 [n_rows], no duplicates.
+ * Must be enqueued before a3_fused_attention on the same stream: attention reads the updated rows. */
+a3_status a3_kv_scatter(const a3_layout *layout, const void *k_new, const void *v_new, const int *row_idx,
+                        int n_rows, void *k_fused, void *v_fused, void *stream);
+
+/* Step 4 (attention part), Eq. 4 and Eq. 5 last line.  For each active row i at packed row
+ * t = act_idx[i]:  out[i, hq] = softmax(q_act[i, hq] . K'[u, hq/G] * sm_scale) V[u, hq/G] over the
+ * packed rows u of the same request with u <= t (causal by global position, the row itself included).
+ * q_act, out: [n_act, n_q_heads, head_dim]; act_idx: device int32 [n_act], strictly ascending.
+ * ws: at least a3_workspace_bytes(layout, n_act) bytes. */
+a3_status a3_fused_attention(const a3_layout *layout, const void *q_act, const int *act_idx, int n_act,
+                             const void *k_fused, const void *v_fused, void *out,
+                             void *ws, size_t ws_bytes, void *stream);
+
+/* Helper between steps 3 and 4: the active rows [Re, Q] of Eq. 4 / Eq. 5 in ascending packed order.
+ * For request r, act_idx receives its k_r selected rows followed by its q_len[r] question rows, at
+ * offset sel_start[r] + q_start[r].  sel_idx: device int32 [total_k] as written by a3_topk_select;
+ * act_idx: device int32 [n_act], n_act = total_k + sum q_len (host value, checked against nothing on
+ * the device: it only sizes the launch). */
+a3_status a3_active_rows(const a3_layout *layout, const int *sel_idx, const int *sel_start, int n_act,
+                         int *act_idx, void *stream);
+
+const char *a3_strerror(a3_status status);
+/* Text of the last error raised on the calling thread ("" if none). */
+const char *a3_last_error(void);
+int a3_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* A3_H */

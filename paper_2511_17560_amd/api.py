@@ -1,0 +1,213 @@
+"""Thin ctypes binding of liba3.so: same entry-point names as include/a3.h, argument
+marshalling only.  torch is used for device memory and for the current HIP stream; every
+step of the path runs in the library's kernels.  There is no fallback: if the library is
+missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liba3.so")
+
+A3_OK, A3_ERR_INVALID_ARG, A3_ERR_UNSUPPORTED, A3_ERR_WORKSPACE, A3_ERR_HIP = 0, -1, -2, -3, -4
+A3_F32, A3_BF16 = 0, 1
+A3_ROPE_INTERLEAVED, A3_ROPE_HALF = 0, 1
+
+EXPORTS = ["a3_workspace_bytes", "a3_layout_prepare", "a3_rope_realign", "a3_question_scores", "a3_topk_select",
+           "a3_selected_qkv_proj", "a3_kv_scatter", "a3_fused_attention", "a3_active_rows", "a3_strerror", "a3_last_error", "a3_version"]
+
+
+class A3Error(RuntimeError):
+    def __init__(self, status: int, where: str, text: str):
+        super().__init__(f"{where}: status {status}: {text}")
+        self.status = status
+
+
+class a3_layout(C.Structure):
+    _fields_ = [
+        ("dtype", C.c_int), ("n_q_heads", C.c_int), ("n_kv_heads", C.c_int), ("head_dim", C.c_int),
+        ("hidden", C.c_int), ("rope_layout", C.c_int), ("rope_base", C.c_double), ("sm_scale", C.c_float),
+        ("n_req", C.c_int), ("n_chunks", C.c_int), ("total_tokens", C.c_int), ("max_ctx_len", C.c_int),
+        ("max_q_len", C.c_int),
+        ("seg_start", C.c_void_p), ("ctx_len", C.c_void_p), ("q_len", C.c_void_p),
+        ("chunk_start", C.c_void_p), ("chunk_len", C.c_void_p), ("chunk_delta", C.c_void_p),
+        ("tok_pos", C.c_void_p), ("tok_req", C.c_void_p), ("tok_chunk", C.c_void_p), ("q_start", C.c_void_p),
+        ("rope_chunk_cs", C.c_void_p), ("rope_pos_cs", C.c_void_p),
+    ]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Loads liba3.so (built beforehand by ``python -m paper_2511_17560_amd.build``)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2511_17560_amd.build` "
+                           "(there is no fallback path)")
+    L = C.CDLL(LIB_PATH)
+    P, I, V = C.POINTER(a3_layout), C.c_int, C.c_void_p
+    L.a3_workspace_bytes.restype = C.c_size_t
+    L.a3_workspace_bytes.argtypes = [P, I]
+    L.a3_layout_prepare.argtypes = [P, V]
+    L.a3_rope_realign.argtypes = [P, V, V, V]
+    L.a3_question_scores.argtypes = [P, V, V, V, V, C.c_size_t, V]
+    L.a3_topk_select.argtypes = [P, V, V, I, V, V, C.c_size_t, V]
+    L.a3_selected_qkv_proj.argtypes = [P, V, V, I, V, V, V, V, V, V, V, V, V, V]
+    L.a3_kv_scatter.argtypes = [P, V, V, V, I, V, V, V]
+    L.a3_fused_attention.argtypes = [P, V, V, I, V, V, V, V, C.c_size_t, V]
+    L.a3_active_rows.argtypes = [P, V, V, I, V, V]
+    for name in ("a3_active_rows", "a3_layout_prepare", "a3_rope_realign", "a3_question_scores", "a3_topk_select",
+                 "a3_selected_qkv_proj", "a3_kv_scatter", "a3_fused_attention"):
+        getattr(L, name).restype = I
+    L.a3_strerror.restype = C.c_char_p
+    L.a3_strerror.argtypes = [I]
+    L.a3_last_error.restype = C.c_char_p
+    L.a3_version.restype = I
+    _lib = L
+    return L
+
+
+def _check(status: int, where: str):
+    if status != A3_OK:
+        L = lib()
+        raise A3Error(status, where, f"{L.a3_strerror(status).decode()}: {L.a3_last_error().decode()}")
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    assert t.is_contiguous(), "tensors must be contiguous"
+    return t.data_ptr()
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def torch_dtype(dtype: str) -> torch.dtype:
+    return {"f32": torch.float32, "bf16": torch.bfloat16}[dtype]
+
+
+class Layout:
+    """Owns the device index arrays and derived tables of one batch and the a3_layout struct
+    that points at them."""
+
+    def __init__(self, *, dtype: str, n_q_heads: int, n_kv_heads: int, head_dim: int, hidden: int,
+                 rope_base: float, rope_layout: int, seg_start, ctx_len, q_len, chunk_start, chunk_len,
+                 chunk_delta, sm_scale: float = 0.0, device="cuda", prepare: bool = True, stream=None):
+        dev = torch.device(device)
+        i32 = lambda a: torch.as_tensor(np.ascontiguousarray(a, dtype=np.int32), device=dev)
+        self.dtype = dtype
+        self.device = dev
+        self.seg_start, self.ctx_len, self.q_len = i32(seg_start), i32(ctx_len), i32(q_len)
+        self.chunk_start, self.chunk_len, self.chunk_delta = i32(chunk_start), i32(chunk_len), i32(chunk_delta)
+        n_req, n_chunks = len(ctx_len), len(chunk_start)
+        T = int(np.asarray(seg_start)[-1])
+        max_ctx = int(np.max(ctx_len)) if n_req else 0
+        max_q = int(np.max(q_len)) if n_req else 0
+        self.total_tokens, self.n_req, self.n_chunks = T, n_req, n_chunks
+        self.tok_pos = torch.empty(max(T, 1), dtype=torch.int32, device=dev)
+        self.tok_req = torch.empty(max(T, 1), dtype=torch.int32, device=dev)
+        self.tok_chunk = torch.empty(max(T, 1), dtype=torch.int32, device=dev)
+        self.q_start = torch.empty(n_req + 1, dtype=torch.int32, device=dev)
+        self.rope_chunk_cs = torch.empty((max(n_chunks, 1), head_dim // 2, 2), dtype=torch.float32, device=dev)
+        self.rope_pos_cs = torch.empty((max(max_ctx + max_q, 1), head_dim // 2, 2), dtype=torch.float32, device=dev)
+        s = a3_layout()
+        s.dtype = {"f32": A3_F32, "bf16": A3_BF16}[dtype]
+        s.n_q_heads, s.n_kv_heads, s.head_dim, s.hidden = n_q_heads, n_kv_heads, head_dim, hidden
+        s.rope_layout, s.rope_base, s.sm_scale = rope_layout, rope_base, sm_scale
+        s.n_req, s.n_chunks, s.total_tokens, s.max_ctx_len, s.max_q_len = n_req, n_chunks, T, max_ctx, max_q
+        s.seg_start, s.ctx_len, s.q_len = self.seg_start.data_ptr(), self.ctx_len.data_ptr(), self.q_len.data_ptr()
+        if n_chunks:
+            s.chunk_start, s.chunk_len = self.chunk_start.data_ptr(), self.chunk_len.data_ptr()
+            s.chunk_delta = self.chunk_delta.data_ptr()
+        s.tok_pos, s.tok_req, s.tok_chunk = self.tok_pos.data_ptr(), self.tok_req.data_ptr(), self.tok_chunk.data_ptr()
+        s.q_start = self.q_start.data_ptr()
+        s.rope_chunk_cs, s.rope_pos_cs = self.rope_chunk_cs.data_ptr(), self.rope_pos_cs.data_ptr()
+        self.struct = s
+        if prepare:
+            a3_layout_prepare(self, stream)
+
+    @classmethod
+    def from_workload(cls, w, device="cuda", **kw) -> "Layout":
+        s = w.shape
+        return cls(dtype=s.dtype, n_q_heads=s.n_q_heads, n_kv_heads=s.n_kv_heads, head_dim=s.head_dim,
+                   hidden=s.hidden, rope_base=s.rope_base, rope_layout=s.rope_layout, seg_start=w.seg_start,
+                   ctx_len=w.ctx_len, q_len=w.q_lens, chunk_start=w.chunk_start, chunk_len=w.chunk_len,
+                   chunk_delta=w.chunk_delta, device=device, **kw)
+
+    @property
+    def ref(self):
+        return C.byref(self.struct)
+
+    def workspace(self, max_active_rows: int) -> torch.Tensor:
+        n = a3_workspace_bytes(self, max_active_rows)
+        return torch.empty(max(n, 256), dtype=torch.uint8, device=self.device)
+
+
+# ---- entry points (same names as the C ABI) -----------------------------------------------------
+
+def a3_version() -> int:
+    return lib().a3_version()
+
+
+def a3_workspace_bytes(layout: Layout, max_active_rows: int) -> int:
+    return int(lib().a3_workspace_bytes(layout.ref, int(max_active_rows)))
+
+
+def a3_layout_prepare(layout: Layout, stream=None) -> None:
+    _check(lib().a3_layout_prepare(layout.ref, _stream(stream)), "a3_layout_prepare")
+
+
+def a3_rope_realign(layout: Layout, k_cat: torch.Tensor, k_fused: torch.Tensor, stream=None) -> None:
+    _check(lib().a3_rope_realign(layout.ref, _ptr(k_cat), _ptr(k_fused), _stream(stream)), "a3_rope_realign")
+
+
+def a3_question_scores(layout: Layout, q_question: torch.Tensor, k_fused: torch.Tensor, scores: torch.Tensor,
+                       ws: torch.Tensor, stream=None) -> None:
+    _check(lib().a3_question_scores(layout.ref, _ptr(q_question), _ptr(k_fused), _ptr(scores), _ptr(ws),
+                                    ws.numel() if ws is not None else 0, _stream(stream)), "a3_question_scores")
+
+
+def a3_topk_select(layout: Layout, scores: torch.Tensor, sel_start: torch.Tensor, total_k: int,
+                   sel_idx: torch.Tensor, ws: Optional[torch.Tensor] = None, stream=None) -> None:
+    _check(lib().a3_topk_select(layout.ref, _ptr(scores), _ptr(sel_start), int(total_k), _ptr(sel_idx), _ptr(ws),
+                                ws.numel() if ws is not None else 0, _stream(stream)), "a3_topk_select")
+
+
+def a3_selected_qkv_proj(layout: Layout, hidden: torch.Tensor, row_idx: Optional[torch.Tensor], n_rows: int,
+                         wq, wk, wv, bq=None, bk=None, bv=None, q_out=None, k_out=None, v_out=None,
+                         stream=None) -> None:
+    _check(lib().a3_selected_qkv_proj(layout.ref, _ptr(hidden), _ptr(row_idx), int(n_rows), _ptr(wq), _ptr(wk),
+                                      _ptr(wv), _ptr(bq), _ptr(bk), _ptr(bv), _ptr(q_out), _ptr(k_out), _ptr(v_out),
+                                      _stream(stream)), "a3_selected_qkv_proj")
+
+
+def a3_kv_scatter(layout: Layout, k_new: torch.Tensor, v_new: torch.Tensor, row_idx: torch.Tensor, n_rows: int,
+                  k_fused: torch.Tensor, v_fused: torch.Tensor, stream=None) -> None:
+    _check(lib().a3_kv_scatter(layout.ref, _ptr(k_new), _ptr(v_new), _ptr(row_idx), int(n_rows), _ptr(k_fused),
+                               _ptr(v_fused), _stream(stream)), "a3_kv_scatter")
+
+
+def a3_fused_attention(layout: Layout, q_act: torch.Tensor, act_idx: torch.Tensor, n_act: int, k_fused: torch.Tensor,
+                       v_fused: torch.Tensor, out: torch.Tensor, ws: torch.Tensor, stream=None) -> None:
+    _check(lib().a3_fused_attention(layout.ref, _ptr(q_act), _ptr(act_idx), int(n_act), _ptr(k_fused), _ptr(v_fused),
+                                    _ptr(out), _ptr(ws), ws.numel() if ws is not None else 0, _stream(stream)),
+           "a3_fused_attention")
+
+
+def a3_active_rows(layout: Layout, sel_idx: Optional[torch.Tensor], sel_start: torch.Tensor, n_act: int,
+                   act_idx: torch.Tensor, stream=None) -> None:
+    _check(lib().a3_active_rows(layout.ref, _ptr(sel_idx), _ptr(sel_start), int(n_act), _ptr(act_idx),
+                                _stream(stream)), "a3_active_rows")

@@ -1,0 +1,72 @@
+// Host-side plumbing of liba3: status strings, per-thread error text, layout validation,
+// workspace sizing.  No kernels here.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "a3_internal.h"
+
+static thread_local char g_last_error[512] = "";
+
+a3_status a3_fail(a3_status code, const char *fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_last_error, sizeof(g_last_error), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+a3_status a3_check_layout(const a3_layout *L, const char *who, bool need_tables) {
+  A3_REQUIRE(L != nullptr, A3_ERR_INVALID_ARG, "%s: layout is NULL", who);
+  A3_REQUIRE(L->dtype == A3_F32 || L->dtype == A3_BF16, A3_ERR_INVALID_ARG, "%s: unknown dtype %d", who, L->dtype);
+  A3_REQUIRE(L->rope_layout == A3_ROPE_INTERLEAVED || L->rope_layout == A3_ROPE_HALF, A3_ERR_INVALID_ARG,
+             "%s: unknown rope_layout %d", who, L->rope_layout);
+  A3_REQUIRE(L->n_q_heads > 0 && L->n_kv_heads > 0 && L->hidden > 0, A3_ERR_INVALID_ARG,
+             "%s: head counts and hidden must be positive", who);
+  A3_REQUIRE(L->n_q_heads % L->n_kv_heads == 0, A3_ERR_INVALID_ARG,
+             "%s: n_q_heads %d is not a multiple of n_kv_heads %d", who, L->n_q_heads, L->n_kv_heads);
+  A3_REQUIRE(L->head_dim == 64 || L->head_dim == 128, A3_ERR_UNSUPPORTED, "%s: head_dim %d (64 or 128 only)", who,
+             L->head_dim);
+  A3_REQUIRE(L->dtype != A3_BF16 || L->head_dim == 128, A3_ERR_UNSUPPORTED,
+             "%s: bf16 kernels need head_dim 128, got %d", who, L->head_dim);
+  A3_REQUIRE(L->hidden % 32 == 0, A3_ERR_UNSUPPORTED, "%s: hidden %d is not a multiple of 32", who, L->hidden);
+  A3_REQUIRE(L->n_q_heads / L->n_kv_heads <= 16, A3_ERR_UNSUPPORTED, "%s: more than 16 query heads per KV head", who);
+  A3_REQUIRE(L->rope_base > 1.0, A3_ERR_INVALID_ARG, "%s: rope_base must be > 1", who);
+  A3_REQUIRE(L->sm_scale >= 0.f, A3_ERR_INVALID_ARG, "%s: sm_scale must be >= 0", who);
+  A3_REQUIRE(L->n_req > 0 && L->n_chunks >= 0 && L->total_tokens > 0, A3_ERR_INVALID_ARG,
+             "%s: n_req/total_tokens must be positive", who);
+  A3_REQUIRE(L->max_ctx_len >= 0 && L->max_q_len >= 0 && L->max_ctx_len + L->max_q_len > 0, A3_ERR_INVALID_ARG,
+             "%s: max_ctx_len/max_q_len invalid", who);
+  A3_REQUIRE((long long)L->max_ctx_len + L->max_q_len <= L->total_tokens, A3_ERR_INVALID_ARG,
+             "%s: max_ctx_len + max_q_len exceeds total_tokens", who);
+  A3_REQUIRE(L->seg_start && L->ctx_len && L->q_len, A3_ERR_INVALID_ARG, "%s: seg_start/ctx_len/q_len is NULL", who);
+  A3_REQUIRE(L->n_chunks == 0 || (L->chunk_start && L->chunk_len && L->chunk_delta), A3_ERR_INVALID_ARG,
+             "%s: chunk arrays are NULL", who);
+  if (need_tables) {
+    A3_REQUIRE(L->tok_pos && L->tok_req && L->tok_chunk && L->q_start && L->rope_pos_cs, A3_ERR_INVALID_ARG,
+               "%s: derived tables are NULL (allocate them and call a3_layout_prepare)", who);
+    A3_REQUIRE(L->n_chunks == 0 || L->rope_chunk_cs, A3_ERR_INVALID_ARG, "%s: rope_chunk_cs is NULL", who);
+  }
+  return A3_OK;
+}
+
+extern "C" const char *a3_strerror(a3_status s) {
+  switch (s) {
+    case A3_OK: return "ok";
+    case A3_ERR_INVALID_ARG: return "invalid argument";
+    case A3_ERR_UNSUPPORTED: return "unsupported shape or type";
+    case A3_ERR_WORKSPACE: return "workspace too small";
+    case A3_ERR_HIP: return "HIP launch failed";
+  }
+  return "unknown status";
+}
+
+extern "C" const char *a3_last_error(void) { return g_last_error; }
+extern "C" int a3_version(void) { return A3_VERSION; }
+
+extern "C" size_t a3_workspace_bytes(const a3_layout *L, int max_active_rows) {
+  if (a3_check_layout(L, "a3_workspace_bytes", false) != A3_OK || max_active_rows < 0) return 0;
+  size_t a = a3_scores_ws_bytes(L);
+  size_t b = a3_attn_ws_bytes(L, max_active_rows);
+  return (a > b ? a : b) + 256;
+}

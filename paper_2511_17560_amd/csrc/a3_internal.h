@@ -1,0 +1,70 @@
+// Internal helpers shared by the HIP translation units of liba3 (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "a3.h"
+
+#define A3_VERSION 100
+
+// ---- error reporting -------------------------------------------------------------------
+a3_status a3_fail(a3_status code, const char *fmt, ...);
+a3_status a3_check_layout(const a3_layout *L, const char *who, bool need_tables);
+
+#define A3_REQUIRE(cond, code, ...)                 \
+  do {                                              \
+    if (!(cond)) return a3_fail(code, __VA_ARGS__); \
+  } while (0)
+
+#define A3_CHECK_LAUNCH(who)                                                              \
+  do {                                                                                    \
+    hipError_t e_ = hipGetLastError();                                                    \
+    if (e_ != hipSuccess) return a3_fail(A3_ERR_HIP, "%s: %s", who, hipGetErrorString(e_)); \
+  } while (0)
+
+static inline bool a3_aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+static inline float a3_scale_of(const a3_layout *L) {
+  return L->sm_scale != 0.f ? L->sm_scale : 1.0f / sqrtf((float)L->head_dim);
+}
+static inline size_t a3_align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// ---- device-side numeric helpers ----------------------------------------------------------
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ float a3_bf2f(bf16_t x) { return (float)x; }
+__device__ __forceinline__ bf16_t a3_f2bf(float x) { return (bf16_t)x; }   // round-to-nearest-even
+
+template <typename T> struct a3_elem;
+template <> struct a3_elem<float> {
+  static constexpr int kVec = 4;   // elements per 16-byte vector
+  __device__ static __forceinline__ float load(const float *p) { return *p; }
+  __device__ static __forceinline__ void store(float *p, float v) { *p = v; }
+};
+template <> struct a3_elem<bf16_t> {
+  static constexpr int kVec = 8;
+  __device__ static __forceinline__ float load(const bf16_t *p) { return (float)*p; }
+  __device__ static __forceinline__ void store(bf16_t *p, float v) { *p = (bf16_t)v; }
+};
+
+// ---- workspace carving (host) ---------------------------------------------------------------
+struct a3_ws_cursor {
+  char *base;
+  size_t off, cap;
+  a3_ws_cursor(void *p, size_t n) : base((char *)p), off(0), cap(n) {}
+  void *take(size_t bytes) {
+    off = a3_align_up(off, 256);
+    void *r = base ? base + off : nullptr;
+    off += bytes;
+    return r;
+  }
+  bool fits() const { return off <= cap; }
+};
+
+// ---- per-step launchers (one per translation unit) ---------------------------------------------
+size_t a3_scores_ws_bytes(const a3_layout *L);
+size_t a3_attn_ws_bytes(const a3_layout *L, int max_active_rows);

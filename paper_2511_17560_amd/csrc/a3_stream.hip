@@ -1,0 +1,288 @@
+// Bandwidth-bound steps of the A^3 fusion path: layout tables, position recovery (Eq. 2)
+// and the cache update (Eq. 5, middle lines).  Plain coalesced 16-byte streaming; one
+// vector per lane, several vectors in flight per lane.
+#include "a3_internal.h"
+
+namespace {
+
+constexpr int kBlock = 256;
+
+// ---------------------------------------------------------------------------------------
+// layout tables
+// ---------------------------------------------------------------------------------------
+
+// largest i in [0, n) with a[i] <= x, or -1
+__device__ __forceinline__ int upper_index(const int *__restrict__ a, int n, int x) {
+  int lo = 0, hi = n;   // invariant: a[lo-1] <= x < a[hi]
+  while (lo < hi) {
+    int mid = (lo + hi) >> 1;
+    if (a[mid] <= x) lo = mid + 1; else hi = mid;
+  }
+  return lo - 1;
+}
+
+__global__ void __launch_bounds__(kBlock)
+prepare_tokens_kernel(const int *__restrict__ seg_start, int n_req, const int *__restrict__ chunk_start,
+                      const int *__restrict__ chunk_len, int n_chunks, int T, int *__restrict__ tok_pos,
+                      int *__restrict__ tok_req, int *__restrict__ tok_chunk, const int *__restrict__ q_len,
+                      int *__restrict__ q_start) {
+  int t = blockIdx.x * kBlock + threadIdx.x;
+  if (t == 0) {                          // n_req is small: a serial prefix sum is enough
+    int run = 0;
+    for (int r = 0; r < n_req; ++r) { q_start[r] = run; run += q_len[r]; }
+    q_start[n_req] = run;
+  }
+  if (t >= T) return;
+  int r = upper_index(seg_start, n_req, t);
+  if (r < 0) r = 0;
+  tok_req[t] = r;
+  tok_pos[t] = t - seg_start[r];
+  int c = n_chunks > 0 ? upper_index(chunk_start, n_chunks, t) : -1;
+  if (c >= 0 && t >= chunk_start[c] + chunk_len[c]) c = -1;
+  tok_chunk[t] = c;
+}
+
+// (cos, sin) of m * theta_i with theta_i = base^(-2i/d); angle formed and evaluated in double.
+__global__ void __launch_bounds__(kBlock)
+prepare_rope_kernel(const int *__restrict__ chunk_delta, int n_chunks, int n_pos, int half, double base,
+                    float2 *__restrict__ chunk_cs, float2 *__restrict__ pos_cs) {
+  long long gid = (long long)blockIdx.x * kBlock + threadIdx.x;
+  long long total = (long long)(n_chunks + n_pos) * half;
+  if (gid >= total) return;
+  int row = (int)(gid / half), i = (int)(gid % half);
+  double m = row < n_chunks ? (double)chunk_delta[row] : (double)(row - n_chunks);
+  double theta = pow(base, -(double)i / (double)half);      // -2i/d with d = 2*half
+  double s, c;
+  sincos(m * theta, &s, &c);
+  float2 v = make_float2((float)c, (float)s);
+  if (row < n_chunks) chunk_cs[(size_t)row * half + i] = v;
+  else pos_cs[(size_t)(row - n_chunks) * half + i] = v;
+}
+
+// ---------------------------------------------------------------------------------------
+// step 1: position recovery
+// ---------------------------------------------------------------------------------------
+
+template <typename T> struct vec16 { uint4 raw; };
+
+template <typename T, int N>
+__device__ __forceinline__ void unpack(const uint4 &raw, float (&f)[N]) {
+  const T *p = reinterpret_cast<const T *>(&raw);
+#pragma unroll
+  for (int i = 0; i < N; ++i) f[i] = a3_elem<T>::load(p + i);
+}
+template <typename T, int N>
+__device__ __forceinline__ uint4 pack(const float (&f)[N]) {
+  uint4 raw;
+  T *p = reinterpret_cast<T *>(&raw);
+#pragma unroll
+  for (int i = 0; i < N; ++i) a3_elem<T>::store(p + i, f[i]);
+  return raw;
+}
+
+// One work item rotates VEC/2 pairs (interleaved: one 16-byte vector; half layout: one vector
+// from each half of the head).  items_per_row = work items per token over all KV heads.
+template <typename T, int LAYOUT, int UNROLL>
+__global__ void __launch_bounds__(kBlock)
+rope_realign_kernel(const T *k_cat, T *k_fused,   /* may alias: each item reads its own elements first */
+                    const int *__restrict__ tok_chunk,
+                    const float2 *__restrict__ chunk_cs, int T_rows, int head_dim, int row_elems,
+                    int items_per_row) {
+  constexpr int VEC = a3_elem<T>::kVec;
+  const int half = head_dim >> 1;
+  const long long total = (long long)T_rows * items_per_row;
+  const long long base = ((long long)blockIdx.x * UNROLL) * kBlock + threadIdx.x;
+
+  uint4 va[UNROLL], vb[UNROLL];
+  int chunk[UNROLL];
+  size_t offa[UNROLL], offb[UNROLL];
+  int pair0[UNROLL];
+#pragma unroll
+  for (int u = 0; u < UNROLL; ++u) {
+    long long gid = base + (long long)u * kBlock;
+    chunk[u] = -1;
+    if (gid < total) {
+      int t = (int)(gid / items_per_row), j = (int)(gid % items_per_row);
+      chunk[u] = tok_chunk[t];
+      if (LAYOUT == A3_ROPE_INTERLEAVED) {
+        int e = j * VEC;                       // element inside the row
+        offa[u] = (size_t)t * row_elems + e;
+        pair0[u] = (e % head_dim) >> 1;
+        if (chunk[u] >= 0) va[u] = *reinterpret_cast<const uint4 *>(k_cat + offa[u]);
+      } else {
+        int per_head = half / VEC;             // work items per head
+        int h = j / per_head, e = (j % per_head) * VEC;
+        offa[u] = (size_t)t * row_elems + (size_t)h * head_dim + e;
+        offb[u] = offa[u] + half;
+        pair0[u] = e;
+        if (chunk[u] >= 0) {
+          va[u] = *reinterpret_cast<const uint4 *>(k_cat + offa[u]);
+          vb[u] = *reinterpret_cast<const uint4 *>(k_cat + offb[u]);
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < UNROLL; ++u) {
+    if (chunk[u] < 0) continue;
+    const float2 *cs = chunk_cs + (size_t)chunk[u] * half + pair0[u];
+    if (LAYOUT == A3_ROPE_INTERLEAVED) {
+      float x[VEC], y[VEC];
+      unpack<T, VEC>(va[u], x);
+#pragma unroll
+      for (int p = 0; p < VEC / 2; ++p) {
+        float2 c = cs[p];
+        y[2 * p] = x[2 * p] * c.x - x[2 * p + 1] * c.y;
+        y[2 * p + 1] = x[2 * p] * c.y + x[2 * p + 1] * c.x;
+      }
+      *reinterpret_cast<uint4 *>(k_fused + offa[u]) = pack<T, VEC>(y);
+    } else {
+      float xa[VEC], xb[VEC], ya[VEC], yb[VEC];
+      unpack<T, VEC>(va[u], xa);
+      unpack<T, VEC>(vb[u], xb);
+#pragma unroll
+      for (int p = 0; p < VEC; ++p) {
+        float2 c = cs[p];
+        ya[p] = xa[p] * c.x - xb[p] * c.y;
+        yb[p] = xa[p] * c.y + xb[p] * c.x;
+      }
+      *reinterpret_cast<uint4 *>(k_fused + offa[u]) = pack<T, VEC>(ya);
+      *reinterpret_cast<uint4 *>(k_fused + offb[u]) = pack<T, VEC>(yb);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// step 5: cache update
+// ---------------------------------------------------------------------------------------
+
+template <int UNROLL>
+__global__ void __launch_bounds__(kBlock)
+kv_scatter_kernel(const uint4 *__restrict__ k_new, const uint4 *__restrict__ v_new, const int *__restrict__ row_idx,
+                  int n_rows, int vec_per_row, uint4 *__restrict__ k_fused, uint4 *__restrict__ v_fused) {
+  const uint4 *src = blockIdx.y == 0 ? k_new : v_new;
+  uint4 *dst = blockIdx.y == 0 ? k_fused : v_fused;
+  const long long total = (long long)n_rows * vec_per_row;
+  const long long base = ((long long)blockIdx.x * UNROLL) * kBlock + threadIdx.x;
+  uint4 v[UNROLL];
+  long long dsto[UNROLL];
+#pragma unroll
+  for (int u = 0; u < UNROLL; ++u) {
+    long long gid = base + (long long)u * kBlock;
+    dsto[u] = -1;
+    if (gid < total) {
+      int i = (int)(gid / vec_per_row), j = (int)(gid % vec_per_row);
+      v[u] = src[gid];
+      dsto[u] = (long long)row_idx[i] * vec_per_row + j;
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < UNROLL; ++u)
+    if (dsto[u] >= 0) dst[dsto[u]] = v[u];
+}
+
+// ---------------------------------------------------------------------------------------
+// active rows = selected rows then question rows, per request
+// ---------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(kBlock)
+active_rows_kernel(const int *__restrict__ sel_idx, const int *__restrict__ sel_start,
+                   const int *__restrict__ q_start, const int *__restrict__ seg_start,
+                   const int *__restrict__ ctx_len, int n_req, int n_act, int *__restrict__ act_idx) {
+  int i = blockIdx.x * kBlock + threadIdx.x;
+  if (i >= n_act) return;
+  // largest r with sel_start[r] + q_start[r] <= i
+  int lo = 0, hi = n_req;
+  while (lo < hi) {
+    int mid = (lo + hi) >> 1;
+    if (sel_start[mid] + q_start[mid] <= i) lo = mid + 1; else hi = mid;
+  }
+  int r = lo - 1;
+  if (r < 0) r = 0;
+  int j = i - (sel_start[r] + q_start[r]);
+  int k = sel_start[r + 1] - sel_start[r];
+  act_idx[i] = j < k ? sel_idx[sel_start[r] + j] : seg_start[r] + ctx_len[r] + (j - k);
+}
+
+template <typename T>
+a3_status launch_realign(const a3_layout *L, const void *k_cat, void *k_fused, hipStream_t st) {
+  constexpr int VEC = a3_elem<T>::kVec;
+  constexpr int UNROLL = 4;
+  const int row_elems = L->n_kv_heads * L->head_dim;
+  const bool inter = L->rope_layout == A3_ROPE_INTERLEAVED;
+  const int items_per_row = inter ? row_elems / VEC : row_elems / (2 * VEC);
+  const long long total = (long long)L->total_tokens * items_per_row;
+  const unsigned grid = (unsigned)((total + (long long)kBlock * UNROLL - 1) / ((long long)kBlock * UNROLL));
+  auto fn = inter ? rope_realign_kernel<T, A3_ROPE_INTERLEAVED, UNROLL> : rope_realign_kernel<T, A3_ROPE_HALF, UNROLL>;
+  hipLaunchKernelGGL(fn, dim3(grid), dim3(kBlock), 0, st, (const T *)k_cat, (T *)k_fused, L->tok_chunk,
+                     (const float2 *)L->rope_chunk_cs, L->total_tokens, L->head_dim, row_elems, items_per_row);
+  A3_CHECK_LAUNCH("a3_rope_realign");
+  return A3_OK;
+}
+
+}  // namespace
+
+extern "C" a3_status a3_layout_prepare(const a3_layout *L, void *stream) {
+  a3_status s = a3_check_layout(L, "a3_layout_prepare", true);
+  if (s != A3_OK) return s;
+  hipStream_t st = (hipStream_t)stream;
+  const int T = L->total_tokens;
+  hipLaunchKernelGGL(prepare_tokens_kernel, dim3((T + kBlock - 1) / kBlock), dim3(kBlock), 0, st, L->seg_start,
+                     L->n_req, L->chunk_start, L->chunk_len, L->n_chunks, T, L->tok_pos, L->tok_req, L->tok_chunk,
+                     L->q_len, L->q_start);
+  A3_CHECK_LAUNCH("a3_layout_prepare(tokens)");
+  const int half = L->head_dim / 2;
+  const int n_pos = L->max_ctx_len + L->max_q_len;
+  const long long total = (long long)(L->n_chunks + n_pos) * half;
+  hipLaunchKernelGGL(prepare_rope_kernel, dim3((unsigned)((total + kBlock - 1) / kBlock)), dim3(kBlock), 0, st,
+                     L->chunk_delta, L->n_chunks, n_pos, half, L->rope_base, (float2 *)L->rope_chunk_cs,
+                     (float2 *)L->rope_pos_cs);
+  A3_CHECK_LAUNCH("a3_layout_prepare(rope)");
+  return A3_OK;
+}
+
+extern "C" a3_status a3_rope_realign(const a3_layout *L, const void *k_cat, void *k_fused, void *stream) {
+  a3_status s = a3_check_layout(L, "a3_rope_realign", true);
+  if (s != A3_OK) return s;
+  A3_REQUIRE(k_cat && k_fused, A3_ERR_INVALID_ARG, "a3_rope_realign: k_cat/k_fused is NULL");
+  A3_REQUIRE(a3_aligned16(k_cat) && a3_aligned16(k_fused), A3_ERR_INVALID_ARG,
+             "a3_rope_realign: tensors must be 16-byte aligned");
+  if (L->n_chunks == 0) return A3_OK;
+  hipStream_t st = (hipStream_t)stream;
+  return L->dtype == A3_BF16 ? launch_realign<bf16_t>(L, k_cat, k_fused, st) : launch_realign<float>(L, k_cat, k_fused, st);
+}
+
+extern "C" a3_status a3_kv_scatter(const a3_layout *L, const void *k_new, const void *v_new, const int *row_idx,
+                                   int n_rows, void *k_fused, void *v_fused, void *stream) {
+  a3_status s = a3_check_layout(L, "a3_kv_scatter", false);
+  if (s != A3_OK) return s;
+  A3_REQUIRE(n_rows >= 0 && n_rows <= L->total_tokens, A3_ERR_INVALID_ARG,
+             "a3_kv_scatter: n_rows %d outside [0, %d]", n_rows, L->total_tokens);
+  if (n_rows == 0) return A3_OK;
+  A3_REQUIRE(k_new && v_new && row_idx && k_fused && v_fused, A3_ERR_INVALID_ARG, "a3_kv_scatter: NULL argument");
+  A3_REQUIRE(a3_aligned16(k_new) && a3_aligned16(v_new) && a3_aligned16(k_fused) && a3_aligned16(v_fused),
+             A3_ERR_INVALID_ARG, "a3_kv_scatter: tensors must be 16-byte aligned");
+  constexpr int UNROLL = 4;
+  const int esz = L->dtype == A3_BF16 ? 2 : 4;
+  const int vec_per_row = L->n_kv_heads * L->head_dim * esz / 16;
+  const long long total = (long long)n_rows * vec_per_row;
+  const unsigned grid = (unsigned)((total + (long long)kBlock * UNROLL - 1) / ((long long)kBlock * UNROLL));
+  hipLaunchKernelGGL(kv_scatter_kernel<UNROLL>, dim3(grid, 2), dim3(kBlock), 0, (hipStream_t)stream,
+                     (const uint4 *)k_new, (const uint4 *)v_new, row_idx, n_rows, vec_per_row, (uint4 *)k_fused,
+                     (uint4 *)v_fused);
+  A3_CHECK_LAUNCH("a3_kv_scatter");
+  return A3_OK;
+}
+
+extern "C" a3_status a3_active_rows(const a3_layout *L, const int *sel_idx, const int *sel_start, int n_act,
+                                    int *act_idx, void *stream) {
+  a3_status s = a3_check_layout(L, "a3_active_rows", true);
+  if (s != A3_OK) return s;
+  A3_REQUIRE(n_act >= 0 && n_act <= L->total_tokens, A3_ERR_INVALID_ARG, "a3_active_rows: n_act %d outside [0, %d]",
+             n_act, L->total_tokens);
+  if (n_act == 0) return A3_OK;
+  A3_REQUIRE(sel_start && act_idx, A3_ERR_INVALID_ARG, "a3_active_rows: NULL argument");
+  hipLaunchKernelGGL(active_rows_kernel, dim3((n_act + kBlock - 1) / kBlock), dim3(kBlock), 0, (hipStream_t)stream,
+                     sel_idx, sel_start, L->q_start, L->seg_start, L->ctx_len, L->n_req, n_act, act_idx);
+  A3_CHECK_LAUNCH("a3_active_rows");
+  return A3_OK;
+}

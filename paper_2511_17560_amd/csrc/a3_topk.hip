@@ -1,0 +1,128 @@
+// Step 3 of the A^3 fusion path: Re = top_p(s) (Eq. 3, second line).
+//
+// One workgroup of 16 wavefronts per request.  The k-th largest score is found exactly by a
+// 4 x 8-bit radix select on an order-preserving integer image of the float, then the rows are
+// compacted in index order with two workgroup-wide prefix sums.  Compacting in index order
+// gives both rules of the selection for free: among equal scores the lowest rows are taken,
+// and the output is ascending.  Integer work only: the result is unique and bit-exact.
+#include "a3_internal.h"
+
+namespace {
+
+constexpr int kBlock = 1024;
+constexpr int kWaves = kBlock / 64;
+
+// Monotone map float -> uint32 (larger float <=> larger key); -0 is folded onto +0.
+__device__ __forceinline__ uint32_t score_key(float s) {
+  uint32_t b = __float_as_uint(s);
+  if (b == 0x80000000u) b = 0u;
+  return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+// Exclusive prefix sum of one int per thread over the workgroup (threads in tid order).
+__device__ __forceinline__ int block_exclusive_scan(int v, int *wave_tot /* [kWaves] LDS */) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int inc = v;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    int x = __shfl_up(inc, off, 64);
+    if (lane >= off) inc += x;
+  }
+  __syncthreads();                       // wave_tot may still be read by a previous scan
+  if (lane == 63) wave_tot[wave] = inc;
+  __syncthreads();
+  int before = 0;
+  for (int w = 0; w < wave; ++w) before += wave_tot[w];
+  return before + inc - v;
+}
+
+__global__ void __launch_bounds__(kBlock)
+topk_select_kernel(const float *__restrict__ scores, const int *__restrict__ seg_start,
+                   const int *__restrict__ ctx_len, const int *__restrict__ sel_start, int *__restrict__ sel_idx) {
+  __shared__ uint32_t hist[256];
+  __shared__ int wave_tot[kWaves];
+  __shared__ uint32_t sh_bin, sh_need;
+
+  const int r = blockIdx.x, tid = threadIdx.x;
+  const int s = seg_start[r];
+  const int N = ctx_len[r];
+  int k = sel_start[r + 1] - sel_start[r];
+  if (k > N) k = N;
+  if (k <= 0) return;                    // uniform over the workgroup
+  int *__restrict__ out = sel_idx + sel_start[r];
+  const float *__restrict__ sc = scores + s;
+
+  // ---- radix select: key of the k-th largest score -------------------------------------
+  uint32_t prefix = 0, mask = 0, need = (uint32_t)k;
+  for (int shift = 24; shift >= 0; shift -= 8) {
+    if (tid < 256) hist[tid] = 0;
+    __syncthreads();
+    for (int i = tid; i < N; i += kBlock) {
+      uint32_t u = score_key(sc[i]);
+      if ((u & mask) == prefix) atomicAdd(&hist[(u >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    if (tid < 64) {
+      // lane owns bins 4*lane .. 4*lane+3; suffix sums run from the highest bin downwards
+      uint32_t c[4], t = 0;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) { c[j] = hist[4 * tid + j]; t += c[j]; }
+      uint32_t suf = t;                  // sum over lanes >= this one
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        uint32_t x = __shfl_down(suf, off, 64);
+        if (tid + off < 64) suf += x;
+      }
+      uint32_t above = suf - t;          // elements in bins of higher lanes
+#pragma unroll
+      for (int j = 3; j >= 0; --j) {
+        if (above < need && above + c[j] >= need) { sh_bin = 4 * tid + j; sh_need = need - above; }
+        above += c[j];
+      }
+    }
+    __syncthreads();
+    prefix |= sh_bin << shift;
+    mask |= 255u << shift;
+    need = sh_need;
+    __syncthreads();
+  }
+  const uint32_t tau = prefix;           // key of the k-th largest; `need` rows equal to it are taken
+
+  // ---- ordered compaction: thread tid owns rows [lo, hi) ----------------------------------
+  const int per = (N + kBlock - 1) / kBlock;
+  const int lo = min(N, tid * per), hi = min(N, lo + per);
+  int cnt_gt = 0, cnt_eq = 0;
+  for (int i = lo; i < hi; ++i) {
+    uint32_t u = score_key(sc[i]);
+    cnt_gt += u > tau;
+    cnt_eq += u == tau;
+  }
+  const int eq_before = block_exclusive_scan(cnt_eq, wave_tot);
+  int take_eq = (int)need - eq_before;
+  take_eq = take_eq < 0 ? 0 : (take_eq > cnt_eq ? cnt_eq : take_eq);
+  int pos = block_exclusive_scan(cnt_gt + take_eq, wave_tot);
+  for (int i = lo; i < hi; ++i) {
+    uint32_t u = score_key(sc[i]);
+    if (u > tau) out[pos++] = s + i;
+    else if (u == tau && take_eq > 0) { out[pos++] = s + i; --take_eq; }
+  }
+}
+
+}  // namespace
+
+extern "C" a3_status a3_topk_select(const a3_layout *L, const float *scores, const int *sel_start, int total_k,
+                                    int *sel_idx, void *ws, size_t ws_bytes, void *stream) {
+  (void)ws; (void)ws_bytes;              // the select keeps everything in LDS
+  a3_status s = a3_check_layout(L, "a3_topk_select", false);
+  if (s != A3_OK) return s;
+  A3_REQUIRE(total_k >= 0, A3_ERR_INVALID_ARG, "a3_topk_select: total_k %d is negative", total_k);
+  A3_REQUIRE((long long)total_k <= (long long)L->max_ctx_len * L->n_req, A3_ERR_INVALID_ARG,
+             "a3_topk_select: total_k %d exceeds the number of context rows", total_k);
+  A3_REQUIRE(scores && sel_start, A3_ERR_INVALID_ARG, "a3_topk_select: scores/sel_start is NULL");
+  if (total_k == 0) return A3_OK;
+  A3_REQUIRE(sel_idx, A3_ERR_INVALID_ARG, "a3_topk_select: sel_idx is NULL");
+  hipLaunchKernelGGL(topk_select_kernel, dim3(L->n_req), dim3(kBlock), 0, (hipStream_t)stream, scores, L->seg_start,
+                     L->ctx_len, sel_start, sel_idx);
+  A3_CHECK_LAUNCH("a3_topk_select");
+  return A3_OK;
+}

@@ -1,0 +1,91 @@
+"""One pass of the whole per-layer fusion path: the sequence of C-ABI calls of one layer, on
+preallocated buffers.  Call sequencing only; all arithmetic happens inside liba3.
+
+    project question rows -> realign keys (Eq. 2) -> scores (Eq. 3) -> top-p (Eq. 3)
+    -> project selected rows (Eq. 5) -> update cache (Eq. 5) -> attention (Eq. 4 / Eq. 5)
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+
+import numpy as np
+import torch
+
+from . import api
+
+
+@dataclass
+class LayerBuffers:
+    """Everything a layer pass writes, allocated once per batch shape."""
+    k_fused: torch.Tensor      # [T, Hkv, d]   realigned + updated keys
+    scores: torch.Tensor       # [T] float32
+    sel_start: torch.Tensor    # [R+1] int32 (device)
+    sel_idx: torch.Tensor      # [total_k] int32 (single request: a view of act_idx)
+    act_idx: torch.Tensor      # [n_act] int32
+    q_rows: torch.Tensor       # [sum q_len] int32, packed rows of the question tokens
+    q_question: torch.Tensor   # [sum q_len, Hq, d]  (single request: a view of q_act)
+    q_act: torch.Tensor        # [n_act, Hq, d]
+    k_act: torch.Tensor        # [n_act, Hkv, d]
+    v_act: torch.Tensor        # [n_act, Hkv, d]
+    out: torch.Tensor          # [n_act, Hq, d]
+    ws: torch.Tensor
+    total_k: int
+    n_act: int
+    single: bool
+
+
+def make_buffers(layout: api.Layout, sel_start: np.ndarray, q_rows: np.ndarray, shape) -> LayerBuffers:
+    dev = layout.device
+    dt = api.torch_dtype(layout.dtype)
+    T = layout.total_tokens
+    Hq, Hkv, d = shape.n_q_heads, shape.n_kv_heads, shape.head_dim
+    total_k = int(sel_start[-1])
+    nq = int(len(q_rows))
+    n_act = total_k + nq
+    single = layout.n_req == 1
+    act_idx = torch.zeros(max(n_act, 1), dtype=torch.int32, device=dev)
+    q_rows_d = torch.as_tensor(np.ascontiguousarray(q_rows, dtype=np.int32), device=dev)
+    q_act = torch.empty((max(n_act, 1), Hq, d), dtype=dt, device=dev)
+    if single:
+        # active order of a single request is [selected | question]: the question part of every
+        # active-row buffer can be written by the first projection and never moves
+        act_idx[total_k:n_act] = q_rows_d
+        sel_idx = act_idx[:total_k]
+        q_question = q_act[total_k:n_act]
+    else:
+        sel_idx = torch.zeros(max(total_k, 1), dtype=torch.int32, device=dev)
+        q_question = torch.empty((max(nq, 1), Hq, d), dtype=dt, device=dev)
+    return LayerBuffers(
+        k_fused=torch.empty((T, Hkv, d), dtype=dt, device=dev),
+        scores=torch.empty(T, dtype=torch.float32, device=dev),
+        sel_start=torch.as_tensor(np.ascontiguousarray(sel_start, dtype=np.int32), device=dev),
+        sel_idx=sel_idx, act_idx=act_idx, q_rows=q_rows_d, q_question=q_question, q_act=q_act,
+        k_act=torch.empty((max(n_act, 1), Hkv, d), dtype=dt, device=dev),
+        v_act=torch.empty((max(n_act, 1), Hkv, d), dtype=dt, device=dev),
+        out=torch.empty((max(n_act, 1), Hq, d), dtype=dt, device=dev),
+        ws=layout.workspace(n_act), total_k=total_k, n_act=n_act, single=single)
+
+
+def fuse_layer(layout: api.Layout, b: LayerBuffers, x_cur: torch.Tensor, k_cat: torch.Tensor, v_cache: torch.Tensor,
+               wq: torch.Tensor, wk: torch.Tensor, wv: torch.Tensor, stream=None) -> None:
+    """Runs steps 1-5 for one layer.  ``k_cat`` is read, ``b.k_fused`` and ``v_cache`` (in place)
+    hold the fused cache afterwards, ``b.out`` the attention output of the active rows."""
+    nq = b.n_act - b.total_k
+    k = b.total_k
+    if b.single:
+        api.a3_selected_qkv_proj(layout, x_cur, b.q_rows, nq, wq, wk, wv, q_out=b.q_act[k:], k_out=b.k_act[k:],
+                                 v_out=b.v_act[k:], stream=stream)
+    else:
+        api.a3_selected_qkv_proj(layout, x_cur, b.q_rows, nq, wq, None, None, q_out=b.q_question, stream=stream)
+    api.a3_rope_realign(layout, k_cat, b.k_fused, stream=stream)
+    api.a3_question_scores(layout, b.q_question, b.k_fused, b.scores, b.ws, stream=stream)
+    api.a3_topk_select(layout, b.scores, b.sel_start, k, b.sel_idx, stream=stream)
+    if b.single:
+        api.a3_selected_qkv_proj(layout, x_cur, b.sel_idx, k, wq, wk, wv, q_out=b.q_act, k_out=b.k_act,
+                                 v_out=b.v_act, stream=stream)
+    else:
+        api.a3_active_rows(layout, b.sel_idx, b.sel_start, b.n_act, b.act_idx, stream=stream)
+        api.a3_selected_qkv_proj(layout, x_cur, b.act_idx, b.n_act, wq, wk, wv, q_out=b.q_act, k_out=b.k_act,
+                                 v_out=b.v_act, stream=stream)
+    api.a3_kv_scatter(layout, b.k_act, b.v_act, b.act_idx, b.n_act, b.k_fused, v_cache, stream=stream)
+    api.a3_fused_attention(layout, b.q_act, b.act_idx, b.n_act, b.k_fused, v_cache, b.out, b.ws, stream=stream)

@@ -1,0 +1,25 @@
+"""Helpers shared by the GPU parity tests: host <-> device conversion and error metrics."""
+import numpy as np
+import torch
+
+from paper_2511_17560_amd import api
+
+
+def to_dev(x: np.ndarray, dtype: str) -> torch.Tensor:
+    """Storage-exact float array -> device tensor of the storage type."""
+    t = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32))
+    return t.to(api.torch_dtype(dtype)).cuda().contiguous()
+
+
+def idev(x) -> torch.Tensor:
+    return torch.as_tensor(np.ascontiguousarray(x, dtype=np.int32), device="cuda")
+
+
+def to_host(t: torch.Tensor) -> np.ndarray:
+    return t.detach().to(torch.float64).cpu().numpy()
+
+
+def max_abs_rel(got: np.ndarray, want: np.ndarray) -> float:
+    """max |a - b| / max |b| over the tensor."""
+    denom = float(np.abs(want).max())
+    return float(np.abs(got - want).max()) / (denom if denom > 0 else 1.0)

@@ -1,0 +1,107 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, sizes workspaces, and rejects bad arguments before launching anything."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2511_17560_amd import api
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "a3.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(a3_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = api.lib()
+    names = _declared_symbols()
+    assert len(names) >= 11
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(api.EXPORTS) == names
+    assert L.a3_version() >= 100
+
+
+def _host_layout(**over):
+    s = api.a3_layout()
+    s.dtype, s.n_q_heads, s.n_kv_heads, s.head_dim, s.hidden = api.A3_BF16, 32, 8, 128, 4096
+    s.rope_layout, s.rope_base, s.sm_scale = 0, 5e5, 0.0
+    s.n_req, s.n_chunks, s.total_tokens, s.max_ctx_len, s.max_q_len = 1, 32, 16448, 16384, 64
+    fake = 0x1000     # never dereferenced on the host: argument checks only look at NULL-ness
+    for f in ("seg_start", "ctx_len", "q_len", "chunk_start", "chunk_len", "chunk_delta", "tok_pos", "tok_req",
+              "tok_chunk", "q_start", "rope_chunk_cs", "rope_pos_cs"):
+        setattr(s, f, fake)
+    for k, v in over.items():
+        setattr(s, k, v)
+    return s
+
+
+def test_workspace_bytes_is_host_only_and_monotone():
+    L = api.lib()
+    s = _host_layout()
+    a = L.a3_workspace_bytes(C.byref(s), 1702)
+    b = L.a3_workspace_bytes(C.byref(s), 16448)
+    assert 0 < a <= b
+    assert L.a3_workspace_bytes(C.byref(_host_layout(head_dim=96)), 10) == 0
+    assert L.a3_workspace_bytes(None, 10) == 0
+
+
+@pytest.mark.parametrize("over,status", [
+    (dict(dtype=7), api.A3_ERR_INVALID_ARG),
+    (dict(n_q_heads=30), api.A3_ERR_INVALID_ARG),          # not a multiple of n_kv_heads
+    (dict(head_dim=96), api.A3_ERR_UNSUPPORTED),
+    (dict(hidden=100), api.A3_ERR_UNSUPPORTED),
+    (dict(rope_base=0.5), api.A3_ERR_INVALID_ARG),
+    (dict(seg_start=None), api.A3_ERR_INVALID_ARG),
+    (dict(tok_pos=None), api.A3_ERR_INVALID_ARG),
+    (dict(total_tokens=10), api.A3_ERR_INVALID_ARG),       # max lengths exceed T
+])
+def test_bad_layouts_are_rejected_before_launch(over, status):
+    L = api.lib()
+    s = _host_layout(**over)
+    assert L.a3_rope_realign(C.byref(s), 0x1000, 0x1000, None) == status
+    assert L.a3_last_error() != b""
+    assert L.a3_strerror(status) not in (b"", b"ok")
+
+
+def test_bad_arguments_are_rejected_before_launch():
+    L = api.lib()
+    s = _host_layout()
+    p = C.byref(s)
+    assert L.a3_rope_realign(p, None, 0x1000, None) == api.A3_ERR_INVALID_ARG
+    assert L.a3_rope_realign(p, 0x1004, 0x1000, None) == api.A3_ERR_INVALID_ARG       # misaligned
+    assert L.a3_question_scores(p, 0x1000, 0x1000, 0x1000, None, 0, None) == api.A3_ERR_WORKSPACE
+    assert L.a3_question_scores(p, 0x1000, 0x1000, 0x1000, 0x1000, 16, None) == api.A3_ERR_WORKSPACE
+    assert L.a3_topk_select(p, 0x1000, 0x1000, -1, 0x1000, None, 0, None) == api.A3_ERR_INVALID_ARG
+    assert L.a3_topk_select(p, 0x1000, 0x1000, 10 ** 6, 0x1000, None, 0, None) == api.A3_ERR_INVALID_ARG
+    assert L.a3_topk_select(p, 0x1000, 0x1000, 0, None, None, 0, None) == api.A3_OK     # nothing to do
+    assert L.a3_selected_qkv_proj(p, 0x1000, None, -3, *([0x1000] * 3), *([None] * 3), *([0x1000] * 3), None) \
+        == api.A3_ERR_INVALID_ARG
+    assert L.a3_selected_qkv_proj(p, 0x1000, None, 5, None, None, None, *([None] * 3), 0x1000, None, None, None) \
+        == api.A3_ERR_INVALID_ARG                                                          # output without weight
+    assert L.a3_selected_qkv_proj(p, 0x1000, None, 0, *([0x1000] * 3), *([None] * 3), *([0x1000] * 3), None) == api.A3_OK
+    assert L.a3_kv_scatter(p, 0x1000, 0x1000, None, 4, 0x1000, 0x1000, None) == api.A3_ERR_INVALID_ARG
+    assert L.a3_kv_scatter(p, None, None, None, 0, None, None, None) == api.A3_OK
+    assert L.a3_fused_attention(p, 0x1000, 0x1000, 10, 0x1000, 0x1000, 0x1000, None, 0, None) == api.A3_ERR_WORKSPACE
+    assert L.a3_fused_attention(p, 0x1000, 0x1000, 10 ** 6, 0x1000, 0x1000, 0x1000, None, 0, None) \
+        == api.A3_ERR_INVALID_ARG
+    assert L.a3_fused_attention(p, None, None, 0, None, None, None, None, 0, None) == api.A3_OK
+    assert L.a3_active_rows(p, None, None, 5, None, None) == api.A3_ERR_INVALID_ARG
+    f32_d64 = _host_layout(dtype=api.A3_F32, head_dim=64)
+    assert L.a3_rope_realign(C.byref(f32_d64), None, None, None) == api.A3_ERR_INVALID_ARG
+    bf16_d64 = _host_layout(head_dim=64)
+    assert L.a3_rope_realign(C.byref(bf16_d64), 0x1000, 0x1000, None) == api.A3_ERR_UNSUPPORTED
+
+
+def test_struct_layout_matches_header_order():
+    text = open(os.path.join(ROOT, "include", "a3.h")).read()
+    body = text[text.index("typedef struct a3_layout {"):text.index("} a3_layout;")]
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    fields = re.findall(r"\b\*?\s*([a-z_]+)\s*;", body)
+    assert fields == [f[0] for f in api.a3_layout._fields_]
