@@ -16,56 +16,118 @@
 //                 V is transposed on its way into LDS (4 keys x 8 dims per lane, register transpose)
 //                 with key bits 2 and 3 swapped so that the A operand is a single 16-byte LDS read.
 // fp32 path: one workgroup per (active row, head), plain FMA (correctness configuration).
+#include <stdlib.h>
+#include <string.h>
+
 #include "a3_internal.h"
 
 namespace {
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr int kD = 128;
-constexpr int kTM = 128;            // packed (row, head) pairs per workgroup: 4 waves x 32
+constexpr int kTM = 128;            // packed (row, head) pairs per work item: 4 waves x 32
 constexpr int kTK = 64;             // keys per tile
 constexpr int kKStride = kD + 8;    // K tile  [key][d]   row stride in elements (272 B)
 constexpr int kVStride = kTK + 8;   // V^T tile [d][key]  row stride in elements (144 B)
+constexpr int kKTile = kTK * kKStride;
+constexpr int kVTile = kD * kVStride;
+constexpr size_t kAttnLds = (size_t)2 * (kKTile + kVTile) * sizeof(bf16_t);   // double buffered: 71680 B
+constexpr int kPlanThreads = 1024;
 
+// Work decomposition written by the plan kernel.
+//   tile  = 128 consecutive packed (row, head) pairs of one request and one KV head group
+//   item  = one tile restricted to a key segment [k_begin, k_end); a tile whose last row sees more
+//           than 1.5 segments of keys is cut into equal segments so that no item is much longer
+//           than the per-CU share of the work; partial results of cut tiles are merged afterwards
 struct attn_plan {
-  int *cnt;          // [n_req]   active rows per request
   int *a_lo;         // [n_req+1] first active row of each request
   int *tile_start;   // [n_req+1] first tile of each request
-  int4 *desc;        // [max_tiles] (request, first m of the tile, visible keys of its last row, rows*G of the request)
-  int *n_tiles;      // [1]
+  int4 *tile_a;      // [max_tiles] (request, first m, visible keys of the last row, rows*G of the request)
+  int2 *tile_b;      // [max_tiles] (first item, number of segments)
+  int4 *items;       // [max_items] (tile, k_begin, k_end, segment) - longest tiles first
+  int *counters;     // [Hkv] work queue heads, then n_tiles, n_items
+  float *part_o;     // [Hkv * max_items][128][128] unnormalised partial O of cut tiles
+  float2 *part_ml;   // [Hkv * max_items][128]      (max in the exp2 domain, sum)
+  int max_tiles, max_items, seg_len;
 };
 
-__global__ void __launch_bounds__(1024)
-attn_plan_kernel(attn_plan p, const int *__restrict__ act_idx, int n_act, const int *__restrict__ tok_req,
-                 const int *__restrict__ seg_start, int n_req, int G, int max_tiles) {
-  const int tid = threadIdx.x;
-  for (int r = tid; r < n_req; r += 1024) p.cnt[r] = 0;
-  __syncthreads();
-  for (int a = tid; a < n_act; a += 1024) atomicAdd(&p.cnt[tok_req[act_idx[a]]], 1);
+__device__ __forceinline__ int lower_bound_i32(const int *__restrict__ a, int n, int x) {
+  int lo = 0, hi = n;            // first index with a[i] >= x
+  while (lo < hi) {
+    int mid = (lo + hi) >> 1;
+    if (a[mid] < x) lo = mid + 1; else hi = mid;
+  }
+  return lo;
+}
+
+__global__ void __launch_bounds__(kPlanThreads)
+attn_plan_kernel(attn_plan p, const int *__restrict__ act_idx, int n_act, const int *__restrict__ seg_start,
+                 int n_req, int G, int Hkv) {
+  __shared__ int wave_tot[kPlanThreads / 64];
+  __shared__ int carry;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // active rows are ascending, so the rows of request r are a contiguous range found by bisection
+  for (int r = tid; r <= n_req; r += kPlanThreads)
+    p.a_lo[r] = r == n_req ? n_act : lower_bound_i32(act_idx, n_act, seg_start[r]);
   __syncthreads();
   if (tid == 0) {
-    int a = 0, t = 0;
+    int t = 0;
     for (int r = 0; r < n_req; ++r) {
-      p.a_lo[r] = a;
       p.tile_start[r] = t;
-      a += p.cnt[r];
-      t += (p.cnt[r] * G + kTM - 1) / kTM;
+      t += ((p.a_lo[r + 1] - p.a_lo[r]) * G + kTM - 1) / kTM;
     }
-    p.a_lo[n_req] = a;
     p.tile_start[n_req] = t;
-    *p.n_tiles = t < max_tiles ? t : max_tiles;
+    carry = 0;
   }
   __syncthreads();
-  for (int r = 0; r < n_req; ++r) {
-    const int t0 = p.tile_start[r], nt = p.tile_start[r + 1] - t0;
-    const int a0 = p.a_lo[r], nr = p.cnt[r];
-    for (int j = tid; j < nt; j += 1024) {
-      if (t0 + j >= max_tiles) break;
+  const int n_tiles = min(p.tile_start[n_req], p.max_tiles);
+  // items are numbered with the tiles in reverse order: within a request later tiles see more keys
+  for (int base = 0; base < n_tiles; base += kPlanThreads) {
+    const int i = base + tid;
+    int nseg = 0, t = 0, r = 0, j = 0, kv = 0, part = 0;
+    if (i < n_tiles) {
+      t = n_tiles - 1 - i;
+      // request of tile t: last r with tile_start[r] <= t
+      int lo = 0, hi = n_req;
+      while (lo < hi) { int mid = (lo + hi) >> 1; if (p.tile_start[mid] <= t) lo = mid + 1; else hi = mid; }
+      r = lo - 1;
+      j = t - p.tile_start[r];
+      const int nr = p.a_lo[r + 1] - p.a_lo[r];
       int last = ((j + 1) * kTM - 1) / G;
       if (last > nr - 1) last = nr - 1;
-      int kv = act_idx[a0 + last] - seg_start[r] + 1;
-      p.desc[t0 + j] = make_int4(r, j * kTM, kv, nr * G);
+      kv = act_idx[p.a_lo[r] + last] - seg_start[r] + 1;
+      nseg = 2 * kv <= 3 * p.seg_len ? 1 : (kv + p.seg_len - 1) / p.seg_len;
+      part = (((kv + nseg - 1) / nseg) + kTK - 1) / kTK * kTK;
+      p.tile_a[t] = make_int4(r, j * kTM, kv, nr * G);
     }
+    // workgroup exclusive scan of nseg
+    int inc = nseg;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      int x = __shfl_up(inc, off, 64);
+      if (lane >= off) inc += x;
+    }
+    if (lane == 63) wave_tot[wave] = inc;
+    __syncthreads();
+    int before = carry;
+    for (int w2 = 0; w2 < wave; ++w2) before += wave_tot[w2];
+    const int item0 = before + inc - nseg;
+    if (i < n_tiles) {
+      p.tile_b[t] = make_int2(item0, nseg);
+      for (int sgm = 0; sgm < nseg; ++sgm) {
+        if (item0 + sgm >= p.max_items) break;
+        int kb = min(kv, sgm * part), ke = min(kv, (sgm + 1) * part);
+        p.items[item0 + sgm] = make_int4(t, kb, ke, sgm);
+      }
+    }
+    __syncthreads();
+    if (tid == kPlanThreads - 1) carry = before + inc;
+    __syncthreads();
+  }
+  if (tid == 0) {
+    for (int g = 0; g < Hkv; ++g) p.counters[g] = 0;
+    p.counters[Hkv] = n_tiles;
+    p.counters[Hkv + 1] = min(carry, p.max_items);
   }
 }
 
@@ -80,161 +142,312 @@ struct attn_args {
   float scale2;
 };
 
+// v_exp_f32: 2^x, about 1 ulp, -inf -> 0, results below the normal range flush to 0
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+// Combine a value across the two 32-lane halves of the wave with v_permlane32_swap (no LDS round
+// trip): after the swap one result holds the low-half values in every lane and the other the
+// high-half values, so max / sum of the two results is the combined value in all 64 lanes.
+__device__ __forceinline__ float halves_max(float x) {
+  const uint32_t u = __float_as_uint(x);
+  auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float halves_sum(float x) {
+  const uint32_t u = __float_as_uint(x);
+  auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
 __device__ __forceinline__ uint32_t pack_lo(uint32_t a, uint32_t b) { return (a & 0xffffu) | (b << 16); }
 __device__ __forceinline__ uint32_t pack_hi(uint32_t a, uint32_t b) { return (a >> 16) | (b & 0xffff0000u); }
 
-__global__ void __launch_bounds__(256)
+// Persistent workgroups: each pops items of its KV head from the head's queue until it is empty.
+__global__ void __launch_bounds__(256, 2)
 attn_bf16_kernel(attn_args a) {
-  __shared__ __align__(16) bf16_t Ks[kTK * kKStride];
-  __shared__ __align__(16) bf16_t Vt[kD * kVStride];
+  extern __shared__ __align__(16) unsigned char lds_raw[];
+  bf16_t *Ks = reinterpret_cast<bf16_t *>(lds_raw);          // [2][64][kKStride]
+  bf16_t *Vt = Ks + 2 * kKTile;                              // [2][128][kVStride]
+  __shared__ int sh_item;
 
-  const int n_tiles = *a.plan.n_tiles;
   const int g = blockIdx.x % a.Hkv;
-  const int rank = blockIdx.x / a.Hkv;
-  if (rank >= n_tiles) return;
-  const int4 desc = a.plan.desc[n_tiles - 1 - rank];      // later tiles see more keys: start them first
-  const int r = desc.x, m0 = desc.y, kv_len = desc.z, m_end = desc.w;
+  const int n_items = a.plan.counters[a.Hkv + 1];
   const int G = a.Hq / a.Hkv;
-  const int a0 = a.plan.a_lo[r];
-  const int base = a.seg_start[r];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, lhi = lane >> 5;
-
   const bf16_t *__restrict__ Q = (const bf16_t *)a.q;
   const bf16_t *__restrict__ K = (const bf16_t *)a.k;
   const bf16_t *__restrict__ V = (const bf16_t *)a.v;
+  const float c2 = a.scale2;
 
-  // this lane's query row
-  const int m = m0 + wave * 32 + l32;
-  const bool valid = m < m_end;
-  const int mc = valid ? m : m_end - 1;
-  const int arow = a0 + mc / G, hq = g * G + mc % G;
-  const int limit = a.act_idx[arow] - base;              // last visible key (request-relative)
-
-  bf16x8 qf[kD / 16];
-  {
-    const bf16_t *qp = Q + ((size_t)arow * a.Hq + hq) * kD + lhi * 8;
-#pragma unroll
-    for (int ks = 0; ks < kD / 16; ++ks) qf[ks] = *reinterpret_cast<const bf16x8 *>(qp + ks * 16);
-  }
-
-  f32x16 o[4];
-#pragma unroll
-  for (int b = 0; b < 4; ++b)
-#pragma unroll
-    for (int x = 0; x < 16; ++x) o[b][x] = 0.f;
-  float row_max = -INFINITY, row_sum = 0.f;
-
-  // staging roles: K tile: 16 lanes per 256-byte row; V tile: lane = (4 keys, 8 dims)
-  const int vkg = tid >> 4, vc = tid & 15;                 // keys 4*vkg.., dims 8*vc..
+  // staging roles.  K tile: 16 lanes per 256-byte row, 4 rows per lane.  V tile: lane = (4 keys, 8 dims).
+  const int kc = tid & 15, kr0 = tid >> 4;
+  // 16 consecutive lanes take 16 different key groups: their 8-byte transposed stores land in 128
+  // contiguous bytes of one V^T row (all 32 LDS banks) instead of 16 rows at a bank-aligned stride
+  const int vkg = tid & 15, vc = tid >> 4;
   const int vpos = ((4 * vkg) & ~12) | (((4 * vkg) & 4) << 1) | (((4 * vkg) & 8) >> 1);   // swap key bits 2 and 3
 
-  for (int k0 = 0; k0 < kv_len; k0 += kTK) {
-    __syncthreads();                                       // previous tile consumed
-    for (int i = tid; i < kTK * 16; i += 256) {
-      int kr = i >> 4, c = i & 15;
-      int row = k0 + kr;
-      if (row > kv_len - 1) row = kv_len - 1;              // stay inside the visible range; masked below
-      uint4 v = *reinterpret_cast<const uint4 *>(K + ((size_t)(base + row) * a.Hkv + g) * kD + c * 8);
-      *reinterpret_cast<uint4 *>(Ks + kr * kKStride + c * 8) = v;
-    }
-    {
-      uint4 rows[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        int row = k0 + 4 * vkg + i;
-        if (row > kv_len - 1) row = kv_len - 1;
-        rows[i] = *reinterpret_cast<const uint4 *>(V + ((size_t)(base + row) * a.Hkv + g) * kD + vc * 8);
-      }
-      const uint32_t *r0 = reinterpret_cast<const uint32_t *>(&rows[0]);
-      const uint32_t *r1 = reinterpret_cast<const uint32_t *>(&rows[1]);
-      const uint32_t *r2 = reinterpret_cast<const uint32_t *>(&rows[2]);
-      const uint32_t *r3 = reinterpret_cast<const uint32_t *>(&rows[3]);
-#pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        uint2 even = make_uint2(pack_lo(r0[w], r1[w]), pack_lo(r2[w], r3[w]));   // dim 8vc+2w,   keys 0..3
-        uint2 odd = make_uint2(pack_hi(r0[w], r1[w]), pack_hi(r2[w], r3[w]));    // dim 8vc+2w+1, keys 0..3
-        *reinterpret_cast<uint2 *>(Vt + (8 * vc + 2 * w) * kVStride + vpos) = even;
-        *reinterpret_cast<uint2 *>(Vt + (8 * vc + 2 * w + 1) * kVStride + vpos) = odd;
-      }
-    }
+  for (;;) {
+    if (tid == 0) sh_item = atomicAdd(&a.plan.counters[g], 1);
     __syncthreads();
+    const int item = sh_item;
+    __syncthreads();
+    if (item >= n_items) break;                            // uniform over the workgroup
+    const int4 it = a.plan.items[item];
+    const int4 ta = a.plan.tile_a[it.x];
+    const int nseg = a.plan.tile_b[it.x].y;
+    const int r = ta.x, m0 = ta.y, kv_len = ta.z, m_end = ta.w;
+    const int k_begin = it.y, k_end = it.z;
+    const int a0 = a.plan.a_lo[r];
+    const int base = a.seg_start[r];
 
-    // ---- S^T = K Q^T : two 32-key blocks ------------------------------------------------
-    f32x16 st[2];
+    // this lane's query row
+    const int m = m0 + wave * 32 + l32;
+    const bool valid = m < m_end;
+    const int mc = valid ? m : m_end - 1;
+    const int arow = a0 + mc / G, hq = g * G + mc % G;
+    const int limit = a.act_idx[arow] - base;              // last visible key (request-relative)
+    int wave_min_limit = limit;
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
-#pragma unroll
-      for (int x = 0; x < 16; ++x) st[b][x] = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < kD / 16; ++ks)
-#pragma unroll
-      for (int b = 0; b < 2; ++b) {
-        bf16x8 kf = *reinterpret_cast<const bf16x8 *>(Ks + (b * 32 + l32) * kKStride + ks * 16 + lhi * 8);
-        st[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], st[b], 0, 0, 0);
-      }
+    for (int off = 32; off > 0; off >>= 1) wave_min_limit = min(wave_min_limit, __shfl_xor(wave_min_limit, off, 64));
 
-    // ---- online softmax for this lane's row ------------------------------------------------
-    // accumulator x of block b: key k0 + 32 b + 8 (x/4) + 4 lhi + x%4
-    float mx = -INFINITY;
+    bf16x8 qf[kD / 16];
+    {
+      const bf16_t *qp = Q + ((size_t)arow * a.Hq + hq) * kD + lhi * 8;
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
-#pragma unroll
-      for (int x = 0; x < 16; ++x) {
-        int key = k0 + 32 * b + 8 * (x >> 2) + 4 * lhi + (x & 3);
-        float s = key <= limit ? st[b][x] * a.scale2 : -INFINITY;
-        st[b][x] = s;
-        mx = fmaxf(mx, s);
-      }
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float new_max = fmaxf(row_max, mx);              // finite: key 0 is visible to every row
-    const float alpha = exp2f(row_max - new_max);
-    row_max = new_max;
-    float psum = 0.f;
-#pragma unroll
-    for (int b = 0; b < 2; ++b)
-#pragma unroll
-      for (int x = 0; x < 16; ++x) {
-        float p = exp2f(st[b][x] - new_max);
-        st[b][x] = p;
-        psum += p;
-      }
-    row_sum = row_sum * alpha + psum;                      // per lane half; halves are added at the end
+      for (int ks = 0; ks < kD / 16; ++ks) qf[ks] = *reinterpret_cast<const bf16x8 *>(qp + ks * 16);
+    }
+
+    f32x16 o[4];
 #pragma unroll
     for (int b = 0; b < 4; ++b)
 #pragma unroll
-      for (int x = 0; x < 16; ++x) o[b][x] *= alpha;
+      for (int x = 0; x < 16; ++x) o[b][x] = 0.f;
+    float row_max = -INFINITY, row_sum = 0.f;               // row_max in raw logit units
 
-    // ---- O^T += V^T P^T ------------------------------------------------------------------------
+    // Next tile staged in registers while the current one is being consumed.  Loads are branch
+    // free (rows past the last visible key are clamped onto it and masked later) so that nothing
+    // forces the loaded registers to be touched before the LDS store at the end of the iteration.
+    uint4 kr_0, kr_1, kr_2, kr_3, vr_0, vr_1, vr_2, vr_3;
+    const uint32_t pitch_b = (uint32_t)a.Hkv * kD * sizeof(bf16_t);
+    const char *kb = reinterpret_cast<const char *>(K + ((size_t)base * a.Hkv + g) * kD);
+    const char *vb = reinterpret_cast<const char *>(V + ((size_t)base * a.Hkv + g) * kD);
+    const uint32_t k_last = (uint32_t)(kv_len - 1) * pitch_b + kc * 16, v_last = (uint32_t)(kv_len - 1) * pitch_b + vc * 16;
+    const uint32_t ko_0 = (uint32_t)kr0 * pitch_b + kc * 16, ko_1 = ko_0 + 16 * pitch_b, ko_2 = ko_0 + 32 * pitch_b,
+                   ko_3 = ko_0 + 48 * pitch_b;
+    const uint32_t vo_0 = (uint32_t)(4 * vkg) * pitch_b + vc * 16, vo_1 = vo_0 + pitch_b, vo_2 = vo_0 + 2 * pitch_b,
+                   vo_3 = vo_0 + 3 * pitch_b;
+#define A3_GLOAD(K0)                                                                       \
+    {                                                                                      \
+      const uint32_t t_off = (uint32_t)(K0) * pitch_b;                                     \
+      kr_0 = *reinterpret_cast<const uint4 *>(kb + min(ko_0 + t_off, k_last));             \
+      kr_1 = *reinterpret_cast<const uint4 *>(kb + min(ko_1 + t_off, k_last));             \
+      kr_2 = *reinterpret_cast<const uint4 *>(kb + min(ko_2 + t_off, k_last));             \
+      kr_3 = *reinterpret_cast<const uint4 *>(kb + min(ko_3 + t_off, k_last));             \
+      vr_0 = *reinterpret_cast<const uint4 *>(vb + min(vo_0 + t_off, v_last));             \
+      vr_1 = *reinterpret_cast<const uint4 *>(vb + min(vo_1 + t_off, v_last));             \
+      vr_2 = *reinterpret_cast<const uint4 *>(vb + min(vo_2 + t_off, v_last));             \
+      vr_3 = *reinterpret_cast<const uint4 *>(vb + min(vo_3 + t_off, v_last));             \
+    }
+#define A3_V_TRANSPOSE_STORE(VD, W, C)                                                                       \
+    {                                                                                                        \
+      uint2 even = make_uint2(pack_lo(vr_0.C, vr_1.C), pack_lo(vr_2.C, vr_3.C)); /* dim 8vc+2W,   4 keys */  \
+      uint2 odd = make_uint2(pack_hi(vr_0.C, vr_1.C), pack_hi(vr_2.C, vr_3.C));  /* dim 8vc+2W+1, 4 keys */  \
+      *reinterpret_cast<uint2 *>((VD) + (8 * vc + 2 * W) * kVStride + vpos) = even;                          \
+      *reinterpret_cast<uint2 *>((VD) + (8 * vc + 2 * W + 1) * kVStride + vpos) = odd;                       \
+    }
+#define A3_LSTORE(BUF)                                                                                       \
+    {                                                                                                        \
+      bf16_t *kd = Ks + (BUF) * kKTile + kr0 * kKStride + kc * 8;                                            \
+      bf16_t *vd = Vt + (BUF) * kVTile;                                                                      \
+      *reinterpret_cast<uint4 *>(kd) = kr_0;                                                                 \
+      *reinterpret_cast<uint4 *>(kd + 16 * kKStride) = kr_1;                                                 \
+      *reinterpret_cast<uint4 *>(kd + 32 * kKStride) = kr_2;                                                 \
+      *reinterpret_cast<uint4 *>(kd + 48 * kKStride) = kr_3;                                                 \
+      A3_V_TRANSPOSE_STORE(vd, 0, x)                                                                         \
+      A3_V_TRANSPOSE_STORE(vd, 1, y)                                                                         \
+      A3_V_TRANSPOSE_STORE(vd, 2, z)                                                                         \
+      A3_V_TRANSPOSE_STORE(vd, 3, w)                                                                         \
+    }
+
+    if (k_begin < k_end) {
+      A3_GLOAD(k_begin)
+      A3_LSTORE(0)
+    }
+    __syncthreads();
+    int buf = 0;
+    for (int k0 = k_begin; k0 < k_end; k0 += kTK, buf ^= 1) {
+      A3_GLOAD(k0 + kTK)                                     // next tile: in flight during everything below
+      const bf16_t *kt = Ks + buf * kKTile + l32 * kKStride + lhi * 8;
+      const bf16_t *vt = Vt + buf * kVTile + l32 * kVStride + lhi * 8;
+
+      // ---- S^T = K Q^T : two 32-key blocks, K fragments read two steps ahead ----------------
+      f32x16 st[2];
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
+      for (int b = 0; b < 2; ++b)
 #pragma unroll
-      for (int s2 = 0; s2 < 2; ++s2) {
+        for (int x = 0; x < 16; ++x) st[b][x] = 0.f;
+      bf16x8 kf[3][2];
+#pragma unroll
+      for (int pre = 0; pre < 2; ++pre)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+          kf[pre][b] = *reinterpret_cast<const bf16x8 *>(kt + b * 32 * kKStride + pre * 16);
+#pragma unroll
+      for (int ks = 0; ks < kD / 16; ++ks) {
+        if (ks + 2 < kD / 16) {
+#pragma unroll
+          for (int b = 0; b < 2; ++b)
+            kf[(ks + 2) % 3][b] = *reinterpret_cast<const bf16x8 *>(kt + b * 32 * kKStride + (ks + 2) * 16);
+        }
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+          st[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks % 3][b], qf[ks], st[b], 0, 0, 0);
+      }
+
+      // first V^T fragments: their LDS latency hides behind the softmax arithmetic
+      bf16x8 vf[2][4];
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+        vf[0][db] = *reinterpret_cast<const bf16x8 *>(vt + db * 32 * kVStride);
+
+      // ---- online softmax for this lane's row (accumulator x of block b: key k0 + 32b + 8(x/4) + 4 lhi + x%4)
+      if (k0 + kTK - 1 > wave_min_limit) {                  // tile touches the causal boundary of some row
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+          for (int x = 0; x < 16; ++x) {
+            int key = k0 + 32 * b + 8 * (x >> 2) + 4 * lhi + (x & 3);
+            if (key > limit) st[b][x] = -INFINITY;
+          }
+      }
+      float mx = st[0][0];
+#pragma unroll
+      for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int x = 0; x < 16; ++x) mx = fmaxf(mx, st[b][x]);
+      mx = halves_max(mx);
+      const float new_max = fmaxf(row_max, mx);
+      const float ref = new_max == -INFINITY ? 0.f : new_max;   // row with no visible key in this segment yet
+      const float alpha = fast_exp2((row_max - ref) * c2);
+      const float nref = -ref * c2;
+      row_max = new_max;
+      float psum = 0.f;
+#pragma unroll
+      for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int x = 0; x < 16; ++x) {
+          float pv = fast_exp2(fmaf(st[b][x], c2, nref));
+          st[b][x] = pv;
+          psum += pv;
+        }
+      row_sum = row_sum * alpha + psum;                     // per lane half; halves are added at the end
+      if (!__all(alpha == 1.0f)) {
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+          for (int x = 0; x < 16; ++x) o[b][x] *= alpha;
+      }
+
+      // ---- O^T += V^T P^T, V^T fragments read one step ahead ------------------------------------
+#pragma unroll
+      for (int step = 0; step < 4; ++step) {                // step = 2 b + s2: keys 32 b + 16 s2 ..
+        if (step + 1 < 4) {
+#pragma unroll
+          for (int db = 0; db < 4; ++db)
+            vf[(step + 1) & 1][db] = *reinterpret_cast<const bf16x8 *>(vt + db * 32 * kVStride + (step + 1) * 16);
+        }
         bf16x8 pf;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) pf[e] = a3_f2bf(st[b][8 * s2 + e]);
+        for (int e = 0; e < 8; ++e) pf[e] = a3_f2bf(st[step >> 1][8 * (step & 1) + e]);
 #pragma unroll
-        for (int db = 0; db < 4; ++db) {
-          bf16x8 vf = *reinterpret_cast<const bf16x8 *>(Vt + (db * 32 + l32) * kVStride + 32 * b + 16 * s2 + 8 * lhi);
-          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, o[db], 0, 0, 0);
-        }
+        for (int db = 0; db < 4; ++db)
+          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[step & 1][db], pf, o[db], 0, 0, 0);
       }
-  }
-
-  row_sum += __shfl_xor(row_sum, 32, 64);
-  if (!valid) return;
-  const float inv = 1.0f / row_sum;
-  bf16_t *orow = (bf16_t *)a.out + ((size_t)arow * a.Hq + hq) * kD;
-  // accumulator x of block db: dim 32 db + 8 (x/4) + 4 lhi + x%4
-#pragma unroll
-  for (int db = 0; db < 4; ++db)
-#pragma unroll
-    for (int q4 = 0; q4 < 4; ++q4) {
-      bf16x4 v;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) v[e] = a3_f2bf(o[db][4 * q4 + e] * inv);
-      *reinterpret_cast<bf16x4 *>(orow + 32 * db + 8 * q4 + 4 * lhi) = v;
+      if (k0 + kTK < k_end) { A3_LSTORE(buf ^ 1) }
+      __syncthreads();
     }
+#undef A3_GLOAD
+#undef A3_LSTORE
+#undef A3_V_TRANSPOSE_STORE
+
+    row_sum = halves_sum(row_sum);
+    if (nseg == 1) {
+      if (valid) {
+        const float inv = 1.0f / row_sum;
+        bf16_t *orow = (bf16_t *)a.out + ((size_t)arow * a.Hq + hq) * kD;
+        // accumulator x of block db: dim 32 db + 8 (x/4) + 4 lhi + x%4
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+          for (int q4 = 0; q4 < 4; ++q4) {
+            bf16x4 v;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = a3_f2bf(o[db][4 * q4 + e] * inv);
+            *reinterpret_cast<bf16x4 *>(orow + 32 * db + 8 * q4 + 4 * lhi) = v;
+          }
+      }
+    } else {
+      const size_t pidx = (size_t)g * a.plan.max_items + item;
+      const int ml = wave * 32 + l32;
+      float *po = a.plan.part_o + (pidx * kTM + ml) * kD;
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          f32x4 v;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = o[db][4 * q4 + e];
+          *reinterpret_cast<f32x4 *>(po + 32 * db + 8 * q4 + 4 * lhi) = v;
+        }
+      if (lhi == 0) a.plan.part_ml[pidx * kTM + ml] = make_float2(row_max * c2, row_sum);
+    }
+  }
+}
+
+// Merges the partial results of tiles that were cut into key segments, in segment order.
+__global__ void __launch_bounds__(256)
+attn_combine_kernel(attn_args a) {
+  const int t = blockIdx.x, g = blockIdx.y;
+  if (t >= a.plan.counters[a.Hkv]) return;
+  const int2 tb = a.plan.tile_b[t];
+  const int nseg = tb.y;
+  if (nseg <= 1) return;
+  const int4 ta = a.plan.tile_a[t];
+  const int G = a.Hq / a.Hkv;
+  const int ml = threadIdx.x >> 1, dh = (threadIdx.x & 1) * 64;
+  const int m = ta.y + ml;
+  if (m >= ta.w) return;
+  const int arow = a.plan.a_lo[ta.x] + m / G, hq = g * G + m % G;
+  float M = -INFINITY;
+  for (int s = 0; s < nseg; ++s) {
+    const size_t pidx = (size_t)g * a.plan.max_items + tb.x + s;
+    M = fmaxf(M, a.plan.part_ml[pidx * kTM + ml].x);
+  }
+  float acc[64];
+#pragma unroll
+  for (int i = 0; i < 64; ++i) acc[i] = 0.f;
+  float L = 0.f;
+  for (int s = 0; s < nseg; ++s) {
+    const size_t pidx = (size_t)g * a.plan.max_items + tb.x + s;
+    const float2 st = a.plan.part_ml[pidx * kTM + ml];
+    const float wgt = exp2f(st.x - M);                      // 0 for a segment this row sees nothing of
+    L += st.y * wgt;
+    const f32x4 *po = reinterpret_cast<const f32x4 *>(a.plan.part_o + (pidx * kTM + ml) * kD + dh);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      f32x4 v = po[i];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) acc[4 * i + e] = fmaf(v[e], wgt, acc[4 * i + e]);
+    }
+  }
+  const float inv = 1.0f / L;
+  bf16_t *orow = (bf16_t *)a.out + ((size_t)arow * a.Hq + hq) * kD + dh;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    bf16x8 v;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = a3_f2bf(acc[8 * i + e] * inv);
+    *reinterpret_cast<bf16x8 *>(orow + 8 * i) = v;
+  }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -309,11 +522,34 @@ int attn_max_tiles(const a3_layout *L, int n_act) {
   return (int)(((long long)n_act * G + kTM - 1) / kTM) + L->n_req;
 }
 
+// Segment length for cutting long tiles: 4096 keys, or 1/8 of the longest request if that is more.
+int attn_seg_len(const a3_layout *L) {
+  const int max_len = L->max_ctx_len + L->max_q_len;
+  int seg = ((max_len + 7) / 8 + kTK - 1) / kTK * kTK;
+  int floor_len = 4096;
+  if (const char *e = getenv("A3_ATTN_SEG")) {          // tuning override, multiple of 64
+    int v = atoi(e);
+    if (v >= 256) floor_len = v / kTK * kTK;
+  }
+  return seg > floor_len ? seg : floor_len;
+}
+
+int attn_max_items(const a3_layout *L, int n_act) {
+  const int max_len = L->max_ctx_len + L->max_q_len;
+  const int seg = attn_seg_len(L);
+  return attn_max_tiles(L, n_act) * ((max_len + seg - 1) / seg);
+}
+
 }  // namespace
 
 size_t a3_attn_ws_bytes(const a3_layout *L, int max_active_rows) {
-  size_t per_req = a3_align_up((size_t)(L->n_req + 1) * sizeof(int), 256);
-  return 3 * per_req + a3_align_up((size_t)attn_max_tiles(L, max_active_rows) * sizeof(int4), 256) + 512;
+  if (L->dtype != A3_BF16) return 256;
+  const size_t per_req = a3_align_up((size_t)(L->n_req + 1) * sizeof(int), 256);
+  const size_t tiles = attn_max_tiles(L, max_active_rows), items = attn_max_items(L, max_active_rows);
+  return 2 * per_req + a3_align_up(tiles * sizeof(int4), 256) + a3_align_up(tiles * sizeof(int2), 256) +
+         a3_align_up(items * sizeof(int4), 256) + a3_align_up((size_t)(L->n_kv_heads + 2) * sizeof(int), 256) +
+         a3_align_up(items * L->n_kv_heads * kTM * kD * sizeof(float), 256) +
+         a3_align_up(items * L->n_kv_heads * kTM * sizeof(float2), 256) + 2048;
 }
 
 extern "C" a3_status a3_fused_attention(const a3_layout *L, const void *q_act, const int *act_idx, int n_act,
@@ -333,21 +569,38 @@ extern "C" a3_status a3_fused_attention(const a3_layout *L, const void *q_act, c
   a.act_idx = act_idx; a.seg_start = L->seg_start; a.tok_req = L->tok_req;
   a.n_act = n_act; a.Hq = L->n_q_heads; a.Hkv = L->n_kv_heads; a.d = L->head_dim;
   a.scale2 = a3_scale_of(L) * kLog2e;
-  a.plan = attn_plan{nullptr, nullptr, nullptr, nullptr, nullptr};
+  memset(&a.plan, 0, sizeof(a.plan));
   if (L->dtype == A3_BF16) {
     A3_REQUIRE(ws != nullptr, A3_ERR_WORKSPACE, "a3_fused_attention: workspace is NULL");
     A3_REQUIRE(ws_bytes >= a3_attn_ws_bytes(L, n_act), A3_ERR_WORKSPACE,
                "a3_fused_attention: workspace %zu bytes, need %zu", ws_bytes, a3_attn_ws_bytes(L, n_act));
-    const int max_tiles = attn_max_tiles(L, n_act);
+    static bool attr_done = false;
+    if (!attr_done) {
+      hipError_t e = hipFuncSetAttribute((const void *)attn_bf16_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                         (int)kAttnLds);
+      if (e != hipSuccess) return a3_fail(A3_ERR_HIP, "a3_fused_attention: %s", hipGetErrorString(e));
+      attr_done = true;
+    }
+    const int max_tiles = attn_max_tiles(L, n_act), max_items = attn_max_items(L, n_act);
+    const int Hkv = L->n_kv_heads;
     a3_ws_cursor cur(ws, ws_bytes);
-    a.plan.cnt = (int *)cur.take((size_t)(L->n_req + 1) * sizeof(int));
     a.plan.a_lo = (int *)cur.take((size_t)(L->n_req + 1) * sizeof(int));
     a.plan.tile_start = (int *)cur.take((size_t)(L->n_req + 1) * sizeof(int));
-    a.plan.desc = (int4 *)cur.take((size_t)max_tiles * sizeof(int4));
-    a.plan.n_tiles = (int *)cur.take(sizeof(int));
-    hipLaunchKernelGGL(attn_plan_kernel, dim3(1), dim3(1024), 0, st, a.plan, act_idx, n_act, L->tok_req, L->seg_start,
-                       L->n_req, L->n_q_heads / L->n_kv_heads, max_tiles);
-    hipLaunchKernelGGL(attn_bf16_kernel, dim3((unsigned)max_tiles * L->n_kv_heads), dim3(256), 0, st, a);
+    a.plan.tile_a = (int4 *)cur.take((size_t)max_tiles * sizeof(int4));
+    a.plan.tile_b = (int2 *)cur.take((size_t)max_tiles * sizeof(int2));
+    a.plan.items = (int4 *)cur.take((size_t)max_items * sizeof(int4));
+    a.plan.counters = (int *)cur.take((size_t)(Hkv + 2) * sizeof(int));
+    a.plan.part_o = (float *)cur.take((size_t)max_items * Hkv * kTM * kD * sizeof(float));
+    a.plan.part_ml = (float2 *)cur.take((size_t)max_items * Hkv * kTM * sizeof(float2));
+    a.plan.max_tiles = max_tiles; a.plan.max_items = max_items; a.plan.seg_len = attn_seg_len(L);
+    hipLaunchKernelGGL(attn_plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, a.plan, act_idx, n_act, L->seg_start,
+                       L->n_req, L->n_q_heads / L->n_kv_heads, Hkv);
+    // persistent workgroups, two per CU; blockIdx % Hkv = KV head, so with 8 KV heads each XCD's L2
+    // serves the K/V of one head
+    int wgs_per_head = (512 + Hkv - 1) / Hkv;
+    if (wgs_per_head > max_items) wgs_per_head = max_items;
+    hipLaunchKernelGGL(attn_bf16_kernel, dim3((unsigned)wgs_per_head * Hkv), dim3(256), kAttnLds, st, a);
+    hipLaunchKernelGGL(attn_combine_kernel, dim3((unsigned)max_tiles, Hkv), dim3(256), 0, st, a);
   } else {
     hipLaunchKernelGGL(attn_f32_kernel, dim3(n_act, L->n_q_heads), dim3(256), 0, st, a);
   }
