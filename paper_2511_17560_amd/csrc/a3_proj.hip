@@ -9,6 +9,8 @@
 // RoPE pairings (adjacent coordinates, or i with i+64) are lane-local and the rotation runs in
 // the epilogue on the fp32 accumulators, before the single rounding to bf16.
 // fp32: a plain LDS-tiled FMA kernel (correctness configuration, not tuned).
+#include <stdlib.h>
+
 #include "a3_internal.h"
 
 namespace {
@@ -16,13 +18,17 @@ namespace {
 // ---------------------------------------------------------------------------------------
 // bf16 MFMA kernel
 // ---------------------------------------------------------------------------------------
-constexpr int kHeadDim = 128;        // features per tile = one head
-constexpr int kTokTile = 128;        // listed rows per tile
-constexpr int kBK = 64;              // reduction slab
-constexpr int kStride = kBK + 8;     // LDS row stride in elements: 144 B, 16 rows cover all 64 banks once
-constexpr int kThreads = 256;
-constexpr int kTileElems = 128 * kStride;
-constexpr size_t kProjLds = (size_t)4 * kTileElems * sizeof(bf16_t);   // W and X tiles, double buffered
+// Workgroup tile: 2 heads (256 output features) x 64*NTW listed rows, 2*NTW waves as 2 (head) x NTW
+// (64 rows).  A wave owns one head x 64 rows: 4 x 2 accumulator blocks of 32x32.  NTW (2, 3 or 4) is
+// chosen per launch: larger tiles need less L2 traffic per flop, smaller ones fill the 256 CUs better.  The weight tile goes
+// through LDS (each fragment feeds two MFMAs: 0.5 LDS reads per MFMA, which the 128 B/clk LDS
+// can sustain next to the matrix cores); the gathered hidden rows are private to a wave's row
+// range and are read straight from global memory into MFMA operand layout, one k-tile ahead.
+constexpr int kHeadDim = 128;
+constexpr int kBK = 64;              // reduction slab per barrier
+constexpr int kWStride = kBK + 8;    // LDS row stride in elements: 144 B, 8 rows cover all 32 banks once
+constexpr int kWPieces = 256 * kBK / 8;   // 16-byte pieces of a weight slab
+constexpr int kWTileElems = 2 * kHeadDim * kWStride;
 
 struct proj_args {
   const bf16_t *hidden;
@@ -34,137 +40,302 @@ struct proj_args {
   const int *tok_pos;
   const float2 *pos_cs;
   int K, Hq, Hkv, rope_layout;
+  int n_pairs, n_tok_tiles;
 };
 
-__global__ void __launch_bounds__(kThreads)
+constexpr size_t proj_lds_bytes(int ntw) { return (size_t)2 * (kWTileElems + 64 * ntw * kWStride) * sizeof(bf16_t); }
+
+struct head_sel { int which, head, heads_out; };
+
+__device__ __forceinline__ head_sel select_head(int h, int Hq, int Hkv) {
+  head_sel r;
+  if (h < Hq) { r.which = 0; r.head = h; r.heads_out = Hq; }
+  else if (h < Hq + Hkv) { r.which = 1; r.head = h - Hq; r.heads_out = Hkv; }
+  else { r.which = 2; r.head = h - Hq - Hkv; r.heads_out = Hkv; }
+  return r;
+}
+
+template <int NTW>
+__global__ void __launch_bounds__(128 * NTW, 1)
 proj_bf16_kernel(proj_args a) {
+  constexpr int kThreads = 128 * NTW;
+  constexpr int kTokTile = 64 * NTW;
+  constexpr int kWChunks = (kWPieces + kThreads - 1) / kThreads;   // weight pieces per lane
+  constexpr int kXChunks = kTokTile * (kBK / 8) / kThreads;        // hidden-row pieces per lane (= 4)
+  constexpr int kXTileElems = kTokTile * kWStride;
   extern __shared__ __align__(16) unsigned char lds_raw[];
-  bf16_t *Ws = reinterpret_cast<bf16_t *>(lds_raw);          // [2][128][kStride]
-  bf16_t *Xs = Ws + 2 * kTileElems;                          // [2][128][kStride]
+  bf16_t *Ws = reinterpret_cast<bf16_t *>(lds_raw);          // [2][256][kWStride]
+  bf16_t *Xs = Ws + 2 * kWTileElems;                         // [2][kTokTile][kWStride]
 
-  // which projection / head this tile belongs to
-  int head = blockIdx.x, which = 0, heads_out = a.Hq;
-  if (head >= a.Hq) { head -= a.Hq; which = 1; heads_out = a.Hkv; }
-  if (which == 1 && head >= a.Hkv) { head -= a.Hkv; which = 2; }
-  bf16_t *__restrict__ out = a.out[which];
-  if (out == nullptr) return;
-  const bf16_t *__restrict__ W = a.w[which] + (size_t)head * kHeadDim * a.K;
-  const int m0 = blockIdx.y * kTokTile;
+  // workgroup -> (head pair, row tile).  Consecutive workgroup ids go to different XCDs; all row
+  // tiles of one head pair are kept on one XCD so its L2 holds that pair's weights.
+  const int xcd = blockIdx.x & 7, q = blockIdx.x >> 3;
+  const int hp = xcd + 8 * (q / a.n_tok_tiles), tt = q % a.n_tok_tiles;
+  if (hp >= a.n_pairs) return;
+  const int n_heads = a.Hq + 2 * a.Hkv;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, lhi = lane >> 5;
+  const int fh = wave & 1, th = wave >> 1;
 
-  // global -> LDS staging: thread moves 16 B of 4 rows of each tile per slab
-  const int c16 = tid & 7, r0 = tid >> 3;
-  const bf16_t *wsrc[4], *xsrc[4];
+  // ---- weight staging: a slab is 256 rows x kBK/8 pieces of 16 B; lane takes pieces tid, tid+kThreads, .. --
+  const bf16_t *wsrc[kWChunks];
+  int wdst[kWChunks];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    int r = r0 + 32 * i;
-    wsrc[i] = W + (size_t)r * a.K + c16 * 8;
-    int m = m0 + r;
-    if (m >= a.n_rows) m = a.n_rows - 1;            // clamp: computed but never stored
-    int src_row = a.row_idx ? a.row_idx[m] : m;
-    xsrc[i] = a.hidden + (size_t)src_row * a.K + c16 * 8;
+  for (int i = 0; i < kWChunks; ++i) {
+    int c = min(tid + i * kThreads, kWPieces - 1);           // clamp (384 lanes: the last round is partial)
+    int row = c / (kBK / 8), wc = c % (kBK / 8);
+    int hsel = min(2 * hp + (row >> 7), n_heads - 1);        // rows 0..127: first head, 128..255: second
+    head_sel hs = select_head(hsel, a.Hq, a.Hkv);
+    const bf16_t *wb = a.w[hs.which];
+    if (wb == nullptr) wb = a.w[0] ? a.w[0] : (a.w[1] ? a.w[1] : a.w[2]);   // unused head: any valid tile
+    int hh = a.w[hs.which] ? hs.head : 0;
+    wsrc[i] = wb + ((size_t)hh * kHeadDim + (row & 127)) * a.K + wc * 8;
+    wdst[i] = row * kWStride + wc * 8;
   }
-  uint4 wreg[4], xreg[4];
-  auto gload = [&](int k0) {
+  // ---- this wave's head and rows ---------------------------------------------------------------------
+  const int my_head = 2 * hp + fh;
+  const head_sel hs = select_head(min(my_head, n_heads - 1), a.Hq, a.Hkv);
+  bf16_t *__restrict__ out = my_head < n_heads ? a.out[hs.which] : nullptr;
+  const bool compute = out != nullptr;
+  const int tok0 = tt * kTokTile + th * 64;
+  // ---- hidden-row staging: 8 lanes fetch one 128-byte segment of a gathered row ---------------------------
+  const bf16_t *xsrc[kXChunks];
+  int xdst[kXChunks];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      wreg[i] = *reinterpret_cast<const uint4 *>(wsrc[i] + k0);
-      xreg[i] = *reinterpret_cast<const uint4 *>(xsrc[i] + k0);
-    }
-  };
-  auto lstore = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      int off = buf * kTileElems + (r0 + 32 * i) * kStride + c16 * 8;
-      *reinterpret_cast<uint4 *>(Ws + off) = wreg[i];
-      *reinterpret_cast<uint4 *>(Xs + off) = xreg[i];
-    }
-  };
+  for (int i = 0; i < kXChunks; ++i) {
+    int c = tid + i * kThreads;
+    int row = c >> 3, xc = c & 7;
+    int m = min(tt * kTokTile + row, a.n_rows - 1);          // clamp: computed but never stored
+    int src_row = a.row_idx ? a.row_idx[m] : m;
+    xsrc[i] = a.hidden + (size_t)src_row * a.K + xc * 8;
+    xdst[i] = row * kWStride + xc * 8;
+  }
 
-  f32x16 acc[4];
+  f32x16 acc[4][2];
 #pragma unroll
-  for (int b = 0; b < 4; ++b)
+  for (int fb = 0; fb < 4; ++fb)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[b][r] = 0.f;
+    for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[fb][tb][r] = 0.f;
 
-  const int frag_row = lane & 31, frag_k = (lane >> 5) * 8;
-  const int KT = a.K / kBK;
-  gload(0);
-  lstore(0);
+  uint4 wreg[kWChunks];
+  uint4 xreg[kXChunks];
+#define A3_WLOAD(K0)                                                                     \
+  _Pragma("unroll") for (int i = 0; i < kWChunks; ++i)                                   \
+    wreg[i] = *reinterpret_cast<const uint4 *>(wsrc[i] + (K0));
+#define A3_WSTORE(BUF)                                                                   \
+  _Pragma("unroll") for (int i = 0; i < kWChunks; ++i)                                   \
+    if ((i + 1) * kThreads <= kWPieces || tid + i * kThreads < kWPieces)                 \
+      *reinterpret_cast<uint4 *>(Ws + (BUF) * kWTileElems + wdst[i]) = wreg[i];
+#define A3_XLOAD(K0)                                                                     \
+  _Pragma("unroll") for (int i = 0; i < kXChunks; ++i)                                   \
+    xreg[i] = *reinterpret_cast<const uint4 *>(xsrc[i] + (K0));
+#define A3_XSTORE(BUF)                                                                   \
+  _Pragma("unroll") for (int i = 0; i < kXChunks; ++i)                                   \
+    *reinterpret_cast<uint4 *>(Xs + (BUF) * kXTileElems + xdst[i]) = xreg[i];
+#define A3_COMPUTE(BUF)                                                                                      \
+  if (compute) {                                                                                             \
+    const bf16_t *wb = Ws + (BUF) * kWTileElems + (fh * kHeadDim + l32) * kWStride + lhi * 8;               \
+    const bf16_t *xb = Xs + (BUF) * kXTileElems + (th * 64 + l32) * kWStride + lhi * 8;                     \
+    _Pragma("unroll") for (int ks = 0; ks < kBK / 16; ++ks) {                                                \
+      bf16x8 wf[4], xf[2];                                                                                   \
+      _Pragma("unroll") for (int tb = 0; tb < 2; ++tb)                                                       \
+        xf[tb] = *reinterpret_cast<const bf16x8 *>(xb + tb * 32 * kWStride + ks * 16);                       \
+      _Pragma("unroll") for (int fb = 0; fb < 4; ++fb)                                                       \
+        wf[fb] = *reinterpret_cast<const bf16x8 *>(wb + fb * 32 * kWStride + ks * 16);                       \
+      _Pragma("unroll") for (int fb = 0; fb < 4; ++fb)                                                       \
+        _Pragma("unroll") for (int tb = 0; tb < 2; ++tb)                                                     \
+          acc[fb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[fb], xf[tb], acc[fb][tb], 0, 0, 0);       \
+    }                                                                                                        \
+  }
+
+  const int K = a.K;                                          // multiple of 64
+  A3_WLOAD(0)
+  A3_XLOAD(0)
+  A3_WSTORE(0)
+  A3_XSTORE(0)
   __syncthreads();
-  for (int kt = 0; kt < KT; ++kt) {
-    const int buf = kt & 1;
-    if (kt + 1 < KT) gload((kt + 1) * kBK);
-    const bf16_t *wb = Ws + buf * kTileElems + frag_row * kStride + frag_k;
-    const bf16_t *xb = Xs + buf * kTileElems + (wave * 32 + frag_row) * kStride + frag_k;
-#pragma unroll
-    for (int ks = 0; ks < kBK / 16; ++ks) {
-      bf16x8 xf = *reinterpret_cast<const bf16x8 *>(xb + ks * 16);
-#pragma unroll
-      for (int b = 0; b < 4; ++b) {
-        bf16x8 wf = *reinterpret_cast<const bf16x8 *>(wb + b * 32 * kStride + ks * 16);
-        acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf, acc[b], 0, 0, 0);
-      }
-    }
-    if (kt + 1 < KT) lstore(buf ^ 1);
+  int buf = 0;
+  for (int k0 = 0; k0 < K; k0 += kBK, buf ^= 1) {
+    const int kn = min(k0 + kBK, K - kBK);                    // next slab (the last one re-reads itself)
+    A3_WLOAD(kn)
+    A3_XLOAD(kn)
+    A3_COMPUTE(buf)
+    A3_WSTORE(buf ^ 1)
+    A3_XSTORE(buf ^ 1)
     __syncthreads();
   }
+#undef A3_WLOAD
+#undef A3_WSTORE
+#undef A3_XLOAD
+#undef A3_XSTORE
+#undef A3_COMPUTE
+  if (!compute) return;
 
-  // ---- epilogue: bias, RoPE, one rounding, store -------------------------------------------
-  // accumulator block b, register r of this lane: feature f = 32 b + 8 (r/4) + 4 (lane/32) + r%4,
-  // token = wave*32 + lane%32
-  const int tok = m0 + wave * 32 + (lane & 31);
-  if (tok >= a.n_rows) return;
-  const int fq = (lane >> 5) * 4;
+  // ---- epilogue: bias, RoPE, one rounding, store -------------------------------------------------------
+  // accumulator block (fb, tb), register r of this lane: feature 32 fb + 8 (r/4) + 4 lhi + r%4,
+  // row tok0 + 32 tb + lane%32
+  const int which = hs.which, head = hs.head, heads_out = hs.heads_out;
+  const int fq = lhi * 4;
   const bf16_t *bias = a.bias[which];
+#pragma unroll
+  for (int tb = 0; tb < 2; ++tb) {
+    const int tok = tok0 + tb * 32 + l32;
+    if (tok >= a.n_rows) continue;
+    if (bias) {
+#pragma unroll
+      for (int fb = 0; fb < 4; ++fb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          acc[fb][tb][r] += a3_bf2f(bias[head * kHeadDim + 32 * fb + 8 * (r >> 2) + fq + (r & 3)]);
+    }
+    if (which != 2) {
+      const int src_row = a.row_idx ? a.row_idx[tok] : tok;
+      const float2 *cs = a.pos_cs + (size_t)a.tok_pos[src_row] * (kHeadDim / 2);
+      if (a.rope_layout == A3_ROPE_INTERLEAVED) {
+#pragma unroll
+        for (int fb = 0; fb < 4; ++fb)
+#pragma unroll
+          for (int q4 = 0; q4 < 4; ++q4) {
+            const int f = 32 * fb + 8 * q4 + fq;               // first of 4 consecutive features
+            const float4 t = *reinterpret_cast<const float4 *>(cs + (f >> 1));   // pairs f/2 and f/2+1
+            float x0 = acc[fb][tb][4 * q4], x1 = acc[fb][tb][4 * q4 + 1], x2 = acc[fb][tb][4 * q4 + 2],
+                  x3 = acc[fb][tb][4 * q4 + 3];
+            acc[fb][tb][4 * q4] = x0 * t.x - x1 * t.y;
+            acc[fb][tb][4 * q4 + 1] = x0 * t.y + x1 * t.x;
+            acc[fb][tb][4 * q4 + 2] = x2 * t.z - x3 * t.w;
+            acc[fb][tb][4 * q4 + 3] = x2 * t.w + x3 * t.z;
+          }
+      } else {
+#pragma unroll
+        for (int fb = 0; fb < 2; ++fb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int p = 32 * fb + 8 * (r >> 2) + fq + (r & 3);  // pair index = feature in the first half
+            const float2 t = cs[p];
+            float xlo = acc[fb][tb][r], xhi = acc[fb + 2][tb][r];
+            acc[fb][tb][r] = xlo * t.x - xhi * t.y;
+            acc[fb + 2][tb][r] = xlo * t.y + xhi * t.x;
+          }
+      }
+    }
+    bf16_t *orow = out + ((size_t)tok * heads_out + head) * kHeadDim;
+#pragma unroll
+    for (int fb = 0; fb < 4; ++fb)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        bf16x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = a3_f2bf(acc[fb][tb][4 * q4 + e]);
+        *reinterpret_cast<bf16x4 *>(orow + 32 * fb + 8 * q4 + fq) = v;
+      }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// bf16 kernel for few rows (the question tokens): weight-streaming bound
+// ---------------------------------------------------------------------------------------
+// With ~64 rows the GEMM is a stream over the 48 MB of weights.  To put every CU on that stream a
+// workgroup takes only 32 features of one head (16 from each half of the head, so both RoPE
+// pairings stay inside it) x 64 rows, and its 4 waves split the reduction dimension four ways;
+// fragments are read straight from global memory and the four partial tiles are added in LDS in
+// wave order.
+__global__ void __launch_bounds__(256)
+proj_small_bf16_kernel(proj_args a) {
+  __shared__ float red[4][2][16][64];                          // [wave][row block][register][lane]
+
+  const int head_all = blockIdx.x >> 2, sb = blockIdx.x & 3;
+  const head_sel hs = select_head(head_all, a.Hq, a.Hkv);
+  bf16_t *__restrict__ out = a.out[hs.which];
+  if (out == nullptr) return;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, lhi = lane >> 5;
+  const int tok0 = blockIdx.y * 64;
+  // MFMA row i of this workgroup's weight block <-> feature of the head
+  const int feat = l32 < 16 ? 16 * sb + l32 : 64 + 16 * sb + (l32 - 16);
+  const int kq = a.K / 4;                                      // this wave's share of the reduction
+  const bf16_t *wp = a.w[hs.which] + ((size_t)hs.head * kHeadDim + feat) * a.K + wave * kq + lhi * 8;
+  const bf16_t *xp[2];
+#pragma unroll
+  for (int tb = 0; tb < 2; ++tb) {
+    int m = min(tok0 + tb * 32 + l32, a.n_rows - 1);
+    int src_row = a.row_idx ? a.row_idx[m] : m;
+    xp[tb] = a.hidden + (size_t)src_row * a.K + wave * kq + lhi * 8;
+  }
+  f32x16 acc[2];
+#pragma unroll
+  for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[tb][r] = 0.f;
+  for (int k = 0; k < kq; k += 64) {                           // kq is a multiple of 16; 4 steps per trip
+    bf16x8 wf[4], xf[4][2];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int kk = min(k + 16 * u, kq - 16);                 // tail of a share that is not a multiple of 64
+      wf[u] = *reinterpret_cast<const bf16x8 *>(wp + kk);
+      xf[u][0] = *reinterpret_cast<const bf16x8 *>(xp[0] + kk);
+      xf[u][1] = *reinterpret_cast<const bf16x8 *>(xp[1] + kk);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (k + 16 * u < kq) {
+        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[u], xf[u][0], acc[0], 0, 0, 0);
+        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[u], xf[u][1], acc[1], 0, 0, 0);
+      }
+    }
+  }
+#pragma unroll
+  for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) red[wave][tb][r][lane] = acc[tb][r];
+  __syncthreads();
+  if (wave >= 2) return;
+  const int tb = wave;                                         // waves 0 and 1 finish one row block each
+  const int tok = tok0 + tb * 32 + l32;
+  if (tok >= a.n_rows) return;
+  float v[16];
+#pragma unroll
+  for (int r = 0; r < 16; ++r) v[r] = (red[0][tb][r][lane] + red[1][tb][r][lane]) + (red[2][tb][r][lane] + red[3][tb][r][lane]);
+  // register r: MFMA row i = 8 (r/4) + 4 lhi + r%4; i < 16 is the first half of the head, i >= 16 the second
+  const bf16_t *bias = a.bias[hs.which];
+  auto feat_of = [&](int r) {
+    int i = 8 * (r >> 2) + 4 * lhi + (r & 3);
+    return i < 16 ? 16 * sb + i : 64 + 16 * sb + (i - 16);
+  };
   if (bias) {
 #pragma unroll
-    for (int b = 0; b < 4; ++b)
-#pragma unroll
-      for (int r = 0; r < 16; ++r)
-        acc[b][r] += a3_bf2f(bias[head * kHeadDim + 32 * b + 8 * (r >> 2) + fq + (r & 3)]);
+    for (int r = 0; r < 16; ++r) v[r] += a3_bf2f(bias[hs.head * kHeadDim + feat_of(r)]);
   }
-  if (which != 2) {
+  if (hs.which != 2) {
     const int src_row = a.row_idx ? a.row_idx[tok] : tok;
     const float2 *cs = a.pos_cs + (size_t)a.tok_pos[src_row] * (kHeadDim / 2);
     if (a.rope_layout == A3_ROPE_INTERLEAVED) {
 #pragma unroll
-      for (int b = 0; b < 4; ++b)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int f = 32 * b + 8 * q + fq;                 // first of 4 consecutive features
-          const float4 t = *reinterpret_cast<const float4 *>(cs + (f >> 1));   // pairs f/2 and f/2+1
-          float x0 = acc[b][4 * q], x1 = acc[b][4 * q + 1], x2 = acc[b][4 * q + 2], x3 = acc[b][4 * q + 3];
-          acc[b][4 * q] = x0 * t.x - x1 * t.y;
-          acc[b][4 * q + 1] = x0 * t.y + x1 * t.x;
-          acc[b][4 * q + 2] = x2 * t.z - x3 * t.w;
-          acc[b][4 * q + 3] = x2 * t.w + x3 * t.z;
-        }
+      for (int r = 0; r < 16; r += 2) {
+        const float2 t = cs[feat_of(r) >> 1];
+        float x0 = v[r], x1 = v[r + 1];
+        v[r] = x0 * t.x - x1 * t.y;
+        v[r + 1] = x0 * t.y + x1 * t.x;
+      }
     } else {
 #pragma unroll
-      for (int b = 0; b < 2; ++b)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int p = 32 * b + 8 * (r >> 2) + fq + (r & 3);   // pair index = feature in the first half
-          const float2 t = cs[p];
-          float xa = acc[b][r], xb2 = acc[b + 2][r];
-          acc[b][r] = xa * t.x - xb2 * t.y;
-          acc[b + 2][r] = xa * t.y + xb2 * t.x;
-        }
+      for (int r = 0; r < 8; ++r) {                            // register r + 8 holds feature + 64
+        const float2 t = cs[feat_of(r)];
+        float xlo = v[r], xhi = v[r + 8];
+        v[r] = xlo * t.x - xhi * t.y;
+        v[r + 8] = xlo * t.y + xhi * t.x;
+      }
     }
   }
-  bf16_t *orow = out + ((size_t)tok * heads_out + head) * kHeadDim;
+  bf16_t *orow = out + ((size_t)tok * hs.heads_out + hs.head) * kHeadDim;
 #pragma unroll
-  for (int b = 0; b < 4; ++b)
+  for (int q4 = 0; q4 < 4; ++q4) {
+    bf16x4 o;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      bf16x4 v;
-      v[0] = a3_f2bf(acc[b][4 * q]);
-      v[1] = a3_f2bf(acc[b][4 * q + 1]);
-      v[2] = a3_f2bf(acc[b][4 * q + 2]);
-      v[3] = a3_f2bf(acc[b][4 * q + 3]);
-      *reinterpret_cast<bf16x4 *>(orow + 32 * b + 8 * q + fq) = v;
-    }
+    for (int e = 0; e < 4; ++e) o[e] = a3_f2bf(v[4 * q4 + e]);
+    *reinterpret_cast<bf16x4 *>(orow + feat_of(4 * q4)) = o;
+  }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -278,15 +449,8 @@ extern "C" a3_status a3_selected_qkv_proj(const a3_layout *L, const void *hidden
   hipStream_t st = (hipStream_t)stream;
   const int n_heads_total = L->n_q_heads + 2 * L->n_kv_heads;
   if (L->dtype == A3_BF16) {
-    A3_REQUIRE(L->hidden % kBK == 0, A3_ERR_UNSUPPORTED, "a3_selected_qkv_proj: bf16 needs hidden %% 64 == 0, got %d",
+    A3_REQUIRE(L->hidden % 64 == 0, A3_ERR_UNSUPPORTED, "a3_selected_qkv_proj: bf16 needs hidden %% 64 == 0, got %d",
                L->hidden);
-    static bool attr_done = false;
-    if (!attr_done) {
-      hipError_t e = hipFuncSetAttribute((const void *)proj_bf16_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                         (int)kProjLds);
-      if (e != hipSuccess) return a3_fail(A3_ERR_HIP, "a3_selected_qkv_proj: %s", hipGetErrorString(e));
-      attr_done = true;
-    }
     proj_args a;
     a.hidden = (const bf16_t *)hidden; a.row_idx = row_idx; a.n_rows = n_rows;
     a.w[0] = (const bf16_t *)wq; a.w[1] = (const bf16_t *)wk; a.w[2] = (const bf16_t *)wv;
@@ -294,8 +458,47 @@ extern "C" a3_status a3_selected_qkv_proj(const a3_layout *L, const void *hidden
     a.out[0] = (bf16_t *)q_out; a.out[1] = (bf16_t *)k_out; a.out[2] = (bf16_t *)v_out;
     a.tok_pos = L->tok_pos; a.pos_cs = (const float2 *)L->rope_pos_cs;
     a.K = L->hidden; a.Hq = L->n_q_heads; a.Hkv = L->n_kv_heads; a.rope_layout = L->rope_layout;
-    dim3 grid(n_heads_total, (n_rows + kTokTile - 1) / kTokTile);
-    hipLaunchKernelGGL(proj_bf16_kernel, grid, dim3(kThreads), kProjLds, st, a);
+    a.n_pairs = (n_heads_total + 1) / 2;
+    a.n_tok_tiles = 0;
+    if (n_rows <= 192 && L->hidden % 64 == 0 && !getenv("A3_PROJ_NTW")) {
+      // few rows: stream the weights with 4 x n_heads x ceil(rows/64) small workgroups
+      hipLaunchKernelGGL(proj_small_bf16_kernel, dim3(4 * n_heads_total, (n_rows + 63) / 64), dim3(256), 0, st, a);
+      A3_CHECK_LAUNCH("a3_selected_qkv_proj");
+      return A3_OK;
+    }
+    // rows per workgroup: 128, 192 or 256.  Estimate each choice by (useful rows / padded rows) x (how
+    // evenly the workgroups fill 256 CUs) x a bonus for the lower L2 traffic of larger tiles.
+    int ntw = 2;
+    if (const char *e = getenv("A3_PROJ_NTW")) ntw = atoi(e);
+    else {
+      double best = -1.0;
+      for (int c = 2; c <= 4; ++c) {
+        const int tiles = (n_rows + 64 * c - 1) / (64 * c);
+        const long wgs = (long)tiles * a.n_pairs;
+        const int per_cu = 1;                                 // LDS allows one workgroup per CU
+        const long rounds = (wgs + 256L * per_cu - 1) / (256L * per_cu);
+        const double fill = (double)wgs / (double)(rounds * 256L * per_cu);
+        const double pad = (double)n_rows / (double)(tiles * 64 * c);
+        const double traffic = 256.0 * 64 * c / (256.0 + 64 * c) / 128.0;   // flop per L2 byte, relative to 256x256
+        const double score = pad * fill * (0.5 + 0.5 * traffic);
+        if (score > best) { best = score; ntw = c; }
+      }
+    }
+    if (ntw < 2 || ntw > 4) ntw = 2;
+    a.n_tok_tiles = (n_rows + 64 * ntw - 1) / (64 * ntw);
+    const unsigned grid = 8u * (unsigned)((a.n_pairs + 7) / 8) * (unsigned)a.n_tok_tiles;
+    static bool attr_done = false;
+    if (!attr_done) {
+      hipError_t e1 = hipFuncSetAttribute((const void *)proj_bf16_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)proj_lds_bytes(2));
+      hipError_t e2 = hipFuncSetAttribute((const void *)proj_bf16_kernel<3>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)proj_lds_bytes(3));
+      hipError_t e3 = hipFuncSetAttribute((const void *)proj_bf16_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)proj_lds_bytes(4));
+      if (e1 != hipSuccess || e2 != hipSuccess || e3 != hipSuccess)
+        return a3_fail(A3_ERR_HIP, "a3_selected_qkv_proj: cannot raise the dynamic LDS limit");
+      attr_done = true;
+    }
+    if (ntw == 2) hipLaunchKernelGGL(proj_bf16_kernel<2>, dim3(grid), dim3(256), proj_lds_bytes(2), st, a);
+    else if (ntw == 3) hipLaunchKernelGGL(proj_bf16_kernel<3>, dim3(grid), dim3(384), proj_lds_bytes(3), st, a);
+    else hipLaunchKernelGGL(proj_bf16_kernel<4>, dim3(grid), dim3(512), proj_lds_bytes(4), st, a);
   } else {
     proj_args_f32 a;
     a.hidden = (const float *)hidden; a.row_idx = row_idx; a.n_rows = n_rows;

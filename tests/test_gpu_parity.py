@@ -139,6 +139,28 @@ def test_selected_qkv_proj(name):
     assert max_abs_rel(to_host(k), want) <= tol(w)
 
 
+@pytest.mark.parametrize("ntw", ["2", "3", "4"])
+@pytest.mark.parametrize("name", ["g7-bf16", "batched-bf16-half", "cfg2"])
+def test_selected_qkv_proj_every_tile_width(name, ntw, monkeypatch):
+    """The large-tile GEMM kernel in each of its three workgroup shapes (the library normally
+    picks one by row count; few rows go to the weight-streaming kernel instead)."""
+    monkeypatch.setenv("A3_PROJ_NTW", ntw)
+    c = ctx_of(name)
+    w, b, res, lay = c["w"], c["b"], c["res"], c["lay"]
+    s, t = w.shape, b["t"]
+    dt = s.dtype
+    rows_np = res["act_idx"]
+    n = len(rows_np)
+    q = torch.zeros((n, s.n_q_heads, s.head_dim), dtype=api.torch_dtype(dt), device="cuda")
+    k = torch.zeros((n, s.n_kv_heads, s.head_dim), dtype=api.torch_dtype(dt), device="cuda")
+    v = torch.zeros_like(k)
+    api.a3_selected_qkv_proj(lay, to_dev(t.x_cur, dt), idev(rows_np), n, to_dev(t.wq, dt), to_dev(t.wk, dt),
+                             to_dev(t.wv, dt), q_out=q, k_out=k, v_out=v)
+    assert max_abs_rel(to_host(q), res["q_act"]) <= tol(w)
+    assert max_abs_rel(to_host(k), res["k_fused"][rows_np]) <= tol(w)
+    assert max_abs_rel(to_host(v), res["v_fused"][rows_np]) <= tol(w)
+
+
 @pytest.mark.parametrize("name", NAMES)
 def test_question_scores(name):
     c = ctx_of(name)
