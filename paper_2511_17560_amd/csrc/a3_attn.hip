@@ -404,6 +404,7 @@ attn_bf16_kernel(attn_args a) {
 }
 
 // Merges the partial results of tiles that were cut into key segments, in segment order.
+// One workgroup per (tile, KV head, quarter of the tile's rows); 8 lanes share a row, 16 dims each.
 __global__ void __launch_bounds__(256)
 attn_combine_kernel(attn_args a) {
   const int t = blockIdx.x, g = blockIdx.y;
@@ -413,36 +414,33 @@ attn_combine_kernel(attn_args a) {
   if (nseg <= 1) return;
   const int4 ta = a.plan.tile_a[t];
   const int G = a.Hq / a.Hkv;
-  const int ml = threadIdx.x >> 1, dh = (threadIdx.x & 1) * 64;
+  const int ml = blockIdx.z * 32 + (threadIdx.x >> 3), d0 = (threadIdx.x & 7) * 16;
   const int m = ta.y + ml;
   if (m >= ta.w) return;
   const int arow = a.plan.a_lo[ta.x] + m / G, hq = g * G + m % G;
+  const size_t p0 = (size_t)g * a.plan.max_items + tb.x;
   float M = -INFINITY;
-  for (int s = 0; s < nseg; ++s) {
-    const size_t pidx = (size_t)g * a.plan.max_items + tb.x + s;
-    M = fmaxf(M, a.plan.part_ml[pidx * kTM + ml].x);
-  }
-  float acc[64];
+  for (int s = 0; s < nseg; ++s) M = fmaxf(M, a.plan.part_ml[(p0 + s) * kTM + ml].x);
+  float acc[16];
 #pragma unroll
-  for (int i = 0; i < 64; ++i) acc[i] = 0.f;
+  for (int i = 0; i < 16; ++i) acc[i] = 0.f;
   float L = 0.f;
   for (int s = 0; s < nseg; ++s) {
-    const size_t pidx = (size_t)g * a.plan.max_items + tb.x + s;
-    const float2 st = a.plan.part_ml[pidx * kTM + ml];
+    const float2 st = a.plan.part_ml[(p0 + s) * kTM + ml];
     const float wgt = exp2f(st.x - M);                      // 0 for a segment this row sees nothing of
     L += st.y * wgt;
-    const f32x4 *po = reinterpret_cast<const f32x4 *>(a.plan.part_o + (pidx * kTM + ml) * kD + dh);
+    const f32x4 *po = reinterpret_cast<const f32x4 *>(a.plan.part_o + ((p0 + s) * kTM + ml) * kD + d0);
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
+    for (int i = 0; i < 4; ++i) {
       f32x4 v = po[i];
 #pragma unroll
       for (int e = 0; e < 4; ++e) acc[4 * i + e] = fmaf(v[e], wgt, acc[4 * i + e]);
     }
   }
   const float inv = 1.0f / L;
-  bf16_t *orow = (bf16_t *)a.out + ((size_t)arow * a.Hq + hq) * kD + dh;
+  bf16_t *orow = (bf16_t *)a.out + ((size_t)arow * a.Hq + hq) * kD + d0;
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
+  for (int i = 0; i < 2; ++i) {
     bf16x8 v;
 #pragma unroll
     for (int e = 0; e < 8; ++e) v[e] = a3_f2bf(acc[8 * i + e] * inv);
@@ -600,7 +598,7 @@ extern "C" a3_status a3_fused_attention(const a3_layout *L, const void *q_act, c
     int wgs_per_head = (512 + Hkv - 1) / Hkv;
     if (wgs_per_head > max_items) wgs_per_head = max_items;
     hipLaunchKernelGGL(attn_bf16_kernel, dim3((unsigned)wgs_per_head * Hkv), dim3(256), kAttnLds, st, a);
-    hipLaunchKernelGGL(attn_combine_kernel, dim3((unsigned)max_tiles, Hkv), dim3(256), 0, st, a);
+    hipLaunchKernelGGL(attn_combine_kernel, dim3((unsigned)max_tiles, Hkv, kTM / 32), dim3(256), 0, st, a);
   } else {
     hipLaunchKernelGGL(attn_f32_kernel, dim3(n_act, L->n_q_heads), dim3(256), 0, st, a);
   }

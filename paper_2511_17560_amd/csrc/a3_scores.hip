@@ -7,12 +7,14 @@
 //   pass A   per (key tile, row): partial (max, sum exp)          -> workspace
 //   combine  per row: merge the partials                          -> (max, 1/sum) per row
 //   pass B   per key tile: sum over all rows of exp(l - max)/sum  -> scores
-// Heads and rows are reduced in a fixed order inside the workgroup that owns a key tile, so
-// the result is deterministic (no atomics).
+// Rows, then heads, are reduced in a fixed order, so the result is deterministic (no atomics).
 //
-// bf16: logits on the matrix cores (32x32x16 bf16 MFMA), K tile staged in LDS with a padded
-// stride, Q fragments read straight from global memory (they are L2 resident), exp2 with
-// log2(e) folded into the scale.  fp32: plain FMA kernels (correctness configuration).
+// bf16: logits on the matrix cores (32x32x16 bf16 MFMA).  A workgroup owns 256 keys of one KV
+// head: the K tile (64 KB) sits in LDS with a padded stride and every Q fragment a wave loads
+// (straight from global memory, Q is L2 resident) meets all 8 key blocks, so both K and Q cross
+// the L2 once per pass.  Pass B leaves one partial score per KV head; a last small kernel adds the
+// heads in order.  exp2 with log2(e) folded into the scale.
+// fp32: plain FMA kernels (correctness configuration).
 #include "a3_internal.h"
 
 namespace {
@@ -36,14 +38,16 @@ struct scores_args {
   float2 *part;             // [n_tiles, total_rows] partial (max, sum) in the exp2 domain
   float2 *stats;            // [total_rows] (max, 1/sum)
   float *scores;            // [T]
-  int n_req, Hq, Hkv, d, T, total_rows, n_tiles;
+  float *part_scores;       // [Hkv, T] bf16 path: per KV head partial scores
+  int n_req, Hq, Hkv, d, T, total_rows, n_tiles, tile_keys;
   float scale2;             // sm_scale * log2(e)
 };
 
 // ---------------------------------------------------------------------------------------
 // combine partial row statistics (shared by both element types)
 // ---------------------------------------------------------------------------------------
-constexpr int kTileKeys = 64;
+constexpr int kTileKeys = 64;      // fp32 kernels
+constexpr int kTileKeysMfma = 256; // bf16 kernels
 
 __global__ void __launch_bounds__(256)
 scores_combine_kernel(scores_args a) {
@@ -55,7 +59,7 @@ scores_combine_kernel(scores_args a) {
   if (row < a.total_rows) {
     const int jq = row / a.Hq;
     const int r = find_segment(a.q_start, a.n_req, jq);
-    const int tiles = (a.ctx_len[r] + kTileKeys - 1) / kTileKeys;
+    const int tiles = (a.ctx_len[r] + a.tile_keys - 1) / a.tile_keys;
     for (int t = slice; t < tiles; t += 8) {
       float2 p = a.part[(size_t)t * a.total_rows + row];
       float mn = fmaxf(m, p.x);
@@ -79,66 +83,90 @@ scores_combine_kernel(scores_args a) {
 }
 
 // ---------------------------------------------------------------------------------------
-// bf16 MFMA kernel, head_dim 128.  PASS 0 = partial row statistics, PASS 1 = column sums.
-// Workgroup = one 64-key tile of one request; loops over KV heads and 128-row blocks.
+// bf16 MFMA kernels, head_dim 128.  PASS 0 = partial row statistics, PASS 1 = column sums.
+// Workgroup = 256 keys of one request and one KV head; each wave walks the (question token, head)
+// rows of the group 64 at a time.
 // ---------------------------------------------------------------------------------------
 constexpr int kD = 128;
-constexpr int kKStride = kD + 8;      // LDS row stride (elements): 272 B
+constexpr int kKStride = kD + 8;      // LDS row stride (elements): 272 B, 8 rows cover all 32 banks once
+constexpr size_t kScoresLds = (size_t)kTileKeysMfma * kKStride * sizeof(bf16_t) + 4 * 64 * sizeof(float2) +
+                              4 * kTileKeysMfma * sizeof(float);
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float halves_max(float x) {
+  const uint32_t u = __float_as_uint(x);
+  auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);   // low-half values / high-half values in all lanes
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float halves_sum(float x) {
+  const uint32_t u = __float_as_uint(x);
+  auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
 
 template <int PASS>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(256, 2)
 scores_bf16_kernel(scores_args a) {
-  __shared__ __align__(16) bf16_t Ks[kTileKeys * kKStride];
-  __shared__ float2 St[128];           // PASS 1: (max, 1/sum) of the current 128-row block
-  __shared__ float red[4][kTileKeys];
+  extern __shared__ __align__(16) unsigned char lds_raw[];
+  bf16_t *Ks = reinterpret_cast<bf16_t *>(lds_raw);                                  // [256][kKStride]
+  float2 *St = reinterpret_cast<float2 *>(Ks + kTileKeysMfma * kKStride);             // [4 waves][64 rows]
+  float *red = reinterpret_cast<float *>(St + 4 * 64);                                // [4 waves][256 keys]
 
-  const int r = blockIdx.y;
+  const int r = blockIdx.z, g = blockIdx.y;
   const int N = a.ctx_len[r];
-  const int i0 = blockIdx.x * kTileKeys;
+  const int i0 = blockIdx.x * kTileKeysMfma;
+  if (i0 >= N) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, lhi = lane >> 5;
   const int s = a.seg_start[r];
   const int nq = a.q_len[r];
-  if (PASS == 1 && blockIdx.x == 0) {
-    for (int j = tid; j < nq; j += 256) a.scores[s + N + j] = -INFINITY;   // question rows are not candidates
-  }
-  if (i0 >= N) return;
   const int G = a.Hq / a.Hkv;
-  const int Mg = nq * G;                // rows per KV head: m = j*G + hh
+  const int Mg = nq * G;                // rows of this KV head: m = j*G + hh
   const int qrow0 = a.q_start[r];
   const bf16_t *__restrict__ Q = (const bf16_t *)a.q;
   const bf16_t *__restrict__ K = (const bf16_t *)a.k;
-  const int l32 = lane & 31, lhi = lane >> 5;
 
-  float colsum[2] = {0.f, 0.f};        // PASS 1: this lane's keys (block 0 / 1), partial over its rows
-
-  for (int g = 0; g < a.Hkv; ++g) {
-    __syncthreads();                    // previous K tile fully consumed
-    // stage K tile: 64 keys x 128 dims; 16 lanes cover one 256-byte row
-    for (int i = tid; i < kTileKeys * 16; i += 256) {
-      int kr = i >> 4, c = i & 15;
-      int row = s + i0 + kr;
-      if (row > a.T - 1) row = a.T - 1;  // tail of the last tile: loaded, masked below
-      uint4 v = *reinterpret_cast<const uint4 *>(K + ((size_t)row * a.Hkv + g) * kD + c * 8);
-      *reinterpret_cast<uint4 *>(Ks + kr * kKStride + c * 8) = v;
+  // ---- K tile: 256 keys x 128 dims of head g; 16 lanes per 256-byte row ---------------------------------
+  {
+    const int c = tid & 15, kr0 = tid >> 4;
+    uint4 v[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      int row = min(s + i0 + kr0 + 16 * i, a.T - 1);           // tail rows: loaded, masked below
+      v[i] = *reinterpret_cast<const uint4 *>(K + ((size_t)row * a.Hkv + g) * kD + c * 8);
     }
-    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 16; ++i) *reinterpret_cast<uint4 *>(Ks + (kr0 + 16 * i) * kKStride + c * 8) = v[i];
+  }
+  __syncthreads();
+  const int n_kb = min(8, (N - i0 + 31) / 32);                 // key blocks with at least one real key
+  const bf16_t *kt = Ks + l32 * kKStride + lhi * 8;
 
-    for (int mb = 0; mb < Mg; mb += 128) {
-      // this wave's 32 rows; the lane's row for fragment loads
-      int m = mb + wave * 32 + l32;
-      int mc = m < Mg ? m : Mg - 1;
-      const int row_id = (qrow0 + mc / G) * a.Hq + g * G + mc % G;   // row of the [sum q_len * Hq] row space
-      const bf16_t *qp = Q + (size_t)row_id * kD + lhi * 8;
-      if (PASS == 1) {
-        __syncthreads();                // St of the previous block consumed
-        if (tid < 128) {
-          int m2 = mb + tid;
-          float2 st = make_float2(0.f, 0.f);
-          if (m2 < Mg) st = a.stats[(qrow0 + m2 / G) * a.Hq + g * G + m2 % G];
-          St[tid] = st;
-        }
-        __syncthreads();
-      }
+  float colsum[8];
+#pragma unroll
+  for (int kb = 0; kb < 8; ++kb) colsum[kb] = 0.f;
+
+  for (int rb0 = wave * 64; rb0 < Mg; rb0 += 256) {            // this wave's rows rb0 .. rb0+63
+    // Q fragments of the two 32-row blocks (rows past Mg are clamped and ignored later)
+    bf16x8 qf[2][kD / 16];
+    int row_id[2];
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+      const int m = min(rb0 + b * 32 + l32, Mg - 1);
+      row_id[b] = (qrow0 + m / G) * a.Hq + g * G + m % G;      // row of the [sum q_len * Hq] row space
+      const bf16_t *qp = Q + (size_t)row_id[b] * kD + lhi * 8;
+#pragma unroll
+      for (int ks = 0; ks < kD / 16; ++ks) qf[b][ks] = *reinterpret_cast<const bf16x8 *>(qp + ks * 16);
+    }
+    if (PASS == 1) {
+      // (max, 1/sum) of this wave's 64 rows, read back as broadcasts below; rows past Mg contribute 0
+      const int m = rb0 + lane;
+      float2 st = make_float2(INFINITY, 0.f);                  // exp2(x - inf) * 0 = 0
+      if (m < Mg) st = a.stats[(qrow0 + m / G) * a.Hq + g * G + m % G];
+      St[wave * 64 + lane] = st;                               // same-wave write/read: no barrier needed
+    }
+    float run_max[2] = {-INFINITY, -INFINITY}, run_sum[2] = {0.f, 0.f};
+    for (int kb = 0; kb < n_kb; ++kb) {
       f32x16 acc[2];
 #pragma unroll
       for (int b = 0; b < 2; ++b)
@@ -146,59 +174,81 @@ scores_bf16_kernel(scores_args a) {
         for (int x = 0; x < 16; ++x) acc[b][x] = 0.f;
 #pragma unroll
       for (int ks = 0; ks < kD / 16; ++ks) {
-        bf16x8 qf = *reinterpret_cast<const bf16x8 *>(qp + ks * 16);
+        const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(kt + kb * 32 * kKStride + ks * 16);
 #pragma unroll
         for (int b = 0; b < 2; ++b) {
-          bf16x8 kf = *reinterpret_cast<const bf16x8 *>(Ks + (b * 32 + l32) * kKStride + ks * 16 + lhi * 8);
-          if (PASS == 0) acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf, acc[b], 0, 0, 0);   // C[key][row]
-          else           acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf, kf, acc[b], 0, 0, 0);   // C[row][key]
+          if (PASS == 0) acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[b][ks], acc[b], 0, 0, 0);   // C[key][row]
+          else           acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[b][ks], kf, acc[b], 0, 0, 0);   // C[row][key]
         }
       }
       if (PASS == 0) {
-        // lane: row m (column l32); registers: keys b*32 + 8(x/4) + 4 lhi + x%4
-        float mx = -INFINITY;
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-          for (int x = 0; x < 16; ++x) {
-            int key = i0 + b * 32 + 8 * (x >> 2) + 4 * lhi + (x & 3);
-            float l = key < N ? acc[b][x] * a.scale2 : -INFINITY;
-            acc[b][x] = l;
-            mx = fmaxf(mx, l);
-          }
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        float sum = 0.f;
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-          for (int x = 0; x < 16; ++x) sum += exp2f(acc[b][x] - mx);
-        sum += __shfl_xor(sum, 32, 64);
-        if (lhi == 0 && m < Mg) a.part[(size_t)blockIdx.x * a.total_rows + row_id] = make_float2(mx, sum);
-      } else {
-        // lane: key l32 of block b (column); registers: rows 8(x/4) + 4 lhi + x%4 of this wave's block
+        // lane: row (column l32 of block b); registers: keys i0 + 32 kb + 8(x/4) + 4 lhi + x%4
+        const bool tail = i0 + 32 * kb + 31 >= N;
 #pragma unroll
         for (int b = 0; b < 2; ++b) {
-          float part = 0.f;
+          if (tail) {
+#pragma unroll
+            for (int x = 0; x < 16; ++x)
+              if (i0 + 32 * kb + 8 * (x >> 2) + 4 * lhi + (x & 3) >= N) acc[b][x] = -INFINITY;
+          }
+          float mx = acc[b][0];
+#pragma unroll
+          for (int x = 1; x < 16; ++x) mx = fmaxf(mx, acc[b][x]);
+          mx = halves_max(mx) * a.scale2;                      // block 0 of a tile always has a real key
+          const float new_max = fmaxf(run_max[b], mx);
+          float sum = 0.f;
+#pragma unroll
+          for (int x = 0; x < 16; ++x) sum += fast_exp2(fmaf(acc[b][x], a.scale2, -new_max));
+          run_sum[b] = run_sum[b] * fast_exp2(run_max[b] - new_max) + sum;   // per lane half
+          run_max[b] = new_max;
+        }
+      } else {
+        // lane: key l32 of block kb; registers: rows 8(x/4) + 4 lhi + x%4 of row block b
+        float part = 0.f;
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
 #pragma unroll
           for (int x = 0; x < 16; ++x) {
-            float2 st = St[wave * 32 + 8 * (x >> 2) + 4 * lhi + (x & 3)];
-            part += exp2f(acc[b][x] * a.scale2 - st.x) * st.y;    // st.y = 0 for rows beyond Mg
+            const float2 st = St[wave * 64 + b * 32 + 8 * (x >> 2) + 4 * lhi + (x & 3)];
+            part += fast_exp2(fmaf(acc[b][x], a.scale2, -st.x)) * st.y;
           }
-          colsum[b] += part;
-        }
+        colsum[kb] += part;
+      }
+    }
+    if (PASS == 0) {
+#pragma unroll
+      for (int b = 0; b < 2; ++b) {
+        const float z = halves_sum(run_sum[b]);
+        if (lhi == 0 && rb0 + b * 32 + l32 < Mg)
+          a.part[(size_t)blockIdx.x * a.total_rows + row_id[b]] = make_float2(run_max[b], z);
       }
     }
   }
   if (PASS == 1) {
 #pragma unroll
-    for (int b = 0; b < 2; ++b) {
-      float v = colsum[b] + __shfl_xor(colsum[b], 32, 64);
-      if (lhi == 0) red[wave][b * 32 + l32] = v;
+    for (int kb = 0; kb < 8; ++kb) {
+      const float v = halves_sum(colsum[kb]);
+      if (lhi == 0) red[wave * kTileKeysMfma + kb * 32 + l32] = v;
     }
     __syncthreads();
-    if (tid < kTileKeys && i0 + tid < N)
-      a.scores[s + i0 + tid] = (red[0][tid] + red[1][tid]) + (red[2][tid] + red[3][tid]);
+    const int key = i0 + tid;
+    if (key < N)
+      a.part_scores[(size_t)g * a.T + s + key] = (red[tid] + red[kTileKeysMfma + tid]) +
+                                                 (red[2 * kTileKeysMfma + tid] + red[3 * kTileKeysMfma + tid]);
   }
+}
+
+// scores[t] = sum over KV heads of the partial scores, in head order; question rows get -inf
+__global__ void __launch_bounds__(256)
+scores_head_sum_kernel(scores_args a, const int *__restrict__ tok_chunk) {
+  const int t = blockIdx.x * 256 + threadIdx.x;
+  if (t >= a.T) return;
+  float v = -INFINITY;
+  if (tok_chunk[t] >= 0) {
+    v = 0.f;
+    for (int g = 0; g < a.Hkv; ++g) v += a.part_scores[(size_t)g * a.T + t];
+  }
+  a.scores[t] = v;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -268,11 +318,15 @@ scores_f32_kernel(scores_args a) {
 
 }  // namespace
 
+static int scores_tile_keys(const a3_layout *L) { return L->dtype == A3_BF16 ? kTileKeysMfma : kTileKeys; }
+
 size_t a3_scores_ws_bytes(const a3_layout *L) {
   // rows of the score matrix over the whole batch are bounded by n_req * max_q_len * Hq
-  size_t total_rows = (size_t)L->n_req * L->max_q_len * L->n_q_heads;
-  size_t n_tiles = (size_t)(L->max_ctx_len + kTileKeys - 1) / kTileKeys;
-  return a3_align_up(n_tiles * total_rows * sizeof(float2), 256) + a3_align_up(total_rows * sizeof(float2), 256) + 256;
+  const size_t total_rows = (size_t)L->n_req * L->max_q_len * L->n_q_heads;
+  const int tk = scores_tile_keys(L);
+  const size_t n_tiles = (size_t)(L->max_ctx_len + tk - 1) / tk;
+  return a3_align_up(n_tiles * total_rows * sizeof(float2), 256) + a3_align_up(total_rows * sizeof(float2), 256) +
+         a3_align_up((size_t)L->n_kv_heads * L->total_tokens * sizeof(float), 256) + 256;
 }
 
 extern "C" a3_status a3_question_scores(const a3_layout *L, const void *q_question, const void *k_fused, float *scores,
@@ -285,30 +339,42 @@ extern "C" a3_status a3_question_scores(const a3_layout *L, const void *q_questi
   A3_REQUIRE(ws != nullptr, A3_ERR_WORKSPACE, "a3_question_scores: workspace is NULL");
   A3_REQUIRE(ws_bytes >= a3_scores_ws_bytes(L), A3_ERR_WORKSPACE,
              "a3_question_scores: workspace %zu bytes, need %zu", ws_bytes, a3_scores_ws_bytes(L));
+  A3_REQUIRE(L->max_ctx_len > 0 && L->max_q_len > 0, A3_ERR_UNSUPPORTED,
+             "a3_question_scores: needs max_ctx_len > 0 and max_q_len > 0");
   hipStream_t st = (hipStream_t)stream;
   const size_t total_rows = (size_t)L->n_req * L->max_q_len * L->n_q_heads;   // upper bound, used as row pitch
-  const int n_tiles = (L->max_ctx_len + kTileKeys - 1) / kTileKeys;
+  const int tk = scores_tile_keys(L);
+  const int n_tiles = (L->max_ctx_len + tk - 1) / tk;
   a3_ws_cursor cur(ws, ws_bytes);
   scores_args a;
   a.q = q_question; a.k = k_fused;
   a.seg_start = L->seg_start; a.ctx_len = L->ctx_len; a.q_len = L->q_len; a.q_start = L->q_start;
   a.part = (float2 *)cur.take((size_t)n_tiles * total_rows * sizeof(float2));
   a.stats = (float2 *)cur.take(total_rows * sizeof(float2));
+  a.part_scores = (float *)cur.take((size_t)L->n_kv_heads * L->total_tokens * sizeof(float));
   a.scores = scores;
   a.n_req = L->n_req; a.Hq = L->n_q_heads; a.Hkv = L->n_kv_heads; a.d = L->head_dim; a.T = L->total_tokens;
-  a.total_rows = (int)total_rows; a.n_tiles = n_tiles;
+  a.total_rows = (int)total_rows; a.n_tiles = n_tiles; a.tile_keys = tk;
   a.scale2 = a3_scale_of(L) * kLog2e;
-  if (n_tiles == 0 || L->max_q_len == 0) {
-    // nothing to score with: every context row gets 0 through pass B's early exit; not supported
-    return a3_fail(A3_ERR_UNSUPPORTED, "a3_question_scores: needs max_ctx_len > 0 and max_q_len > 0");
-  }
-  dim3 grid(n_tiles, L->n_req);
   dim3 cgrid((unsigned)((total_rows + 31) / 32));
   if (L->dtype == A3_BF16) {
-    hipLaunchKernelGGL(scores_bf16_kernel<0>, grid, dim3(256), 0, st, a);
+    static bool attr_done = false;
+    if (!attr_done) {
+      hipError_t e0 = hipFuncSetAttribute((const void *)scores_bf16_kernel<0>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                          (int)kScoresLds);
+      hipError_t e1 = hipFuncSetAttribute((const void *)scores_bf16_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                          (int)kScoresLds);
+      if (e0 != hipSuccess || e1 != hipSuccess)
+        return a3_fail(A3_ERR_HIP, "a3_question_scores: cannot raise the dynamic LDS limit");
+      attr_done = true;
+    }
+    dim3 grid(n_tiles, L->n_kv_heads, L->n_req);
+    hipLaunchKernelGGL(scores_bf16_kernel<0>, grid, dim3(256), kScoresLds, st, a);
     hipLaunchKernelGGL(scores_combine_kernel, cgrid, dim3(256), 0, st, a);
-    hipLaunchKernelGGL(scores_bf16_kernel<1>, grid, dim3(256), 0, st, a);
+    hipLaunchKernelGGL(scores_bf16_kernel<1>, grid, dim3(256), kScoresLds, st, a);
+    hipLaunchKernelGGL(scores_head_sum_kernel, dim3((L->total_tokens + 255) / 256), dim3(256), 0, st, a, L->tok_chunk);
   } else {
+    dim3 grid(n_tiles, L->n_req);
     hipLaunchKernelGGL(scores_f32_kernel<0>, grid, dim3(256), 0, st, a);
     hipLaunchKernelGGL(scores_combine_kernel, cgrid, dim3(256), 0, st, a);
     hipLaunchKernelGGL(scores_f32_kernel<1>, grid, dim3(256), 0, st, a);

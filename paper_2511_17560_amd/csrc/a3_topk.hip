@@ -36,9 +36,28 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int *wave_tot /* [kWa
   return before + inc - v;
 }
 
+// Adds one to hist[bin] for every active lane.  Lanes of a wave that hit the same bin are merged
+// into a single LDS atomic (the top byte of the scores takes only a handful of values, and
+// thousands of same-address atomics would serialise).
+__device__ __forceinline__ void hist_add_merged(uint32_t *hist, uint32_t bin, bool active) {
+  unsigned long long todo = __ballot(active);
+  const int lane = threadIdx.x & 63;
+  while (todo) {
+    const int leader = __ffsll(todo) - 1;
+    const uint32_t lbin = __shfl(bin, leader, 64);
+    const unsigned long long same = __ballot(active && bin == lbin);
+    if (lane == leader) atomicAdd(&hist[lbin], (uint32_t)__popcll(same));
+    todo &= ~same;
+  }
+}
+
+// USE_LDS: the order-preserving keys of the request are staged once in LDS (needs 4 bytes per
+// context row); otherwise every pass re-reads the scores from global memory.
+template <bool USE_LDS>
 __global__ void __launch_bounds__(kBlock)
 topk_select_kernel(const float *__restrict__ scores, const int *__restrict__ seg_start,
                    const int *__restrict__ ctx_len, const int *__restrict__ sel_start, int *__restrict__ sel_idx) {
+  extern __shared__ uint32_t keys[];                         // [N] when USE_LDS
   __shared__ uint32_t hist[256];
   __shared__ int wave_tot[kWaves];
   __shared__ uint32_t sh_bin, sh_need;
@@ -51,15 +70,27 @@ topk_select_kernel(const float *__restrict__ scores, const int *__restrict__ seg
   if (k <= 0) return;                    // uniform over the workgroup
   int *__restrict__ out = sel_idx + sel_start[r];
   const float *__restrict__ sc = scores + s;
+  // one pad word per 32 keys: the compaction reads a contiguous run per lane, and without the pad
+  // the runs of all lanes would start in the same two LDS banks
+  auto key_at = [&](int i) -> uint32_t { return USE_LDS ? keys[i + (i >> 5)] : score_key(sc[i]); };
+
+  if (USE_LDS) {
+    for (int i = tid; i < N; i += kBlock) keys[i + (i >> 5)] = score_key(sc[i]);
+    __syncthreads();
+  }
 
   // ---- radix select: key of the k-th largest score -------------------------------------
   uint32_t prefix = 0, mask = 0, need = (uint32_t)k;
   for (int shift = 24; shift >= 0; shift -= 8) {
     if (tid < 256) hist[tid] = 0;
     __syncthreads();
-    for (int i = tid; i < N; i += kBlock) {
-      uint32_t u = score_key(sc[i]);
-      if ((u & mask) == prefix) atomicAdd(&hist[(u >> shift) & 255u], 1u);
+    const int n_round = (N + kBlock - 1) / kBlock * kBlock;  // whole waves take part in the merged add
+    for (int i = tid; i < n_round; i += kBlock) {
+      const uint32_t u = i < N ? key_at(i) : 0u;
+      const bool active = i < N && (u & mask) == prefix;
+      const uint32_t bin = (u >> shift) & 255u;
+      if (shift == 24) hist_add_merged(hist, bin, active);
+      else if (active) atomicAdd(&hist[bin], 1u);
     }
     __syncthreads();
     if (tid < 64) {
@@ -93,7 +124,7 @@ topk_select_kernel(const float *__restrict__ scores, const int *__restrict__ seg
   const int lo = min(N, tid * per), hi = min(N, lo + per);
   int cnt_gt = 0, cnt_eq = 0;
   for (int i = lo; i < hi; ++i) {
-    uint32_t u = score_key(sc[i]);
+    uint32_t u = key_at(i);
     cnt_gt += u > tau;
     cnt_eq += u == tau;
   }
@@ -102,11 +133,13 @@ topk_select_kernel(const float *__restrict__ scores, const int *__restrict__ seg
   take_eq = take_eq < 0 ? 0 : (take_eq > cnt_eq ? cnt_eq : take_eq);
   int pos = block_exclusive_scan(cnt_gt + take_eq, wave_tot);
   for (int i = lo; i < hi; ++i) {
-    uint32_t u = score_key(sc[i]);
+    uint32_t u = key_at(i);
     if (u > tau) out[pos++] = s + i;
     else if (u == tau && take_eq > 0) { out[pos++] = s + i; --take_eq; }
   }
 }
+
+constexpr int kMaxLdsKeys = 36 * 1024;   // 148.5 KB of padded keys next to the small static arrays
 
 }  // namespace
 
@@ -121,8 +154,21 @@ extern "C" a3_status a3_topk_select(const a3_layout *L, const float *scores, con
   A3_REQUIRE(scores && sel_start, A3_ERR_INVALID_ARG, "a3_topk_select: scores/sel_start is NULL");
   if (total_k == 0) return A3_OK;
   A3_REQUIRE(sel_idx, A3_ERR_INVALID_ARG, "a3_topk_select: sel_idx is NULL");
-  hipLaunchKernelGGL(topk_select_kernel, dim3(L->n_req), dim3(kBlock), 0, (hipStream_t)stream, scores, L->seg_start,
-                     L->ctx_len, sel_start, sel_idx);
+  if (L->max_ctx_len <= kMaxLdsKeys) {
+    const size_t lds = ((size_t)L->max_ctx_len + L->max_ctx_len / 32 + 1) * sizeof(uint32_t);
+    static size_t attr_bytes = 0;
+    if (lds > attr_bytes) {
+      hipError_t e = hipFuncSetAttribute((const void *)topk_select_kernel<true>,
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)((kMaxLdsKeys + kMaxLdsKeys / 32 + 1) * sizeof(uint32_t)));
+      if (e != hipSuccess) return a3_fail(A3_ERR_HIP, "a3_topk_select: %s", hipGetErrorString(e));
+      attr_bytes = kMaxLdsKeys * sizeof(uint32_t);
+    }
+    hipLaunchKernelGGL(topk_select_kernel<true>, dim3(L->n_req), dim3(kBlock), lds, (hipStream_t)stream, scores,
+                       L->seg_start, L->ctx_len, sel_start, sel_idx);
+  } else {
+    hipLaunchKernelGGL(topk_select_kernel<false>, dim3(L->n_req), dim3(kBlock), 0, (hipStream_t)stream, scores,
+                       L->seg_start, L->ctx_len, sel_start, sel_idx);
+  }
   A3_CHECK_LAUNCH("a3_topk_select");
   return A3_OK;
 }

@@ -39,12 +39,14 @@ def _workload(name):
         return synth.custom(SMALL_BF16_HALF, [[130, 70], [33], [257, 64, 90]], [5, 33, 12], ratio=(20, 100), seed=42)
     if name == "g7-bf16":
         return synth.custom(SMALL_G7, [[200, 150, 93]], [9], ratio=(25, 100), seed=43)
+    if name == "long-bf16":      # visible keys beyond 1.5 x 4096: tiles are cut into key segments and merged
+        return synth.custom(SMALL_BF16, [[3000, 2500, 2100]], [40], ratio=(10, 100), n_planted=4, seed=45)
     if name == "batched-f32-d128":
         return synth.custom(SMALL_F32_D128, [[40, 77], [129]], [7, 3], ratio=(30, 100), seed=44)
     raise KeyError(name)
 
 
-NAMES = ["cfg1", "cfg1-half", "ragged-bf16", "batched-bf16-half", "g7-bf16", "batched-f32-d128", "cfg2"]
+NAMES = ["cfg1", "cfg1-half", "ragged-bf16", "batched-bf16-half", "g7-bf16", "batched-f32-d128", "cfg2", "long-bf16"]
 _cache = {}
 
 
@@ -224,6 +226,23 @@ def test_fused_attention(name):
     assert max_abs_rel(to_host(out), res["out"]) <= tol(w)
 
 
+@pytest.mark.parametrize("seg", ["256", "512"])
+@pytest.mark.parametrize("name", ["ragged-bf16", "batched-bf16-half", "g7-bf16", "cfg2"])
+def test_fused_attention_with_short_key_segments(name, seg, monkeypatch):
+    """Forces the split of tiles into key segments (normally only beyond ~6K visible keys) on the
+    small workloads: partial results, rows that see nothing of a later segment, ordered merge."""
+    monkeypatch.setenv("A3_ATTN_SEG", seg)
+    c = ctx_of(name)
+    w, res, lay = c["w"], c["res"], c["lay"]
+    s = w.shape
+    act = res["act_idx"]
+    out = torch.zeros((len(act), s.n_q_heads, s.head_dim), dtype=torch.bfloat16, device="cuda")
+    ws = lay.workspace(len(act))
+    api.a3_fused_attention(lay, to_dev(res["q_act"], "bf16"), idev(act), len(act), to_dev(res["k_fused"], "bf16"),
+                           to_dev(res["v_fused"], "bf16"), out, ws)
+    assert max_abs_rel(to_host(out), res["out"]) <= tol(w)
+
+
 @pytest.mark.parametrize("name", NAMES)
 def test_chained_layer(name):
     """All steps on the GPU's own intermediates.  The selected set must equal the oracle's up to
@@ -267,3 +286,39 @@ def test_chained_layer(name):
     stale = np.setdiff1d(np.arange(w.total_tokens), np.union1d(got_act, want_act))
     assert max_abs_rel(to_host(bufs.k_fused)[stale], res["k_fused"][stale]) <= (1e-5 if dt == "f32" else 2.0 ** -7)
     assert np.array_equal(to_host(v_cache)[stale], res["v_fused"][stale])
+
+
+@pytest.mark.parametrize("case", ["ties", "all-equal", "k-zero-and-full", "long-global-path", "negatives"])
+def test_topk_select_edge_cases(case):
+    """Top-p on hand-made score arrays, bit-exact against the oracle: heavy ties across the cut,
+    all-equal scores (lowest rows win), k = 0 and k = N per request, a request longer than the
+    LDS-staged limit (global re-read path), and scores of both signs with +-0."""
+    rng = np.random.default_rng(99)
+    shape = synth.ModelShape("topk", "f32", 32, 1, 1, 64, 1e4)
+    if case == "long-global-path":
+        w = synth.custom(shape, [[20000, 20001], [777]], [3, 2], ratio=(10, 100))
+    elif case == "k-zero-and-full":
+        w = synth.custom(shape, [[300], [1025, 40], [64]], [2, 2, 2], ratio=(100, 100))
+    else:
+        w = synth.custom(shape, [[1500, 900], [3000]], [4, 1], ratio=(15, 100))
+    T = w.total_tokens
+    if case == "all-equal":
+        sc = np.full(T, 0.25, np.float32)
+    elif case == "ties":
+        sc = (rng.integers(0, 12, size=T) / 16.0).astype(np.float32)
+    elif case == "negatives":
+        sc = rng.standard_normal(T).astype(np.float32)
+        sc[::7] = 0.0
+        sc[3::11] = -0.0
+    else:
+        sc = rng.random(T).astype(np.float32) * np.exp(rng.uniform(-8, 3, T)).astype(np.float32)
+    sc[w.question_rows()] = -np.inf
+    sel_start = w.sel_start.copy()
+    if case == "k-zero-and-full":
+        sel_start = np.array([0, 0, 0 + w.ctx_len[1], w.ctx_len[1] + 1], np.int32)   # k = 0, N, 1
+    want = ora.topk_select(sc, w.seg_start, w.ctx_len, sel_start)
+    lay = api.Layout.from_workload(w)
+    total_k = int(sel_start[-1])
+    sel = torch.full((max(total_k, 1),), -1, dtype=torch.int32, device="cuda")
+    api.a3_topk_select(lay, torch.from_numpy(sc).cuda(), idev(sel_start), total_k, sel)
+    assert np.array_equal(sel.cpu().numpy()[:total_k], want)
