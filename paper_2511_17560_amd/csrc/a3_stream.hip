@@ -87,11 +87,12 @@ __global__ void __launch_bounds__(kBlock)
 rope_realign_kernel(const T *k_cat, T *k_fused,   /* may alias: each item reads its own elements first */
                     const int *__restrict__ tok_chunk,
                     const float2 *__restrict__ chunk_cs, int T_rows, int head_dim, int row_elems,
-                    int items_per_row) {
+                    int items_per_row, int items_shift /* log2(items_per_row) or -1 */) {
   constexpr int VEC = a3_elem<T>::kVec;
   const int half = head_dim >> 1;
-  const long long total = (long long)T_rows * items_per_row;
-  const long long base = ((long long)blockIdx.x * UNROLL) * kBlock + threadIdx.x;
+  // 32-bit indexing (the host checks T_rows * items_per_row < 2^31): 64-bit division is emulated
+  const unsigned total = (unsigned)T_rows * (unsigned)items_per_row;
+  const unsigned base = (blockIdx.x * UNROLL) * kBlock + threadIdx.x;
 
   uint4 va[UNROLL], vb[UNROLL];
   int chunk[UNROLL];
@@ -99,10 +100,11 @@ rope_realign_kernel(const T *k_cat, T *k_fused,   /* may alias: each item reads 
   int pair0[UNROLL];
 #pragma unroll
   for (int u = 0; u < UNROLL; ++u) {
-    long long gid = base + (long long)u * kBlock;
+    const unsigned gid = base + u * kBlock;
     chunk[u] = -1;
     if (gid < total) {
-      int t = (int)(gid / items_per_row), j = (int)(gid % items_per_row);
+      const int t = items_shift >= 0 ? (int)(gid >> items_shift) : (int)(gid / (unsigned)items_per_row);
+      const int j = (int)(gid - (unsigned)t * (unsigned)items_per_row);
       chunk[u] = tok_chunk[t];
       if (LAYOUT == A3_ROPE_INTERLEAVED) {
         int e = j * VEC;                       // element inside the row
@@ -159,19 +161,21 @@ rope_realign_kernel(const T *k_cat, T *k_fused,   /* may alias: each item reads 
 template <int UNROLL>
 __global__ void __launch_bounds__(kBlock)
 kv_scatter_kernel(const uint4 *__restrict__ k_new, const uint4 *__restrict__ v_new, const int *__restrict__ row_idx,
-                  int n_rows, int vec_per_row, uint4 *__restrict__ k_fused, uint4 *__restrict__ v_fused) {
+                  int n_rows, int vec_per_row, int vec_shift /* log2(vec_per_row) or -1 */,
+                  uint4 *__restrict__ k_fused, uint4 *__restrict__ v_fused) {
   const uint4 *src = blockIdx.y == 0 ? k_new : v_new;
   uint4 *dst = blockIdx.y == 0 ? k_fused : v_fused;
-  const long long total = (long long)n_rows * vec_per_row;
-  const long long base = ((long long)blockIdx.x * UNROLL) * kBlock + threadIdx.x;
+  const unsigned total = (unsigned)n_rows * (unsigned)vec_per_row;     // < 2^31, checked on the host
+  const unsigned base = (blockIdx.x * UNROLL) * kBlock + threadIdx.x;
   uint4 v[UNROLL];
   long long dsto[UNROLL];
 #pragma unroll
   for (int u = 0; u < UNROLL; ++u) {
-    long long gid = base + (long long)u * kBlock;
+    const unsigned gid = base + u * kBlock;
     dsto[u] = -1;
     if (gid < total) {
-      int i = (int)(gid / vec_per_row), j = (int)(gid % vec_per_row);
+      const int i = vec_shift >= 0 ? (int)(gid >> vec_shift) : (int)(gid / (unsigned)vec_per_row);
+      const int j = (int)(gid - (unsigned)i * (unsigned)vec_per_row);
       v[u] = src[gid];
       dsto[u] = (long long)row_idx[i] * vec_per_row + j;
     }
@@ -211,10 +215,12 @@ a3_status launch_realign(const a3_layout *L, const void *k_cat, void *k_fused, h
   const bool inter = L->rope_layout == A3_ROPE_INTERLEAVED;
   const int items_per_row = inter ? row_elems / VEC : row_elems / (2 * VEC);
   const long long total = (long long)L->total_tokens * items_per_row;
+  A3_REQUIRE(total < (1LL << 31), A3_ERR_UNSUPPORTED, "a3_rope_realign: cache too large for 32-bit indexing");
   const unsigned grid = (unsigned)((total + (long long)kBlock * UNROLL - 1) / ((long long)kBlock * UNROLL));
+  const int items_shift = (items_per_row & (items_per_row - 1)) == 0 ? __builtin_ctz(items_per_row) : -1;
   auto fn = inter ? rope_realign_kernel<T, A3_ROPE_INTERLEAVED, UNROLL> : rope_realign_kernel<T, A3_ROPE_HALF, UNROLL>;
   hipLaunchKernelGGL(fn, dim3(grid), dim3(kBlock), 0, st, (const T *)k_cat, (T *)k_fused, L->tok_chunk,
-                     (const float2 *)L->rope_chunk_cs, L->total_tokens, L->head_dim, row_elems, items_per_row);
+                     (const float2 *)L->rope_chunk_cs, L->total_tokens, L->head_dim, row_elems, items_per_row, items_shift);
   A3_CHECK_LAUNCH("a3_rope_realign");
   return A3_OK;
 }
@@ -265,10 +271,12 @@ extern "C" a3_status a3_kv_scatter(const a3_layout *L, const void *k_new, const 
   const int esz = L->dtype == A3_BF16 ? 2 : 4;
   const int vec_per_row = L->n_kv_heads * L->head_dim * esz / 16;
   const long long total = (long long)n_rows * vec_per_row;
+  A3_REQUIRE(total < (1LL << 31), A3_ERR_UNSUPPORTED, "a3_kv_scatter: too many rows for 32-bit indexing");
   const unsigned grid = (unsigned)((total + (long long)kBlock * UNROLL - 1) / ((long long)kBlock * UNROLL));
+  const int vec_shift = (vec_per_row & (vec_per_row - 1)) == 0 ? __builtin_ctz(vec_per_row) : -1;
   hipLaunchKernelGGL(kv_scatter_kernel<UNROLL>, dim3(grid, 2), dim3(kBlock), 0, (hipStream_t)stream,
-                     (const uint4 *)k_new, (const uint4 *)v_new, row_idx, n_rows, vec_per_row, (uint4 *)k_fused,
-                     (uint4 *)v_fused);
+                     (const uint4 *)k_new, (const uint4 *)v_new, row_idx, n_rows, vec_per_row, vec_shift,
+                     (uint4 *)k_fused, (uint4 *)v_fused);
   A3_CHECK_LAUNCH("a3_kv_scatter");
   return A3_OK;
 }
