@@ -18,17 +18,21 @@ namespace {
 // ---------------------------------------------------------------------------------------
 // bf16 MFMA kernel
 // ---------------------------------------------------------------------------------------
-// Workgroup tile: 2 heads (256 output features) x 64*NTW listed rows, 2*NTW waves as 2 (head) x NTW
-// (64 rows).  A wave owns one head x 64 rows: 4 x 2 accumulator blocks of 32x32.  NTW (2, 3 or 4) is
-// chosen per launch: larger tiles need less L2 traffic per flop, smaller ones fill the 256 CUs better.  The weight tile goes
-// through LDS (each fragment feeds two MFMAs: 0.5 LDS reads per MFMA, which the 128 B/clk LDS
-// can sustain next to the matrix cores); the gathered hidden rows are private to a wave's row
-// range and are read straight from global memory into MFMA operand layout, one k-tile ahead.
+// The 128 B/clk LDS feeds at most one 16-byte fragment read per 32x32x16 MFMA issued on the CU,
+// so a wave has to reuse every fragment several times.  A wave therefore owns one head
+// (128 features = 4 blocks) x 32*TB listed rows (TB = 2, 3 or 4 blocks): (4 + TB) fragment reads
+// per 4*TB MFMAs, accumulators in up to 256 registers, one wave per SIMD.  The workgroup is
+// 2 (heads) x 2 (row halves) waves: 256 features x 64*TB rows, both operands staged through LDS
+// with full 128-byte row segments per 8 lanes.  TB is chosen per launch: larger tiles need less
+// LDS and L2 traffic per flop, smaller ones fill the 256 CUs better.
+// Loads go from global memory straight into LDS (global_load_lds, 16 bytes per lane, no staging
+// registers), three 32-wide k-slabs ahead of the MFMAs in a ring of four LDS stages; rows are
+// unpadded and the 16-byte pieces of a row are XOR-swizzled against bank conflicts.
 constexpr int kHeadDim = 128;
-constexpr int kBK = 64;              // reduction slab per barrier
-constexpr int kWStride = kBK + 8;    // LDS row stride in elements: 144 B, 8 rows cover all 32 banks once
-constexpr int kWPieces = 256 * kBK / 8;   // 16-byte pieces of a weight slab
-constexpr int kWTileElems = 2 * kHeadDim * kWStride;
+constexpr int kBK = 32;              // reduction slab per barrier
+constexpr int kRowBytes = kBK * 2;   // an LDS row is one 64-byte k-slab of a weight or hidden row, unpadded
+constexpr int kStages = 4;           // LDS stages: loads run 3 slabs ahead of the MFMAs
+constexpr size_t proj_lds_bytes(int tb) { return (size_t)kStages * (2 * kHeadDim + 64 * tb) * kRowBytes; }
 
 struct proj_args {
   const bf16_t *hidden;
@@ -43,8 +47,6 @@ struct proj_args {
   int n_pairs, n_tok_tiles;
 };
 
-constexpr size_t proj_lds_bytes(int ntw) { return (size_t)2 * (kWTileElems + 64 * ntw * kWStride) * sizeof(bf16_t); }
-
 struct head_sel { int which, head, heads_out; };
 
 __device__ __forceinline__ head_sel select_head(int h, int Hq, int Hkv) {
@@ -55,17 +57,18 @@ __device__ __forceinline__ head_sel select_head(int h, int Hq, int Hkv) {
   return r;
 }
 
-template <int NTW>
-__global__ void __launch_bounds__(128 * NTW, 1)
+// s_waitcnt immediate that waits until at most n vector-memory operations are outstanding and
+// nothing else (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8)
+constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
+
+template <int TB>
+__global__ void __launch_bounds__(256, 1)
 proj_bf16_kernel(proj_args a) {
-  constexpr int kThreads = 128 * NTW;
-  constexpr int kTokTile = 64 * NTW;
-  constexpr int kWChunks = (kWPieces + kThreads - 1) / kThreads;   // weight pieces per lane
-  constexpr int kXChunks = kTokTile * (kBK / 8) / kThreads;        // hidden-row pieces per lane (= 4)
-  constexpr int kXTileElems = kTokTile * kWStride;
-  extern __shared__ __align__(16) unsigned char lds_raw[];
-  bf16_t *Ws = reinterpret_cast<bf16_t *>(lds_raw);          // [2][256][kWStride]
-  bf16_t *Xs = Ws + 2 * kWTileElems;                         // [2][kTokTile][kWStride]
+  constexpr int kTokTile = 64 * TB;
+  constexpr int kWBytes = 2 * kHeadDim * kRowBytes;          // weight part of a stage: 256 rows
+  constexpr int kStageBytes = kWBytes + kTokTile * kRowBytes;
+  constexpr int kLoads = 4 + TB;                             // direct-to-LDS loads per wave per slab
+  extern __shared__ __align__(16) unsigned char lds[];       // [kStages][256 + 64 TB rows][64 B]
 
   // workgroup -> (head pair, row tile).  Consecutive workgroup ids go to different XCDs; all row
   // tiles of one head pair are kept on one XCD so its L2 holds that pair's weights.
@@ -77,100 +80,126 @@ proj_bf16_kernel(proj_args a) {
   const int l32 = lane & 31, lhi = lane >> 5;
   const int fh = wave & 1, th = wave >> 1;
 
-  // ---- weight staging: a slab is 256 rows x kBK/8 pieces of 16 B; lane takes pieces tid, tid+kThreads, .. --
-  const bf16_t *wsrc[kWChunks];
-  int wdst[kWChunks];
+  // ---- loading roles.  One wave instruction brings 16 rows x 64 B: lane -> (row lane/4, slot lane%4),
+  // and the lane fetches the 16-byte piece (slot ^ swz(row)) of its row, so that LDS slot s of row r
+  // holds piece s ^ swz(r), swz(r) = (r/4) % 4: the 16 consecutive rows that one quarter of a wave
+  // reads at one piece index then touch all 64 LDS banks (256 bytes) exactly once.  Wave w issues weight rows 16 (4 j + w) .. +15 (j = 0..3: two per head)
+  // and hidden rows 16 (4 j + w) .. +15 (j = 0..TB-1).
+  const int lrow = lane >> 2, slot = lane & 3;
+  const int piece = slot ^ ((lrow >> 2) & 3);
+  const char *wsrc[4];
 #pragma unroll
-  for (int i = 0; i < kWChunks; ++i) {
-    int c = min(tid + i * kThreads, kWPieces - 1);           // clamp (384 lanes: the last round is partial)
-    int row = c / (kBK / 8), wc = c % (kBK / 8);
-    int hsel = min(2 * hp + (row >> 7), n_heads - 1);        // rows 0..127: first head, 128..255: second
-    head_sel hs = select_head(hsel, a.Hq, a.Hkv);
-    const bf16_t *wb = a.w[hs.which];
-    if (wb == nullptr) wb = a.w[0] ? a.w[0] : (a.w[1] ? a.w[1] : a.w[2]);   // unused head: any valid tile
-    int hh = a.w[hs.which] ? hs.head : 0;
-    wsrc[i] = wb + ((size_t)hh * kHeadDim + (row & 127)) * a.K + wc * 8;
-    wdst[i] = row * kWStride + wc * 8;
+  for (int j = 0; j < 4; ++j) {
+    const int row = 16 * (4 * j + wave) + lrow;              // 0..255
+    const head_sel hsl = select_head(min(2 * hp + (row >> 7), n_heads - 1), a.Hq, a.Hkv);
+    const bf16_t *wb = a.w[hsl.which];
+    int hh = hsl.head;
+    if (wb == nullptr) { wb = a.w[0] ? a.w[0] : (a.w[1] ? a.w[1] : a.w[2]); hh = 0; }   // unused head: any valid tile
+    wsrc[j] = reinterpret_cast<const char *>(wb + ((size_t)hh * kHeadDim + (row & 127)) * a.K + piece * 8);
   }
+  const char *xsrc[TB];
+#pragma unroll
+  for (int j = 0; j < TB; ++j) {
+    const int row = 16 * (4 * j + wave) + lrow;              // 0..64 TB - 1
+    const int m = min(tt * kTokTile + row, a.n_rows - 1);    // clamp: computed but never stored
+    const int src_row = a.row_idx ? a.row_idx[m] : m;
+    xsrc[j] = reinterpret_cast<const char *>(a.hidden + (size_t)src_row * a.K + piece * 8);
+  }
+  // global_load_lds: lane i's 16 bytes land at (M0 = wave-uniform LDS byte address) + 16 i.  Issued as
+  // inline assembly on purpose: the compiler then neither tracks these as LDS writes (it would put
+  // a full vmcnt(0) in front of every LDS read and undo the lookahead) nor reorders memory accesses
+  // across them; the waits for them are the explicit s_waitcnt below.  M0 is not used by anything
+  // else in this kernel (LDS instructions need no M0 on gfx9 and later).
+  const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds;
+#define A3_DMA(GPTR, LDS_OFF)                                                                                 \
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"                                          \
+               :: "s"(__builtin_amdgcn_readfirstlane(lds_base + (uint32_t)(LDS_OFF))), "v"(GPTR) : "memory")
+#define A3_ISSUE(STAGE, K0)                                                                                   \
+  {                                                                                                           \
+    const uint32_t st_ = (STAGE) * kStageBytes;                                                               \
+    const size_t kb_ = (size_t)(K0) * sizeof(bf16_t);                                                         \
+    _Pragma("unroll") for (int j = 0; j < 4; ++j) A3_DMA(wsrc[j] + kb_, st_ + 16 * (4 * j + wave) * kRowBytes); \
+    _Pragma("unroll") for (int j = 0; j < TB; ++j)                                                            \
+      A3_DMA(xsrc[j] + kb_, st_ + kWBytes + 16 * (4 * j + wave) * kRowBytes);                                 \
+  }
+
   // ---- this wave's head and rows ---------------------------------------------------------------------
   const int my_head = 2 * hp + fh;
   const head_sel hs = select_head(min(my_head, n_heads - 1), a.Hq, a.Hkv);
   bf16_t *__restrict__ out = my_head < n_heads ? a.out[hs.which] : nullptr;
   const bool compute = out != nullptr;
-  const int tok0 = tt * kTokTile + th * 64;
-  // ---- hidden-row staging: 8 lanes fetch one 128-byte segment of a gathered row ---------------------------
-  const bf16_t *xsrc[kXChunks];
-  int xdst[kXChunks];
-#pragma unroll
-  for (int i = 0; i < kXChunks; ++i) {
-    int c = tid + i * kThreads;
-    int row = c >> 3, xc = c & 7;
-    int m = min(tt * kTokTile + row, a.n_rows - 1);          // clamp: computed but never stored
-    int src_row = a.row_idx ? a.row_idx[m] : m;
-    xsrc[i] = a.hidden + (size_t)src_row * a.K + xc * 8;
-    xdst[i] = row * kWStride + xc * 8;
-  }
+  const int tok0 = tt * kTokTile + th * 32 * TB;
+  // fragment addresses: row base + swizzled slot of piece 2 ks + lhi
+  const int swz = (l32 >> 2) & 3;
+  const int frag_w = (fh * kHeadDim + l32) * kRowBytes, frag_x = kWBytes + (th * 32 * TB + l32) * kRowBytes;
+  const int slot_k0 = ((lhi) ^ swz) * 16, slot_k1 = ((2 + lhi) ^ swz) * 16;
 
-  f32x16 acc[4][2];
+  f32x16 acc[4][TB];
 #pragma unroll
   for (int fb = 0; fb < 4; ++fb)
 #pragma unroll
-    for (int tb = 0; tb < 2; ++tb)
+    for (int tb = 0; tb < TB; ++tb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[fb][tb][r] = 0.f;
 
-  uint4 wreg[kWChunks];
-  uint4 xreg[kXChunks];
-#define A3_WLOAD(K0)                                                                     \
-  _Pragma("unroll") for (int i = 0; i < kWChunks; ++i)                                   \
-    wreg[i] = *reinterpret_cast<const uint4 *>(wsrc[i] + (K0));
-#define A3_WSTORE(BUF)                                                                   \
-  _Pragma("unroll") for (int i = 0; i < kWChunks; ++i)                                   \
-    if ((i + 1) * kThreads <= kWPieces || tid + i * kThreads < kWPieces)                 \
-      *reinterpret_cast<uint4 *>(Ws + (BUF) * kWTileElems + wdst[i]) = wreg[i];
-#define A3_XLOAD(K0)                                                                     \
-  _Pragma("unroll") for (int i = 0; i < kXChunks; ++i)                                   \
-    xreg[i] = *reinterpret_cast<const uint4 *>(xsrc[i] + (K0));
-#define A3_XSTORE(BUF)                                                                   \
-  _Pragma("unroll") for (int i = 0; i < kXChunks; ++i)                                   \
-    *reinterpret_cast<uint4 *>(Xs + (BUF) * kXTileElems + xdst[i]) = xreg[i];
-#define A3_COMPUTE(BUF)                                                                                      \
+#define A3_FRAGS(WF, XF, ST, SLOT)                                                                           \
+  {                                                                                                          \
+    _Pragma("unroll") for (int tb = 0; tb < TB; ++tb)                                                        \
+      XF[tb] = *reinterpret_cast<const bf16x8 *>((ST) + frag_x + tb * 32 * kRowBytes + (SLOT));              \
+    _Pragma("unroll") for (int fb = 0; fb < 4; ++fb)                                                         \
+      WF[fb] = *reinterpret_cast<const bf16x8 *>((ST) + frag_w + fb * 32 * kRowBytes + (SLOT));              \
+  }
+#define A3_MFMAS(WF, XF)                                                                                     \
   if (compute) {                                                                                             \
-    const bf16_t *wb = Ws + (BUF) * kWTileElems + (fh * kHeadDim + l32) * kWStride + lhi * 8;               \
-    const bf16_t *xb = Xs + (BUF) * kXTileElems + (th * 64 + l32) * kWStride + lhi * 8;                     \
-    _Pragma("unroll") for (int ks = 0; ks < kBK / 16; ++ks) {                                                \
-      bf16x8 wf[4], xf[2];                                                                                   \
-      _Pragma("unroll") for (int tb = 0; tb < 2; ++tb)                                                       \
-        xf[tb] = *reinterpret_cast<const bf16x8 *>(xb + tb * 32 * kWStride + ks * 16);                       \
-      _Pragma("unroll") for (int fb = 0; fb < 4; ++fb)                                                       \
-        wf[fb] = *reinterpret_cast<const bf16x8 *>(wb + fb * 32 * kWStride + ks * 16);                       \
-      _Pragma("unroll") for (int fb = 0; fb < 4; ++fb)                                                       \
-        _Pragma("unroll") for (int tb = 0; tb < 2; ++tb)                                                     \
-          acc[fb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[fb], xf[tb], acc[fb][tb], 0, 0, 0);       \
-    }                                                                                                        \
+    _Pragma("unroll") for (int fb = 0; fb < 4; ++fb)                                                         \
+      _Pragma("unroll") for (int tb = 0; tb < TB; ++tb)                                                      \
+        acc[fb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(WF[fb], XF[tb], acc[fb][tb], 0, 0, 0);         \
   }
 
-  const int K = a.K;                                          // multiple of 64
-  A3_WLOAD(0)
-  A3_XLOAD(0)
-  A3_WSTORE(0)
-  A3_XSTORE(0)
-  __syncthreads();
-  int buf = 0;
-  for (int k0 = 0; k0 < K; k0 += kBK, buf ^= 1) {
-    const int kn = min(k0 + kBK, K - kBK);                    // next slab (the last one re-reads itself)
-    A3_WLOAD(kn)
-    A3_XLOAD(kn)
-    A3_COMPUTE(buf)
-    A3_WSTORE(buf ^ 1)
-    A3_XSTORE(buf ^ 1)
-    __syncthreads();
+  // ---- main loop: 32-wide k-slabs, kStages LDS stages, loads run kStages-1 slabs ahead ------------------
+  // One wave per SIMD, so LDS latency has to be hidden inside the wave: the fragments of the second
+  // k-step of a slab are read while the MFMAs of the first run, and the fragments of the next slab's
+  // first k-step are read (right after its barrier) while the MFMAs of this slab's second k-step run.
+  const int n_slabs = a.K / kBK;
+  const int k_last = a.K - kBK;
+#pragma unroll
+  for (int s0 = 0; s0 < kStages - 1; ++s0) A3_ISSUE(s0, min(s0 * kBK, k_last))
+  bf16x8 wf0[4], xf0[TB], wf1[4], xf1[TB];
+  __builtin_amdgcn_s_waitcnt(vmcnt_imm((kStages - 2) * kLoads));   // this wave's loads of slab 0 have landed
+  __builtin_amdgcn_s_barrier();                                     // ... and everybody's
+  A3_ISSUE(kStages - 1, min((kStages - 1) * kBK, k_last))
+  A3_FRAGS(wf0, xf0, lds, slot_k0)
+  for (int sl = 0; sl < n_slabs; ++sl) {
+    const unsigned char *st = lds + (sl % kStages) * kStageBytes;
+    A3_FRAGS(wf1, xf1, st, slot_k1)
+    A3_MFMAS(wf0, xf0)
+    // Slab sl+1: this wave's loads have landed once only the 2 younger slabs are outstanding, and
+    // after the barrier everybody's have.  The barrier also says that every wave has fetched its last
+    // fragments of slab sl (lgkmcnt(0) first), whose stage the loads issued next will overwrite.
+    // (Bare barrier: a fence here would wait for the loads in flight.)
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm((kStages - 2) * kLoads) & ~(15 << 8));
+    __builtin_amdgcn_s_barrier();
+    const unsigned char *sn = lds + ((sl + 1) % kStages) * kStageBytes;
+    A3_FRAGS(wf0, xf0, sn, slot_k0)                             // past the last slab: re-reads a stale stage, unused
+    // the loads of slab sl+4 are spread between the MFMAs instead of hitting the address unit in
+    // one burst from all four waves right after the barrier
+    {
+      const uint32_t st_ = ((sl + kStages) % kStages) * kStageBytes;
+      const size_t kb_ = (size_t)min((sl + kStages) * kBK, k_last) * sizeof(bf16_t);
+#pragma unroll
+      for (int i = 0; i < 4 * TB; ++i) {
+        const int fb = i / TB, tb = i % TB;
+        if (compute) acc[fb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf1[fb], xf1[tb], acc[fb][tb], 0, 0, 0);
+        if (i < 4) A3_DMA(wsrc[i] + kb_, st_ + 16 * (4 * i + wave) * kRowBytes);
+        else if (i < kLoads) A3_DMA(xsrc[i - 4] + kb_, st_ + kWBytes + 16 * (4 * (i - 4) + wave) * kRowBytes);
+      }
+    }
   }
-#undef A3_WLOAD
-#undef A3_WSTORE
-#undef A3_XLOAD
-#undef A3_XSTORE
-#undef A3_COMPUTE
+  __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));                   // drain the tail loads before LDS is released
+#undef A3_DMA
+#undef A3_ISSUE
+#undef A3_FRAGS
+#undef A3_MFMAS
   if (!compute) return;
 
   // ---- epilogue: bias, RoPE, one rounding, store -------------------------------------------------------
@@ -180,7 +209,7 @@ proj_bf16_kernel(proj_args a) {
   const int fq = lhi * 4;
   const bf16_t *bias = a.bias[which];
 #pragma unroll
-  for (int tb = 0; tb < 2; ++tb) {
+  for (int tb = 0; tb < TB; ++tb) {
     const int tok = tok0 + tb * 32 + l32;
     if (tok >= a.n_rows) continue;
     if (bias) {
@@ -451,6 +480,8 @@ extern "C" a3_status a3_selected_qkv_proj(const a3_layout *L, const void *hidden
   if (L->dtype == A3_BF16) {
     A3_REQUIRE(L->hidden % 64 == 0, A3_ERR_UNSUPPORTED, "a3_selected_qkv_proj: bf16 needs hidden %% 64 == 0, got %d",
                L->hidden);
+    A3_REQUIRE((long long)L->total_tokens * L->hidden * 2 < (1LL << 32), A3_ERR_UNSUPPORTED,
+               "a3_selected_qkv_proj: hidden tensor larger than 4 GiB");
     proj_args a;
     a.hidden = (const bf16_t *)hidden; a.row_idx = row_idx; a.n_rows = n_rows;
     a.w[0] = (const bf16_t *)wq; a.w[1] = (const bf16_t *)wk; a.w[2] = (const bf16_t *)wv;
@@ -497,8 +528,8 @@ extern "C" a3_status a3_selected_qkv_proj(const a3_layout *L, const void *hidden
       attr_done = true;
     }
     if (ntw == 2) hipLaunchKernelGGL(proj_bf16_kernel<2>, dim3(grid), dim3(256), proj_lds_bytes(2), st, a);
-    else if (ntw == 3) hipLaunchKernelGGL(proj_bf16_kernel<3>, dim3(grid), dim3(384), proj_lds_bytes(3), st, a);
-    else hipLaunchKernelGGL(proj_bf16_kernel<4>, dim3(grid), dim3(512), proj_lds_bytes(4), st, a);
+    else if (ntw == 3) hipLaunchKernelGGL(proj_bf16_kernel<3>, dim3(grid), dim3(256), proj_lds_bytes(3), st, a);
+    else hipLaunchKernelGGL(proj_bf16_kernel<4>, dim3(grid), dim3(256), proj_lds_bytes(4), st, a);
   } else {
     proj_args_f32 a;
     a.hidden = (const float *)hidden; a.row_idx = row_idx; a.n_rows = n_rows;
