@@ -27,11 +27,11 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr int kD = 128;
 constexpr int kTM = 128;            // packed (row, head) pairs per work item: 4 waves x 32
 constexpr int kTK = 64;             // keys per tile
-constexpr int kKStride = kD + 8;    // K tile  [key][d]   row stride in elements (272 B)
+constexpr int kKRowBytes = kD * 2;   // K tile  [key][d]   256-byte rows, unpadded; 16-byte pieces XOR-swizzled by key % 16
 constexpr int kVStride = kTK + 8;   // V^T tile [d][key]  row stride in elements (144 B)
-constexpr int kKTile = kTK * kKStride;
+constexpr int kKTile = kTK * kD;     // elements
 constexpr int kVTile = kD * kVStride;
-constexpr size_t kAttnLds = (size_t)2 * (kKTile + kVTile) * sizeof(bf16_t);   // double buffered: 71680 B
+constexpr size_t kAttnLds = (size_t)2 * (kKTile + kVTile) * sizeof(bf16_t);   // double buffered: 69632 B
 constexpr int kPlanThreads = 1024;
 
 // Work decomposition written by the plan kernel.
@@ -47,7 +47,7 @@ struct attn_plan {
   int4 *items;       // [max_items] (tile, k_begin, k_end, segment) - longest tiles first
   int *counters;     // [Hkv] work queue heads, then n_tiles, n_items
   float *part_o;     // [Hkv * max_items][128][128] unnormalised partial O of cut tiles
-  float2 *part_ml;   // [Hkv * max_items][128]      (max in the exp2 domain, sum)
+  float2 *part_ml;   // [Hkv * max_items][128]      (exponent reference in the exp2 domain, sum)
   int max_tiles, max_items, seg_len;
 };
 
@@ -164,7 +164,7 @@ __device__ __forceinline__ uint32_t pack_hi(uint32_t a, uint32_t b) { return (a 
 __global__ void __launch_bounds__(256, 2)
 attn_bf16_kernel(attn_args a) {
   extern __shared__ __align__(16) unsigned char lds_raw[];
-  bf16_t *Ks = reinterpret_cast<bf16_t *>(lds_raw);          // [2][64][kKStride]
+  bf16_t *Ks = reinterpret_cast<bf16_t *>(lds_raw);          // [2][64][128], swizzled
   bf16_t *Vt = Ks + 2 * kKTile;                              // [2][128][kVStride]
   __shared__ int sh_item;
 
@@ -178,8 +178,16 @@ attn_bf16_kernel(attn_args a) {
   const bf16_t *__restrict__ V = (const bf16_t *)a.v;
   const float c2 = a.scale2;
 
-  // staging roles.  K tile: 16 lanes per 256-byte row, 4 rows per lane.  V tile: lane = (4 keys, 8 dims).
-  const int kc = tid & 15, kr0 = tid >> 4;
+  // K tile: global memory -> LDS directly (global_load_lds, 16 bytes per lane, lane i lands at base + 16 i).
+  // One wave instruction brings 4 keys x 256 B; instruction j of wave w covers keys 4 (4 j + w) .. +3.
+  // The lane fetches piece (slot ^ key % 16) of its key, so LDS slot s of key r holds piece s ^ (r % 16)
+  // and the 16 keys a quarter wave reads at one piece index touch all 64 banks once.
+  const int drow = 4 * wave + (lane >> 4);                   // key of the lane in instruction 0
+  const int dpiece = (lane & 15) ^ (drow & 15);              // (4 (4 j + w) + lane/16) % 16 does not depend on j
+  const uint32_t lds_k = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds_raw;
+  // fragment read: key b*32 + l32, piece 2 ks + lhi -> slot (2 ks + lhi) ^ (l32 % 16)
+  const int kfrag = l32 * kKRowBytes, kswz = (lhi ^ (l32 & 15)) * 16;
+  // V tile: lane = (4 keys, 8 dims), transposed in registers on its way into LDS.
   // 16 consecutive lanes take 16 different key groups: their 8-byte transposed stores land in 128
   // contiguous bytes of one V^T row (all 32 LDS banks) instead of 16 rows at a bank-aligned stride
   const int vkg = tid & 15, vc = tid >> 4;
@@ -221,27 +229,35 @@ attn_bf16_kernel(attn_args a) {
     for (int b = 0; b < 4; ++b)
 #pragma unroll
       for (int x = 0; x < 16; ++x) o[b][x] = 0.f;
-    float row_max = -INFINITY, row_sum = 0.f;               // row_max in raw logit units
+    float row_ref = -INFINITY, row_sum = 0.f;               // exponent reference in raw logit units
 
     // Next tile staged in registers while the current one is being consumed.  Loads are branch
     // free (rows past the last visible key are clamped onto it and masked later) so that nothing
     // forces the loaded registers to be touched before the LDS store at the end of the iteration.
-    uint4 kr_0, kr_1, kr_2, kr_3, vr_0, vr_1, vr_2, vr_3;
+    uint4 vr_0, vr_1, vr_2, vr_3;
     const uint32_t pitch_b = (uint32_t)a.Hkv * kD * sizeof(bf16_t);
     const char *kb = reinterpret_cast<const char *>(K + ((size_t)base * a.Hkv + g) * kD);
     const char *vb = reinterpret_cast<const char *>(V + ((size_t)base * a.Hkv + g) * kD);
-    const uint32_t k_last = (uint32_t)(kv_len - 1) * pitch_b + kc * 16, v_last = (uint32_t)(kv_len - 1) * pitch_b + vc * 16;
-    const uint32_t ko_0 = (uint32_t)kr0 * pitch_b + kc * 16, ko_1 = ko_0 + 16 * pitch_b, ko_2 = ko_0 + 32 * pitch_b,
-                   ko_3 = ko_0 + 48 * pitch_b;
+    const uint32_t k_last = (uint32_t)(kv_len - 1) * pitch_b + dpiece * 16, v_last = (uint32_t)(kv_len - 1) * pitch_b + vc * 16;
+    const uint32_t ko_0 = (uint32_t)drow * pitch_b + dpiece * 16;
     const uint32_t vo_0 = (uint32_t)(4 * vkg) * pitch_b + vc * 16, vo_1 = vo_0 + pitch_b, vo_2 = vo_0 + 2 * pitch_b,
                    vo_3 = vo_0 + 3 * pitch_b;
+    // Inline assembly on purpose: the compiler then neither treats these as LDS writes (it would wait
+    // for all of them before every LDS read) nor moves memory accesses across them.  They are issued
+    // right after the V loads of the same tile: the hardware counter the compiler waits on before
+    // using the V registers counts them too, so that wait (which ends at zero, just before the
+    // barrier that publishes the tile) covers them; issued before the V loads they would instead
+    // be waited for at the top of the loop, where the compiler guards the reuse of the V registers.
+#define A3_KDMA(BUF, K0)                                                                                     \
+    _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                          \
+      const char *gp_ = kb + min(ko_0 + ((uint32_t)(K0) + 16u * j) * pitch_b, k_last);                       \
+      asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"                                     \
+                   :: "s"(__builtin_amdgcn_readfirstlane(lds_k + (BUF) * (kKTile * 2) + 4 * (4 * j + wave) * kKRowBytes)), \
+                      "v"(gp_) : "memory");                                                                  \
+    }
 #define A3_GLOAD(K0)                                                                       \
     {                                                                                      \
       const uint32_t t_off = (uint32_t)(K0) * pitch_b;                                     \
-      kr_0 = *reinterpret_cast<const uint4 *>(kb + min(ko_0 + t_off, k_last));             \
-      kr_1 = *reinterpret_cast<const uint4 *>(kb + min(ko_1 + t_off, k_last));             \
-      kr_2 = *reinterpret_cast<const uint4 *>(kb + min(ko_2 + t_off, k_last));             \
-      kr_3 = *reinterpret_cast<const uint4 *>(kb + min(ko_3 + t_off, k_last));             \
       vr_0 = *reinterpret_cast<const uint4 *>(vb + min(vo_0 + t_off, v_last));             \
       vr_1 = *reinterpret_cast<const uint4 *>(vb + min(vo_1 + t_off, v_last));             \
       vr_2 = *reinterpret_cast<const uint4 *>(vb + min(vo_2 + t_off, v_last));             \
@@ -256,12 +272,7 @@ attn_bf16_kernel(attn_args a) {
     }
 #define A3_LSTORE(BUF)                                                                                       \
     {                                                                                                        \
-      bf16_t *kd = Ks + (BUF) * kKTile + kr0 * kKStride + kc * 8;                                            \
       bf16_t *vd = Vt + (BUF) * kVTile;                                                                      \
-      *reinterpret_cast<uint4 *>(kd) = kr_0;                                                                 \
-      *reinterpret_cast<uint4 *>(kd + 16 * kKStride) = kr_1;                                                 \
-      *reinterpret_cast<uint4 *>(kd + 32 * kKStride) = kr_2;                                                 \
-      *reinterpret_cast<uint4 *>(kd + 48 * kKStride) = kr_3;                                                 \
       A3_V_TRANSPOSE_STORE(vd, 0, x)                                                                         \
       A3_V_TRANSPOSE_STORE(vd, 1, y)                                                                         \
       A3_V_TRANSPOSE_STORE(vd, 2, z)                                                                         \
@@ -270,13 +281,21 @@ attn_bf16_kernel(attn_args a) {
 
     if (k_begin < k_end) {
       A3_GLOAD(k_begin)
+      A3_KDMA(0, k_begin)
       A3_LSTORE(0)
     }
+    // Everything loaded so far (Q fragments, first tile) has arrived: inside the loop the compiler's
+    // waits then only concern the V registers of the loop itself.  (Its counter arithmetic does not
+    // know about the direct-to-LDS loads; a pending Q load would make it wait for fresh V loads
+    // in the middle of the MFMAs.)
+    __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
     int buf = 0;
     for (int k0 = k_begin; k0 < k_end; k0 += kTK, buf ^= 1) {
+      const bool more = k0 + kTK < k_end;
       A3_GLOAD(k0 + kTK)                                     // next tile: in flight during everything below
-      const bf16_t *kt = Ks + buf * kKTile + l32 * kKStride + lhi * 8;
+      if (more) { A3_KDMA(buf ^ 1, k0 + kTK) }
+      const unsigned char *kt = reinterpret_cast<const unsigned char *>(Ks) + buf * (kKTile * 2) + kfrag;
       const bf16_t *vt = Vt + buf * kVTile + l32 * kVStride + lhi * 8;
 
       // ---- S^T = K Q^T : two 32-key blocks, K fragments read two steps ahead ----------------
@@ -290,13 +309,13 @@ attn_bf16_kernel(attn_args a) {
       for (int pre = 0; pre < 2; ++pre)
 #pragma unroll
         for (int b = 0; b < 2; ++b)
-          kf[pre][b] = *reinterpret_cast<const bf16x8 *>(kt + b * 32 * kKStride + pre * 16);
+          kf[pre][b] = *reinterpret_cast<const bf16x8 *>(kt + b * 32 * kKRowBytes + ((32 * pre) ^ kswz));
 #pragma unroll
       for (int ks = 0; ks < kD / 16; ++ks) {
         if (ks + 2 < kD / 16) {
 #pragma unroll
           for (int b = 0; b < 2; ++b)
-            kf[(ks + 2) % 3][b] = *reinterpret_cast<const bf16x8 *>(kt + b * 32 * kKStride + (ks + 2) * 16);
+            kf[(ks + 2) % 3][b] = *reinterpret_cast<const bf16x8 *>(kt + b * 32 * kKRowBytes + ((32 * (ks + 2)) ^ kswz));
         }
 #pragma unroll
         for (int b = 0; b < 2; ++b)
@@ -325,11 +344,20 @@ attn_bf16_kernel(attn_args a) {
 #pragma unroll
         for (int x = 0; x < 16; ++x) mx = fmaxf(mx, st[b][x]);
       mx = halves_max(mx);
-      const float new_max = fmaxf(row_max, mx);
-      const float ref = new_max == -INFINITY ? 0.f : new_max;   // row with no visible key in this segment yet
-      const float alpha = fast_exp2((row_max - ref) * c2);
-      const float nref = -ref * c2;
-      row_max = new_max;
+      // Lazy rescaling: the exponent reference `row_ref` only has to stay within 2^8 of the running
+      // maximum, not equal to it, so the accumulators are rescaled a handful of times per row
+      // instead of whenever the maximum moves (64 multiplies each time).  P then ranges up to 256.
+      if (__any((mx - row_ref) * c2 > 8.0f)) {              // also true for the first visible key (-inf reference)
+        const float new_ref = fmaxf(row_ref, mx);
+        const float alpha = new_ref == -INFINITY ? 1.0f : fast_exp2((row_ref - new_ref) * c2);
+        row_ref = new_ref;
+        row_sum *= alpha;
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+          for (int x = 0; x < 16; ++x) o[b][x] *= alpha;
+      }
+      const float nref = row_ref == -INFINITY ? 0.f : -row_ref * c2;   // no visible key yet: every P is 0
       float psum = 0.f;
 #pragma unroll
       for (int b = 0; b < 2; ++b)
@@ -339,13 +367,7 @@ attn_bf16_kernel(attn_args a) {
           st[b][x] = pv;
           psum += pv;
         }
-      row_sum = row_sum * alpha + psum;                     // per lane half; halves are added at the end
-      if (!__all(alpha == 1.0f)) {
-#pragma unroll
-        for (int b = 0; b < 4; ++b)
-#pragma unroll
-          for (int x = 0; x < 16; ++x) o[b][x] *= alpha;
-      }
+      row_sum += psum;                                      // per lane half; halves are added at the end
 
       // ---- O^T += V^T P^T, V^T fragments read one step ahead ------------------------------------
 #pragma unroll
@@ -362,9 +384,10 @@ attn_bf16_kernel(attn_args a) {
         for (int db = 0; db < 4; ++db)
           o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[step & 1][db], pf, o[db], 0, 0, 0);
       }
-      if (k0 + kTK < k_end) { A3_LSTORE(buf ^ 1) }
+      if (more) { A3_LSTORE(buf ^ 1) }
       __syncthreads();
     }
+#undef A3_KDMA
 #undef A3_GLOAD
 #undef A3_LSTORE
 #undef A3_V_TRANSPOSE_STORE
@@ -398,7 +421,7 @@ attn_bf16_kernel(attn_args a) {
           for (int e = 0; e < 4; ++e) v[e] = o[db][4 * q4 + e];
           *reinterpret_cast<f32x4 *>(po + 32 * db + 8 * q4 + 4 * lhi) = v;
         }
-      if (lhi == 0) a.plan.part_ml[pidx * kTM + ml] = make_float2(row_max * c2, row_sum);
+      if (lhi == 0) a.plan.part_ml[pidx * kTM + ml] = make_float2(row_ref * c2, row_sum);
     }
   }
 }

@@ -31,8 +31,10 @@ namespace {
 constexpr int kHeadDim = 128;
 constexpr int kBK = 32;              // reduction slab per barrier
 constexpr int kRowBytes = kBK * 2;   // an LDS row is one 64-byte k-slab of a weight or hidden row, unpadded
-constexpr int kStages = 4;           // LDS stages: loads run 3 slabs ahead of the MFMAs
-constexpr size_t proj_lds_bytes(int tb) { return (size_t)kStages * (2 * kHeadDim + 64 * tb) * kRowBytes; }
+// LDS stages: loads run stages-1 slabs ahead of the MFMAs.  The 128-row tile keeps 3 stages (72 KB) so
+// that two workgroups share a CU and cover each other's barriers; the larger tiles run alone with 4.
+constexpr int proj_stages(int tb) { return tb == 2 ? 3 : 4; }
+constexpr size_t proj_lds_bytes(int tb) { return (size_t)proj_stages(tb) * (2 * kHeadDim + 64 * tb) * kRowBytes; }
 
 struct proj_args {
   const bf16_t *hidden;
@@ -62,9 +64,10 @@ __device__ __forceinline__ head_sel select_head(int h, int Hq, int Hkv) {
 constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
 
 template <int TB>
-__global__ void __launch_bounds__(256, 1)
+__global__ void __launch_bounds__(256, TB == 2 ? 2 : 1)
 proj_bf16_kernel(proj_args a) {
   constexpr int kTokTile = 64 * TB;
+  constexpr int kStages = proj_stages(TB);
   constexpr int kWBytes = 2 * kHeadDim * kRowBytes;          // weight part of a stage: 256 rows
   constexpr int kStageBytes = kWBytes + kTokTile * kRowBytes;
   constexpr int kLoads = 4 + TB;                             // direct-to-LDS loads per wave per slab
@@ -506,7 +509,7 @@ extern "C" a3_status a3_selected_qkv_proj(const a3_layout *L, const void *hidden
       for (int c = 2; c <= 4; ++c) {
         const int tiles = (n_rows + 64 * c - 1) / (64 * c);
         const long wgs = (long)tiles * a.n_pairs;
-        const int per_cu = 1;                                 // LDS allows one workgroup per CU
+        const int per_cu = c == 2 ? 2 : 1;                    // co-resident workgroups
         const long rounds = (wgs + 256L * per_cu - 1) / (256L * per_cu);
         const double fill = (double)wgs / (double)(rounds * 256L * per_cu);
         const double pad = (double)n_rows / (double)(tiles * 64 * c);
