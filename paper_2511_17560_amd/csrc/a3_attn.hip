@@ -25,7 +25,9 @@ namespace {
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr int kD = 128;
-constexpr int kTM = 128;            // packed (row, head) pairs per work item: 4 waves x 32
+constexpr int kAttnWaves = 8;        // waves per workgroup: 0-3 stage V, 4-7 issue the K loads
+constexpr int kAttnThreads = 64 * kAttnWaves;
+constexpr int kTM = 32 * kAttnWaves; // packed (row, head) pairs per work item: 32 per wave
 constexpr int kTK = 64;             // keys per tile
 constexpr int kKRowBytes = kD * 2;   // K tile  [key][d]   256-byte rows, unpadded; 16-byte pieces XOR-swizzled by key % 16
 constexpr int kVStride = kTK + 8;   // V^T tile [d][key]  row stride in elements (144 B)
@@ -161,7 +163,7 @@ __device__ __forceinline__ uint32_t pack_lo(uint32_t a, uint32_t b) { return (a 
 __device__ __forceinline__ uint32_t pack_hi(uint32_t a, uint32_t b) { return (a >> 16) | (b & 0xffff0000u); }
 
 // Persistent workgroups: each pops items of its KV head from the head's queue until it is empty.
-__global__ void __launch_bounds__(256, 2)
+__global__ void __launch_bounds__(kAttnThreads, 1)
 attn_bf16_kernel(attn_args a) {
   extern __shared__ __align__(16) unsigned char lds_raw[];
   bf16_t *Ks = reinterpret_cast<bf16_t *>(lds_raw);          // [2][64][128], swizzled
@@ -179,10 +181,11 @@ attn_bf16_kernel(attn_args a) {
   const float c2 = a.scale2;
 
   // K tile: global memory -> LDS directly (global_load_lds, 16 bytes per lane, lane i lands at base + 16 i).
-  // One wave instruction brings 4 keys x 256 B; instruction j of wave w covers keys 4 (4 j + w) .. +3.
+  // One wave instruction brings 4 keys x 256 B; instruction j of wave 4 + w covers keys 4 (4 j + w) .. +3.
   // The lane fetches piece (slot ^ key % 16) of its key, so LDS slot s of key r holds piece s ^ (r % 16)
   // and the 16 keys a quarter wave reads at one piece index touch all 64 banks once.
-  const int drow = 4 * wave + (lane >> 4);                   // key of the lane in instruction 0
+  const int dwave = wave & 3;                                // K loads are issued by waves 4..7
+  const int drow = 4 * dwave + (lane >> 4);                  // key of the lane in instruction 0
   const int dpiece = (lane & 15) ^ (drow & 15);              // (4 (4 j + w) + lane/16) % 16 does not depend on j
   const uint32_t lds_k = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds_raw;
   // fragment read: key b*32 + l32, piece 2 ks + lhi -> slot (2 ks + lhi) ^ (l32 % 16)
@@ -190,7 +193,7 @@ attn_bf16_kernel(attn_args a) {
   // V tile: lane = (4 keys, 8 dims), transposed in registers on its way into LDS.
   // 16 consecutive lanes take 16 different key groups: their 8-byte transposed stores land in 128
   // contiguous bytes of one V^T row (all 32 LDS banks) instead of 16 rows at a bank-aligned stride
-  const int vkg = tid & 15, vc = tid >> 4;
+  const int vkg = tid & 15, vc = (tid & 255) >> 4;           // V is staged by waves 0..3
   const int vpos = ((4 * vkg) & ~12) | (((4 * vkg) & 4) << 1) | (((4 * vkg) & 8) >> 1);   // swap key bits 2 and 3
 
   for (;;) {
@@ -252,7 +255,7 @@ attn_bf16_kernel(attn_args a) {
     _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                          \
       const char *gp_ = kb + min(ko_0 + ((uint32_t)(K0) + 16u * j) * pitch_b, k_last);                       \
       asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"                                     \
-                   :: "s"(__builtin_amdgcn_readfirstlane(lds_k + (BUF) * (kKTile * 2) + 4 * (4 * j + wave) * kKRowBytes)), \
+                   :: "s"(__builtin_amdgcn_readfirstlane(lds_k + (BUF) * (kKTile * 2) + 4 * (4 * j + dwave) * kKRowBytes)), \
                       "v"(gp_) : "memory");                                                                  \
     }
 #define A3_GLOAD(K0)                                                                       \
@@ -280,9 +283,12 @@ attn_bf16_kernel(attn_args a) {
     }
 
     if (k_begin < k_end) {
-      A3_GLOAD(k_begin)
-      A3_KDMA(0, k_begin)
-      A3_LSTORE(0)
+      if (wave < 4) {
+        A3_GLOAD(k_begin)
+        A3_LSTORE(0)
+      } else {
+        A3_KDMA(0, k_begin)
+      }
     }
     // Everything loaded so far (Q fragments, first tile) has arrived: inside the loop the compiler's
     // waits then only concern the V registers of the loop itself.  (Its counter arithmetic does not
@@ -293,8 +299,11 @@ attn_bf16_kernel(attn_args a) {
     int buf = 0;
     for (int k0 = k_begin; k0 < k_end; k0 += kTK, buf ^= 1) {
       const bool more = k0 + kTK < k_end;
-      A3_GLOAD(k0 + kTK)                                     // next tile: in flight during everything below
-      if (more) { A3_KDMA(buf ^ 1, k0 + kTK) }
+      if (wave < 4) {
+        A3_GLOAD(k0 + kTK)                                   // next tile: in flight during everything below
+      } else if (more) {
+        A3_KDMA(buf ^ 1, k0 + kTK)
+      }
       const unsigned char *kt = reinterpret_cast<const unsigned char *>(Ks) + buf * (kKTile * 2) + kfrag;
       const bf16_t *vt = Vt + buf * kVTile + l32 * kVStride + lhi * 8;
 
@@ -384,7 +393,10 @@ attn_bf16_kernel(attn_args a) {
         for (int db = 0; db < 4; ++db)
           o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[step & 1][db], pf, o[db], 0, 0, 0);
       }
-      if (more) { A3_LSTORE(buf ^ 1) }
+      if (more) {
+        if (wave < 4) { A3_LSTORE(buf ^ 1) }
+        else __builtin_amdgcn_s_waitcnt(0x0f70);            // vmcnt(0): this wave's K loads have landed
+      }
       __syncthreads();
     }
 #undef A3_KDMA
@@ -616,11 +628,11 @@ extern "C" a3_status a3_fused_attention(const a3_layout *L, const void *q_act, c
     a.plan.max_tiles = max_tiles; a.plan.max_items = max_items; a.plan.seg_len = attn_seg_len(L);
     hipLaunchKernelGGL(attn_plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, a.plan, act_idx, n_act, L->seg_start,
                        L->n_req, L->n_q_heads / L->n_kv_heads, Hkv);
-    // persistent workgroups, two per CU; blockIdx % Hkv = KV head, so with 8 KV heads each XCD's L2
+    // persistent workgroups, one per CU; blockIdx % Hkv = KV head, so with 8 KV heads each XCD's L2
     // serves the K/V of one head
-    int wgs_per_head = (512 + Hkv - 1) / Hkv;
+    int wgs_per_head = (256 + Hkv - 1) / Hkv;
     if (wgs_per_head > max_items) wgs_per_head = max_items;
-    hipLaunchKernelGGL(attn_bf16_kernel, dim3((unsigned)wgs_per_head * Hkv), dim3(256), kAttnLds, st, a);
+    hipLaunchKernelGGL(attn_bf16_kernel, dim3((unsigned)wgs_per_head * Hkv), dim3(kAttnThreads), kAttnLds, st, a);
     hipLaunchKernelGGL(attn_combine_kernel, dim3((unsigned)max_tiles, Hkv, kTM / 32), dim3(256), 0, st, a);
   } else {
     hipLaunchKernelGGL(attn_f32_kernel, dim3(n_act, L->n_q_heads), dim3(256), 0, st, a);
