@@ -39,6 +39,14 @@ def _workload(name):
         return synth.custom(SMALL_BF16_HALF, [[130, 70], [33], [257, 64, 90]], [5, 33, 12], ratio=(20, 100), seed=42)
     if name == "g7-bf16":
         return synth.custom(SMALL_G7, [[200, 150, 93]], [9], ratio=(25, 100), seed=43)
+    if name == "cfg3-layer0":    # the 16K benchmark configuration, first and last of its 32 independent layers
+        return synth.config(3, layer=0)
+    if name == "cfg3-layer31":
+        return synth.config(3, layer=31)
+    if name == "cfg4":
+        return synth.config(4)
+    if name == "cfg5":
+        return synth.config(5)
     if name == "long-bf16":      # visible keys beyond 1.5 x 4096: tiles are cut into key segments and merged
         return synth.custom(SMALL_BF16, [[3000, 2500, 2100]], [40], ratio=(10, 100), n_planted=4, seed=45)
     if name == "batched-f32-d128":
@@ -47,10 +55,16 @@ def _workload(name):
 
 
 NAMES = ["cfg1", "cfg1-half", "ragged-bf16", "batched-bf16-half", "g7-bf16", "batched-f32-d128", "cfg2", "long-bf16"]
+# full-size configurations: one oracle layer each takes tens of seconds, so each is built once and runs
+# the chained test and the teacher-forced tests of the three kernels whose behaviour depends on scale
+BIG_NAMES = ["cfg3-layer0", "cfg3-layer31", "cfg4", "cfg5"]
 _cache = {}
 
 
 def ctx_of(name):
+    if name in BIG_NAMES and name not in _cache:       # keep one full-size context at a time
+        for k in [k for k in _cache if k in BIG_NAMES]:
+            del _cache[k]
     if name not in _cache:
         w = _workload(name)
         b = wl.build(w)
@@ -322,3 +336,14 @@ def test_topk_select_edge_cases(case):
     sel = torch.full((max(total_k, 1),), -1, dtype=torch.int32, device="cuda")
     api.a3_topk_select(lay, torch.from_numpy(sc).cuda(), idev(sel_start), total_k, sel)
     assert np.array_equal(sel.cpu().numpy()[:total_k], want)
+
+
+@pytest.mark.parametrize("name", BIG_NAMES)
+def test_full_size_config(name):
+    """Configurations 3 (two of its 32 layers), 4 and 5 at full size, in the launch configuration the
+    benchmark uses: scores, top-p and attention on the oracle's inputs, then the chained layer."""
+    test_question_scores(name)
+    test_topk_select_bit_exact_on_oracle_scores(name)
+    test_fused_attention(name)
+    test_chained_layer(name)
+    _cache.pop(name, None)
