@@ -133,6 +133,16 @@ a3_status a3_selected_qkv_proj(const a3_layout *layout, const void *hidden, cons
                                const void *bq, const void *bk, const void *bv,
                                void *q_out, void *k_out, void *v_out, void *stream);
 
+/* Steps 4 (projection part) and 5 in one call, Eq. 5 first three lines: as a3_selected_qkv_proj, but
+ * K and V of listed row i are written straight into the caches at packed row row_idx[i]
+ * (k_fused[row_idx[i]] <- K_i, v_fused[row_idx[i]] <- V_i; row_idx NULL means row i); Q stays compact
+ * in q_out.  k_fused, v_fused: [T, n_kv_heads, head_dim]; each of the three outputs may be NULL.
+ * Saves the round trip of the fresh K/V through a compact buffer and the a3_kv_scatter launch. */
+a3_status a3_selected_qkv_proj_scatter(const a3_layout *layout, const void *hidden, const int *row_idx,
+                                       int n_rows, const void *wq, const void *wk, const void *wv,
+                                       const void *bq, const void *bk, const void *bv,
+                                       void *q_out, void *k_fused, void *v_fused, void *stream);
+
 /* Step 5, Eq. 5 middle lines.  k_fused[row_idx[i]] <- k_new[i], v_fused[row_idx[i]] <- v_new[i].
  * k_new, v_new: [n_rows, n_kv_heads, head_dim]; row_idx: device int32 [n_rows], no duplicates.
  * Must be enqueued before a3_fused_attention on the same stream: attention reads the updated rows. */

@@ -20,7 +20,7 @@ A3_F32, A3_BF16 = 0, 1
 A3_ROPE_INTERLEAVED, A3_ROPE_HALF = 0, 1
 
 EXPORTS = ["a3_workspace_bytes", "a3_layout_prepare", "a3_rope_realign", "a3_question_scores", "a3_topk_select",
-           "a3_selected_qkv_proj", "a3_kv_scatter", "a3_fused_attention", "a3_active_rows", "a3_strerror", "a3_last_error", "a3_version"]
+           "a3_selected_qkv_proj", "a3_selected_qkv_proj_scatter", "a3_kv_scatter", "a3_fused_attention", "a3_active_rows", "a3_strerror", "a3_last_error", "a3_version"]
 
 
 class A3Error(RuntimeError):
@@ -62,11 +62,12 @@ def lib() -> C.CDLL:
     L.a3_question_scores.argtypes = [P, V, V, V, V, C.c_size_t, V]
     L.a3_topk_select.argtypes = [P, V, V, I, V, V, C.c_size_t, V]
     L.a3_selected_qkv_proj.argtypes = [P, V, V, I, V, V, V, V, V, V, V, V, V, V]
+    L.a3_selected_qkv_proj_scatter.argtypes = [P, V, V, I, V, V, V, V, V, V, V, V, V, V]
     L.a3_kv_scatter.argtypes = [P, V, V, V, I, V, V, V]
     L.a3_fused_attention.argtypes = [P, V, V, I, V, V, V, V, C.c_size_t, V]
     L.a3_active_rows.argtypes = [P, V, V, I, V, V]
-    for name in ("a3_active_rows", "a3_layout_prepare", "a3_rope_realign", "a3_question_scores", "a3_topk_select",
-                 "a3_selected_qkv_proj", "a3_kv_scatter", "a3_fused_attention"):
+    for name in ("a3_selected_qkv_proj_scatter", "a3_active_rows", "a3_layout_prepare", "a3_rope_realign", "a3_question_scores", "a3_topk_select",
+                 "a3_selected_qkv_proj", "a3_selected_qkv_proj_scatter", "a3_kv_scatter", "a3_fused_attention"):
         getattr(L, name).restype = I
     L.a3_strerror.restype = C.c_char_p
     L.a3_strerror.argtypes = [I]
@@ -192,6 +193,15 @@ def a3_selected_qkv_proj(layout: Layout, hidden: torch.Tensor, row_idx: Optional
     _check(lib().a3_selected_qkv_proj(layout.ref, _ptr(hidden), _ptr(row_idx), int(n_rows), _ptr(wq), _ptr(wk),
                                       _ptr(wv), _ptr(bq), _ptr(bk), _ptr(bv), _ptr(q_out), _ptr(k_out), _ptr(v_out),
                                       _stream(stream)), "a3_selected_qkv_proj")
+
+
+def a3_selected_qkv_proj_scatter(layout: Layout, hidden: torch.Tensor, row_idx: Optional[torch.Tensor], n_rows: int,
+                                 wq, wk, wv, bq=None, bk=None, bv=None, q_out=None, k_fused=None, v_fused=None,
+                                 stream=None) -> None:
+    _check(lib().a3_selected_qkv_proj_scatter(layout.ref, _ptr(hidden), _ptr(row_idx), int(n_rows), _ptr(wq),
+                                              _ptr(wk), _ptr(wv), _ptr(bq), _ptr(bk), _ptr(bv), _ptr(q_out),
+                                              _ptr(k_fused), _ptr(v_fused), _stream(stream)),
+           "a3_selected_qkv_proj_scatter")
 
 
 def a3_kv_scatter(layout: Layout, k_new: torch.Tensor, v_new: torch.Tensor, row_idx: torch.Tensor, n_rows: int,

@@ -47,6 +47,7 @@ struct proj_args {
   const float2 *pos_cs;
   int K, Hq, Hkv, rope_layout;
   int n_pairs, n_tok_tiles;
+  int scatter_kv;        // K and V go to row row_idx[i] of their output (the caches) instead of row i
 };
 
 struct head_sel { int which, head, heads_out; };
@@ -252,7 +253,8 @@ proj_bf16_kernel(proj_args a) {
           }
       }
     }
-    bf16_t *orow = out + ((size_t)tok * heads_out + head) * kHeadDim;
+    const int out_row = (a.scatter_kv && which != 0) ? (a.row_idx ? a.row_idx[tok] : tok) : tok;
+    bf16_t *orow = out + ((size_t)out_row * heads_out + head) * kHeadDim;
 #pragma unroll
     for (int fb = 0; fb < 4; ++fb)
 #pragma unroll
@@ -360,7 +362,8 @@ proj_small_bf16_kernel(proj_args a) {
       }
     }
   }
-  bf16_t *orow = out + ((size_t)tok * hs.heads_out + hs.head) * kHeadDim;
+  const int out_row = (a.scatter_kv && hs.which != 0) ? (a.row_idx ? a.row_idx[tok] : tok) : tok;
+  bf16_t *orow = out + ((size_t)out_row * hs.heads_out + hs.head) * kHeadDim;
 #pragma unroll
   for (int q4 = 0; q4 < 4; ++q4) {
     bf16x4 o;
@@ -386,6 +389,7 @@ struct proj_args_f32 {
   const int *tok_pos;
   const float2 *pos_cs;
   int K, Hq, Hkv, d, rope_layout;
+  int scatter_kv;
 };
 
 __global__ void __launch_bounds__(256)
@@ -455,7 +459,8 @@ proj_f32_kernel(proj_args_f32 a) {
       ya = xa * t.x - xb * t.y;
       yb = xa * t.y + xb * t.x;
     }
-    float *orow = out + ((size_t)m * heads_out + head) * d;
+    const int out_row = (a.scatter_kv && which != 0) ? (a.row_idx ? a.row_idx[m] : m) : m;
+    float *orow = out + ((size_t)out_row * heads_out + head) * d;
     orow[ia] = ya;
     orow[ib] = yb;
   }
@@ -463,10 +468,9 @@ proj_f32_kernel(proj_args_f32 a) {
 
 }  // namespace
 
-extern "C" a3_status a3_selected_qkv_proj(const a3_layout *L, const void *hidden, const int *row_idx, int n_rows,
-                                          const void *wq, const void *wk, const void *wv, const void *bq,
-                                          const void *bk, const void *bv, void *q_out, void *k_out, void *v_out,
-                                          void *stream) {
+static a3_status proj_launch(const a3_layout *L, const void *hidden, const int *row_idx, int n_rows, const void *wq,
+                             const void *wk, const void *wv, const void *bq, const void *bk, const void *bv,
+                             void *q_out, void *k_out, void *v_out, int scatter_kv, void *stream) {
   a3_status s = a3_check_layout(L, "a3_selected_qkv_proj", true);
   if (s != A3_OK) return s;
   A3_REQUIRE(n_rows >= 0 && n_rows <= L->total_tokens, A3_ERR_INVALID_ARG,
@@ -494,6 +498,7 @@ extern "C" a3_status a3_selected_qkv_proj(const a3_layout *L, const void *hidden
     a.K = L->hidden; a.Hq = L->n_q_heads; a.Hkv = L->n_kv_heads; a.rope_layout = L->rope_layout;
     a.n_pairs = (n_heads_total + 1) / 2;
     a.n_tok_tiles = 0;
+    a.scatter_kv = scatter_kv;
     if (n_rows <= 192 && L->hidden % 64 == 0 && !getenv("A3_PROJ_NTW")) {
       // few rows: stream the weights with 4 x n_heads x ceil(rows/64) small workgroups
       hipLaunchKernelGGL(proj_small_bf16_kernel, dim3(4 * n_heads_total, (n_rows + 63) / 64), dim3(256), 0, st, a);
@@ -541,9 +546,24 @@ extern "C" a3_status a3_selected_qkv_proj(const a3_layout *L, const void *hidden
     a.out[0] = (float *)q_out; a.out[1] = (float *)k_out; a.out[2] = (float *)v_out;
     a.tok_pos = L->tok_pos; a.pos_cs = (const float2 *)L->rope_pos_cs;
     a.K = L->hidden; a.Hq = L->n_q_heads; a.Hkv = L->n_kv_heads; a.d = L->head_dim; a.rope_layout = L->rope_layout;
+    a.scatter_kv = scatter_kv;
     dim3 grid(n_heads_total, (n_rows + kF32Rows - 1) / kF32Rows);
     hipLaunchKernelGGL(proj_f32_kernel, grid, dim3(256), 0, st, a);
   }
   A3_CHECK_LAUNCH("a3_selected_qkv_proj");
   return A3_OK;
+}
+
+extern "C" a3_status a3_selected_qkv_proj(const a3_layout *L, const void *hidden, const int *row_idx, int n_rows,
+                                          const void *wq, const void *wk, const void *wv, const void *bq,
+                                          const void *bk, const void *bv, void *q_out, void *k_out, void *v_out,
+                                          void *stream) {
+  return proj_launch(L, hidden, row_idx, n_rows, wq, wk, wv, bq, bk, bv, q_out, k_out, v_out, 0, stream);
+}
+
+extern "C" a3_status a3_selected_qkv_proj_scatter(const a3_layout *L, const void *hidden, const int *row_idx,
+                                                  int n_rows, const void *wq, const void *wk, const void *wv,
+                                                  const void *bq, const void *bk, const void *bv, void *q_out,
+                                                  void *k_fused, void *v_fused, void *stream) {
+  return proj_launch(L, hidden, row_idx, n_rows, wq, wk, wv, bq, bk, bv, q_out, k_fused, v_fused, 1, stream);
 }

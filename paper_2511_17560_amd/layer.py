@@ -67,25 +67,36 @@ def make_buffers(layout: api.Layout, sel_start: np.ndarray, q_rows: np.ndarray, 
 
 
 def fuse_layer(layout: api.Layout, b: LayerBuffers, x_cur: torch.Tensor, k_cat: torch.Tensor, v_cache: torch.Tensor,
-               wq: torch.Tensor, wk: torch.Tensor, wv: torch.Tensor, stream=None) -> None:
+               wq: torch.Tensor, wk: torch.Tensor, wv: torch.Tensor, stream=None, fused_scatter: bool = True) -> None:
     """Runs steps 1-5 for one layer.  ``k_cat`` is read, ``b.k_fused`` and ``v_cache`` (in place)
-    hold the fused cache afterwards, ``b.out`` the attention output of the active rows."""
+    hold the fused cache afterwards, ``b.out`` the attention output of the active rows.
+
+    ``fused_scatter`` (default) lets the projections write the fresh K/V straight into the caches
+    (a3_selected_qkv_proj_scatter); otherwise the plain sequence a3_selected_qkv_proj ->
+    a3_kv_scatter is used.  Both give the same cache: the question rows are written before the
+    realign, which only writes context rows, and the selected rows after the scores were read."""
     nq = b.n_act - b.total_k
     k = b.total_k
     if b.single:
-        api.a3_selected_qkv_proj(layout, x_cur, b.q_rows, nq, wq, wk, wv, q_out=b.q_act[k:], k_out=b.k_act[k:],
-                                 v_out=b.v_act[k:], stream=stream)
+        if fused_scatter:
+            api.a3_selected_qkv_proj_scatter(layout, x_cur, b.q_rows, nq, wq, wk, wv, q_out=b.q_act[k:],
+                                             k_fused=b.k_fused, v_fused=v_cache, stream=stream)
+        else:
+            api.a3_selected_qkv_proj(layout, x_cur, b.q_rows, nq, wq, wk, wv, q_out=b.q_act[k:], k_out=b.k_act[k:],
+                                     v_out=b.v_act[k:], stream=stream)
     else:
         api.a3_selected_qkv_proj(layout, x_cur, b.q_rows, nq, wq, None, None, q_out=b.q_question, stream=stream)
     api.a3_rope_realign(layout, k_cat, b.k_fused, stream=stream)
     api.a3_question_scores(layout, b.q_question, b.k_fused, b.scores, b.ws, stream=stream)
     api.a3_topk_select(layout, b.scores, b.sel_start, k, b.sel_idx, stream=stream)
-    if b.single:
-        api.a3_selected_qkv_proj(layout, x_cur, b.sel_idx, k, wq, wk, wv, q_out=b.q_act, k_out=b.k_act,
-                                 v_out=b.v_act, stream=stream)
-    else:
+    rows, n_rows = (b.sel_idx, k) if b.single else (b.act_idx, b.n_act)
+    if not b.single:
         api.a3_active_rows(layout, b.sel_idx, b.sel_start, b.n_act, b.act_idx, stream=stream)
-        api.a3_selected_qkv_proj(layout, x_cur, b.act_idx, b.n_act, wq, wk, wv, q_out=b.q_act, k_out=b.k_act,
+    if fused_scatter:
+        api.a3_selected_qkv_proj_scatter(layout, x_cur, rows, n_rows, wq, wk, wv, q_out=b.q_act, k_fused=b.k_fused,
+                                         v_fused=v_cache, stream=stream)
+    else:
+        api.a3_selected_qkv_proj(layout, x_cur, rows, n_rows, wq, wk, wv, q_out=b.q_act, k_out=b.k_act,
                                  v_out=b.v_act, stream=stream)
-    api.a3_kv_scatter(layout, b.k_act, b.v_act, b.act_idx, b.n_act, b.k_fused, v_cache, stream=stream)
+        api.a3_kv_scatter(layout, b.k_act, b.v_act, b.act_idx, b.n_act, b.k_fused, v_cache, stream=stream)
     api.a3_fused_attention(layout, b.q_act, b.act_idx, b.n_act, b.k_fused, v_cache, b.out, b.ws, stream=stream)

@@ -257,8 +257,15 @@ def test_fused_attention_with_short_key_segments(name, seg, monkeypatch):
     assert max_abs_rel(to_host(out), res["out"]) <= tol(w)
 
 
+@pytest.mark.parametrize("name", ["cfg1", "ragged-bf16", "batched-bf16-half", "cfg2"])
+def test_chained_layer_plain_six_call_sequence(name):
+    """Same as test_chained_layer, through a3_selected_qkv_proj + a3_kv_scatter instead of the fused
+    projection-and-scatter call."""
+    test_chained_layer(name, fused_scatter=False)
+
+
 @pytest.mark.parametrize("name", NAMES)
-def test_chained_layer(name):
+def test_chained_layer(name, fused_scatter=True):
     """All steps on the GPU's own intermediates.  The selected set must equal the oracle's up to
     near-ties: a row in the symmetric difference must score within 1e-3 (relative) of the
     oracle's k-th score.  Planted rows must be selected.  Downstream tensors are compared on the
@@ -271,7 +278,7 @@ def test_chained_layer(name):
     x = to_dev(t.x_cur, dt)
     k_cat, v_cache = to_dev(b["k_cat"], dt), to_dev(b["v_cat"], dt)
     wq, wk, wv = to_dev(t.wq, dt), to_dev(t.wk, dt), to_dev(t.wv, dt)
-    layer.fuse_layer(lay, bufs, x, k_cat, v_cache, wq, wk, wv)
+    layer.fuse_layer(lay, bufs, x, k_cat, v_cache, wq, wk, wv, fused_scatter=fused_scatter)
     torch.cuda.synchronize()
     got_act = bufs.act_idx.cpu().numpy()[:bufs.n_act]
     want_act = res["act_idx"]
