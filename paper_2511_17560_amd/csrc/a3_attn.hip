@@ -307,28 +307,30 @@ attn_bf16_kernel(attn_args a) {
       const unsigned char *kt = reinterpret_cast<const unsigned char *>(Ks) + buf * (kKTile * 2) + kfrag;
       const bf16_t *vt = Vt + buf * kVTile + l32 * kVStride + lhi * 8;
 
-      // ---- S^T = K Q^T : two 32-key blocks, K fragments read two steps ahead ----------------
+      // ---- S^T = K Q^T : two 32-key blocks, K fragments read one step ahead -----------------
       f32x16 st[2];
 #pragma unroll
       for (int b = 0; b < 2; ++b)
 #pragma unroll
         for (int x = 0; x < 16; ++x) st[b][x] = 0.f;
-      bf16x8 kf[3][2];
+      // The scheduling barriers pin the order "reads of step ks + 1, then MFMAs of step ks": left alone
+      // the compiler sinks every read to just before its use and the LDS latency is exposed
+      bf16x8 kf[2][2];
 #pragma unroll
-      for (int pre = 0; pre < 2; ++pre)
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-          kf[pre][b] = *reinterpret_cast<const bf16x8 *>(kt + b * 32 * kKRowBytes + ((32 * pre) ^ kswz));
+      for (int b = 0; b < 2; ++b)
+        kf[0][b] = *reinterpret_cast<const bf16x8 *>(kt + b * 32 * kKRowBytes + (0 ^ kswz));
 #pragma unroll
       for (int ks = 0; ks < kD / 16; ++ks) {
-        if (ks + 2 < kD / 16) {
+        if (ks + 1 < kD / 16) {
 #pragma unroll
           for (int b = 0; b < 2; ++b)
-            kf[(ks + 2) % 3][b] = *reinterpret_cast<const bf16x8 *>(kt + b * 32 * kKRowBytes + ((32 * (ks + 2)) ^ kswz));
+            kf[(ks + 1) & 1][b] = *reinterpret_cast<const bf16x8 *>(kt + b * 32 * kKRowBytes + ((32 * (ks + 1)) ^ kswz));
         }
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int b = 0; b < 2; ++b)
-          st[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks % 3][b], qf[ks], st[b], 0, 0, 0);
+          st[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks & 1][b], qf[ks], st[b], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
       }
 
       // first V^T fragments: their LDS latency hides behind the softmax arithmetic

@@ -268,81 +268,36 @@ proj_bf16_kernel(proj_args a) {
 }
 
 // ---------------------------------------------------------------------------------------
-// bf16 kernel for few rows (the question tokens): weight-streaming bound
+// bf16 kernels for few rows (the question tokens): weight-streaming bound
 // ---------------------------------------------------------------------------------------
-// With ~64 rows the GEMM is a stream over the 48 MB of weights.  To put every CU on that stream a
-// workgroup takes only 32 features of one head (16 from each half of the head, so both RoPE
-// pairings stay inside it) x 64 rows, and its 4 waves split the reduction dimension four ways;
-// fragments are read straight from global memory and the four partial tiles are added in LDS in
-// wave order.
-__global__ void __launch_bounds__(256)
-proj_small_bf16_kernel(proj_args a) {
-  __shared__ float red[4][2][16][64];                          // [wave][row block][register][lane]
-
-  const int head_all = blockIdx.x >> 2, sb = blockIdx.x & 3;
-  const head_sel hs = select_head(head_all, a.Hq, a.Hkv);
-  bf16_t *__restrict__ out = a.out[hs.which];
-  if (out == nullptr) return;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int l32 = lane & 31, lhi = lane >> 5;
-  const int tok0 = blockIdx.y * 64;
-  // MFMA row i of this workgroup's weight block <-> feature of the head
-  const int feat = l32 < 16 ? 16 * sb + l32 : 64 + 16 * sb + (l32 - 16);
-  const int kq = a.K / 4;                                      // this wave's share of the reduction
-  const bf16_t *wp = a.w[hs.which] + ((size_t)hs.head * kHeadDim + feat) * a.K + wave * kq + lhi * 8;
-  const bf16_t *xp[2];
-#pragma unroll
-  for (int tb = 0; tb < 2; ++tb) {
-    int m = min(tok0 + tb * 32 + l32, a.n_rows - 1);
-    int src_row = a.row_idx ? a.row_idx[m] : m;
-    xp[tb] = a.hidden + (size_t)src_row * a.K + wave * kq + lhi * 8;
-  }
-  f32x16 acc[2];
-#pragma unroll
-  for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) acc[tb][r] = 0.f;
-  for (int k = 0; k < kq; k += 64) {                           // kq is a multiple of 16; 4 steps per trip
-    bf16x8 wf[4], xf[4][2];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int kk = min(k + 16 * u, kq - 16);                 // tail of a share that is not a multiple of 64
-      wf[u] = *reinterpret_cast<const bf16x8 *>(wp + kk);
-      xf[u][0] = *reinterpret_cast<const bf16x8 *>(xp[0] + kk);
-      xf[u][1] = *reinterpret_cast<const bf16x8 *>(xp[1] + kk);
-    }
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      if (k + 16 * u < kq) {
-        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[u], xf[u][0], acc[0], 0, 0, 0);
-        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[u], xf[u][1], acc[1], 0, 0, 0);
-      }
-    }
-  }
-#pragma unroll
-  for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) red[wave][tb][r][lane] = acc[tb][r];
-  __syncthreads();
-  if (wave >= 2) return;
-  const int tb = wave;                                         // waves 0 and 1 finish one row block each
-  const int tok = tok0 + tb * 32 + l32;
+// Last step of both few-row kernels for one lane = one listed row: adds the NW partial tiles in wave
+// order (partial w of accumulator register r is part[w * wave_stride + r * 64]), then bias, RoPE
+// and the single rounding.  A workgroup holds 32 features of one head: 16 sb + (0..15) and the same
+// + 64, so both RoPE pairings are inside it; accumulator register r is MFMA row
+// i = 8 (r/4) + 4 lhi + r%4, and i < 16 is the first half of the head, i >= 16 the second.
+template <int NW>
+__device__ __forceinline__ void small_finish(const proj_args &a, const head_sel hs, int sb, int tok, int lhi,
+                                             const float *part, int wave_stride) {
   if (tok >= a.n_rows) return;
   float v[16];
 #pragma unroll
-  for (int r = 0; r < 16; ++r) v[r] = (red[0][tb][r][lane] + red[1][tb][r][lane]) + (red[2][tb][r][lane] + red[3][tb][r][lane]);
-  // register r: MFMA row i = 8 (r/4) + 4 lhi + r%4; i < 16 is the first half of the head, i >= 16 the second
-  const bf16_t *bias = a.bias[hs.which];
+  for (int r = 0; r < 16; ++r) {
+    float t = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) t += part[w * wave_stride + r * 64];   // fixed order
+    v[r] = t;
+  }
   auto feat_of = [&](int r) {
     int i = 8 * (r >> 2) + 4 * lhi + (r & 3);
     return i < 16 ? 16 * sb + i : 64 + 16 * sb + (i - 16);
   };
+  const bf16_t *bias = a.bias[hs.which];
   if (bias) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) v[r] += a3_bf2f(bias[hs.head * kHeadDim + feat_of(r)]);
   }
+  const int src_row = a.row_idx ? a.row_idx[tok] : tok;
   if (hs.which != 2) {
-    const int src_row = a.row_idx ? a.row_idx[tok] : tok;
     const float2 *cs = a.pos_cs + (size_t)a.tok_pos[src_row] * (kHeadDim / 2);
     if (a.rope_layout == A3_ROPE_INTERLEAVED) {
 #pragma unroll
@@ -362,8 +317,8 @@ proj_small_bf16_kernel(proj_args a) {
       }
     }
   }
-  const int out_row = (a.scatter_kv && hs.which != 0) ? (a.row_idx ? a.row_idx[tok] : tok) : tok;
-  bf16_t *orow = out + ((size_t)out_row * hs.heads_out + hs.head) * kHeadDim;
+  const int out_row = (a.scatter_kv && hs.which != 0) ? src_row : tok;
+  bf16_t *orow = a.out[hs.which] + ((size_t)out_row * hs.heads_out + hs.head) * kHeadDim;
 #pragma unroll
   for (int q4 = 0; q4 < 4; ++q4) {
     bf16x4 o;
@@ -371,6 +326,192 @@ proj_small_bf16_kernel(proj_args a) {
     for (int e = 0; e < 4; ++e) o[e] = a3_f2bf(v[4 * q4 + e]);
     *reinterpret_cast<bf16x4 *>(orow + feat_of(4 * q4)) = o;
   }
+}
+
+// Hidden size a multiple of 256.  With ~64 rows the GEMM is a stream over the 48 MB of weights.  To
+// put every CU on that stream a workgroup takes only 32 features of one head x 64 rows, and its 4
+// waves split the reduction dimension four ways.  Each wave runs its own pipeline with no workgroup
+// barrier: stages of 64 reduction elements (32 weight rows + 64 hidden rows, 128 bytes each) go
+// from global memory straight into the wave's private ring of three LDS stages with fully coalesced
+// direct-to-LDS loads (8 lanes per 128-byte row), two stages ahead of the MFMAs.  (Fragments loaded
+// straight into registers would touch 32 different cache lines per instruction, and the address
+// path of the L1, not HBM, then sets the pace.)  LDS slot s of row r holds the 16-byte piece
+// s ^ ((r/2) % 8) of the row's 128 bytes: the 16 consecutive rows a quarter wave reads at one piece
+// index touch all 64 banks once.
+constexpr int kSmStageBytes = 96 * 128;
+constexpr int kSmRing = 3;
+constexpr size_t kSmLdsBytes = (size_t)4 * kSmRing * kSmStageBytes;      // 144 KB
+
+__global__ void __launch_bounds__(256)
+proj_small_dma_bf16_kernel(proj_args a) {
+  extern __shared__ __align__(16) unsigned char lds[];
+
+  const int head_all = blockIdx.x >> 2, sb = blockIdx.x & 3;
+  const head_sel hs = select_head(head_all, a.Hq, a.Hkv);
+  if (a.out[hs.which] == nullptr) return;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, lhi = lane >> 5;
+  const int tok0 = blockIdx.y * 64;
+  const int kq = a.K / 4;                                      // this wave's share: a multiple of 64
+
+  // loading role: one instruction brings 8 rows x 128 B, lane -> (row lane/8, slot lane%8)
+  const int drow = lane >> 3, dslot = lane & 7;
+  const char *wsrc[4], *xsrc[8];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int row = 8 * j + drow;                              // MFMA row of the weight block
+    const int feat = row < 16 ? 16 * sb + row : 64 + 16 * sb + (row - 16);
+    wsrc[j] = reinterpret_cast<const char *>(a.w[hs.which] + ((size_t)hs.head * kHeadDim + feat) * a.K + wave * kq) +
+              16 * (dslot ^ ((row >> 1) & 7));
+  }
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int row = 8 * j + drow;
+    const int m = min(tok0 + row, a.n_rows - 1);               // clamp: computed but never stored
+    const int src_row = a.row_idx ? a.row_idx[m] : m;
+    xsrc[j] = reinterpret_cast<const char *>(a.hidden + (size_t)src_row * a.K + wave * kq) +
+              16 * (dslot ^ ((row >> 1) & 7));
+  }
+  unsigned char *ring = lds + wave * (kSmRing * kSmStageBytes);
+  const uint32_t lds_ring = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)ring;
+  // Inline assembly as in the large kernel: lane i's 16 bytes land at M0 + 16 i, the compiler does not
+  // track these loads, and the waits for them are the explicit s_waitcnt below.
+#define A3_SM_ISSUE(SLOT, K0)                                                                                  \
+  {                                                                                                            \
+    _Pragma("unroll") for (int j = 0; j < 4; ++j)                                                              \
+      asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"                                       \
+                   :: "s"(__builtin_amdgcn_readfirstlane(lds_ring + (SLOT) * kSmStageBytes + 1024 * j)),       \
+                      "v"(wsrc[j] + 2 * (K0)) : "memory");                                                     \
+    _Pragma("unroll") for (int j = 0; j < 8; ++j)                                                              \
+      asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"                                       \
+                   :: "s"(__builtin_amdgcn_readfirstlane(lds_ring + (SLOT) * kSmStageBytes + 4096 + 1024 * j)), \
+                      "v"(xsrc[j] + 2 * (K0)) : "memory");                                                     \
+  }
+  f32x16 acc[2];
+#pragma unroll
+  for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[tb][r] = 0.f;
+  // everything the compiler loaded itself (row indices) has arrived: from here on only the
+  // direct-to-LDS loads are outstanding and the counts below are exact
+  __builtin_amdgcn_s_waitcnt(0);
+  const int n_st = kq / 64;
+  A3_SM_ISSUE(0, 0)
+  if (n_st > 1) A3_SM_ISSUE(1, 64)
+  const int frag = l32 * 128, fswz = (l32 >> 1) & 7;           // rows 32 tb + l32 swizzle like row l32
+  int slot = 0, slot2 = 2;
+  for (int s = 0; s < n_st; ++s) {
+    if (s + 2 < n_st) {
+      A3_SM_ISSUE(slot2, 64 * (s + 2))
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm(24));               // 12 loads per stage: stage s has landed
+    } else if (s + 1 < n_st) {
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm(12));
+    } else {
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    }
+    asm volatile("" ::: "memory");
+    const unsigned char *st = ring + slot * kSmStageBytes + frag;
+    bf16x8 wf[4], xa[4], xb[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int po = 16 * ((2 * u + lhi) ^ fswz);
+      wf[u] = *reinterpret_cast<const bf16x8 *>(st + po);
+      xa[u] = *reinterpret_cast<const bf16x8 *>(st + 4096 + po);
+      xb[u] = *reinterpret_cast<const bf16x8 *>(st + 8192 + po);
+    }
+    __builtin_amdgcn_sched_barrier(0);                         // all twelve reads in flight before the first MFMA
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[u], xa[u], acc[0], 0, 0, 0);
+      acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[u], xb[u], acc[1], 0, 0, 0);
+    }
+    // the fragments are in registers before the next trip overwrites the slot read two trips ago
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    slot = slot == kSmRing - 1 ? 0 : slot + 1;
+    slot2 = slot2 == kSmRing - 1 ? 0 : slot2 + 1;
+  }
+#undef A3_SM_ISSUE
+  // the wave's own ring is free now: it holds the wave's partial tile, [row block][register][lane]
+  float *red = reinterpret_cast<float *>(ring);
+#pragma unroll
+  for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) red[(tb * 16 + r) * 64 + lane] = acc[tb][r];
+  __syncthreads();
+  if (wave >= 2) return;
+  const int tb = wave;                                         // waves 0 and 1 finish one row block each
+  small_finish<4>(a, hs, sb, tok0 + tb * 32 + l32, lhi, reinterpret_cast<const float *>(lds) + tb * 16 * 64 + lane,
+                  kSmRing * kSmStageBytes / 4);
+}
+
+// Any other hidden size that is a multiple of 64: fragments straight from global memory.
+// A workgroup takes 32 features of one head (16 from each half of the head, so both RoPE
+// pairings stay inside it) x 64 rows, and its NW waves (2 when the hidden size is a multiple of
+// 128, else 1) split the reduction dimension NW ways in shares of whole 64-wide stages; fragments
+// are read straight from global memory and the partial tiles are added in LDS in wave order.
+template <int NW>                                               // waves per workgroup = ways the reduction is split
+__global__ void __launch_bounds__(64 * NW)
+proj_small_bf16_kernel(proj_args a) {
+  __shared__ float red[NW][2][16][64];                         // [wave][row block][register][lane]
+
+  const int head_all = blockIdx.x >> 2, sb = blockIdx.x & 3;
+  const head_sel hs = select_head(head_all, a.Hq, a.Hkv);
+  bf16_t *__restrict__ out = a.out[hs.which];
+  if (out == nullptr) return;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, lhi = lane >> 5;
+  const int tok0 = blockIdx.y * 64;
+  // MFMA row i of this workgroup's weight block <-> feature of the head
+  const int feat = l32 < 16 ? 16 * sb + l32 : 64 + 16 * sb + (l32 - 16);
+  const int kq = a.K / NW;                                     // this wave's share of the reduction
+  const bf16_t *wp = a.w[hs.which] + ((size_t)hs.head * kHeadDim + feat) * a.K + wave * kq + lhi * 8;
+  const bf16_t *xp0, *xp1;
+  {
+    int m = min(tok0 + l32, a.n_rows - 1);
+    xp0 = a.hidden + (size_t)(a.row_idx ? a.row_idx[m] : m) * a.K + wave * kq + lhi * 8;
+    m = min(tok0 + 32 + l32, a.n_rows - 1);
+    xp1 = a.hidden + (size_t)(a.row_idx ? a.row_idx[m] : m) * a.K + wave * kq + lhi * 8;
+  }
+  f32x16 acc[2];
+#pragma unroll
+  for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[tb][r] = 0.f;
+  // Two register stages of four k-steps each: the loads of one stage are in flight while the other
+  // is multiplied, so every wave always has weight bytes on their way from HBM.  The share kq is a
+  // multiple of 64 (one stage).
+  bf16x8 wf0[4], wf1[4], xa0[4], xa1[4], xb0[4], xb1[4];
+#define A3_SMALL_LOAD(WF, XA, XB, K0)                                            \
+  _Pragma("unroll") for (int u = 0; u < 4; ++u) {                                \
+    WF[u] = *reinterpret_cast<const bf16x8 *>(wp + (K0) + 16 * u);               \
+    XA[u] = *reinterpret_cast<const bf16x8 *>(xp0 + (K0) + 16 * u);              \
+    XB[u] = *reinterpret_cast<const bf16x8 *>(xp1 + (K0) + 16 * u);              \
+  }
+#define A3_SMALL_MMA(WF, XA, XB)                                                 \
+  _Pragma("unroll") for (int u = 0; u < 4; ++u) {                                \
+    acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(WF[u], XA[u], acc[0], 0, 0, 0); \
+    acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(WF[u], XB[u], acc[1], 0, 0, 0); \
+  }
+  A3_SMALL_LOAD(wf0, xa0, xb0, 0)
+  int k = 0;
+  for (; k + 128 <= kq; k += 128) {
+    A3_SMALL_LOAD(wf1, xa1, xb1, k + 64)
+    A3_SMALL_MMA(wf0, xa0, xb0)
+    const int kn = min(k + 128, kq - 64);                      // past the end: the last stage again, unused
+    A3_SMALL_LOAD(wf0, xa0, xb0, kn)
+    A3_SMALL_MMA(wf1, xa1, xb1)
+  }
+  if (k < kq) { A3_SMALL_MMA(wf0, xa0, xb0) }                  // odd number of stages
+#undef A3_SMALL_LOAD
+#undef A3_SMALL_MMA
+#pragma unroll
+  for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) red[wave][tb][r][lane] = acc[tb][r];
+  __syncthreads();
+  if (wave >= 2) return;
+  for (int tb = wave; tb < 2; tb += (NW > 1 ? 2 : 1))          // waves 0 and 1 finish one row block each
+    small_finish<NW>(a, hs, sb, tok0 + tb * 32 + l32, lhi, &red[0][tb][0][lane], 2 * 16 * 64);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -501,7 +642,21 @@ static a3_status proj_launch(const a3_layout *L, const void *hidden, const int *
     a.scatter_kv = scatter_kv;
     if (n_rows <= 192 && L->hidden % 64 == 0 && !getenv("A3_PROJ_NTW")) {
       // few rows: stream the weights with 4 x n_heads x ceil(rows/64) small workgroups
-      hipLaunchKernelGGL(proj_small_bf16_kernel, dim3(4 * n_heads_total, (n_rows + 63) / 64), dim3(256), 0, st, a);
+      const dim3 grid(4 * n_heads_total, (n_rows + 63) / 64);
+      if (L->hidden % 256 == 0) {
+        static bool small_attr_done = false;
+        if (!small_attr_done) {
+          hipError_t e = hipFuncSetAttribute((const void *)proj_small_dma_bf16_kernel,
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSmLdsBytes);
+          if (e != hipSuccess) return a3_fail(A3_ERR_HIP, "a3_selected_qkv_proj: cannot raise the dynamic LDS limit");
+          small_attr_done = true;
+        }
+        hipLaunchKernelGGL(proj_small_dma_bf16_kernel, grid, dim3(256), kSmLdsBytes, st, a);
+      } else if (L->hidden % 128 == 0) {
+        hipLaunchKernelGGL(proj_small_bf16_kernel<2>, grid, dim3(128), 0, st, a);
+      } else {
+        hipLaunchKernelGGL(proj_small_bf16_kernel<1>, grid, dim3(64), 0, st, a);
+      }
       A3_CHECK_LAUNCH("a3_selected_qkv_proj");
       return A3_OK;
     }
