@@ -5,12 +5,12 @@
 // A column sum of row softmaxes needs every row's (max, sum exp) before any column can be
 // summed, so the logits are formed twice:
 //   pass A   per (key tile, row): partial (max, sum exp)          -> workspace
-//   combine  per row: merge the partials                          -> (max, 1/sum) per row
+//   combine  per row: merge the partials                          -> max + log2(sum) per row
 //   pass B   per key tile: sum over all rows of exp(l - max)/sum  -> scores
 // Rows, then heads, are reduced in a fixed order, so the result is deterministic (no atomics).
 //
 // bf16: logits on the matrix cores (32x32x16 bf16 MFMA).  A workgroup owns 256 keys of one KV
-// head: the K tile (64 KB) sits in LDS with a padded stride and every Q fragment a wave loads
+// head: the K tile (64 KB) sits in LDS (loaded there directly, swizzled) and every Q fragment a wave loads
 // (straight from global memory, Q is L2 resident) meets all 8 key blocks, so both K and Q cross
 // the L2 once per pass.  Pass B leaves one partial score per KV head; a last small kernel adds the
 // heads in order.  exp2 with log2(e) folded into the scale.
@@ -36,7 +36,7 @@ struct scores_args {
   const void *k;            // [T, Hkv, d]
   const int *seg_start, *ctx_len, *q_len, *q_start;
   float2 *part;             // [n_tiles, total_rows] partial (max, sum) in the exp2 domain
-  float2 *stats;            // [total_rows] (max, 1/sum)
+  float2 *stats;            // [total_rows] (max + log2(sum), unused)
   float *scores;            // [T]
   float *part_scores;       // [Hkv, T] bf16 path: per KV head partial scores
   int n_req, Hq, Hkv, d, T, total_rows, n_tiles, tile_keys;
@@ -51,35 +51,32 @@ constexpr int kTileKeysMfma = 256; // bf16 kernels
 
 __global__ void __launch_bounds__(256)
 scores_combine_kernel(scores_args a) {
-  // 32 rows x 8 tile slices per workgroup
-  __shared__ float2 red[8][32];
-  const int row = blockIdx.x * 32 + (threadIdx.x & 31);
-  const int slice = threadIdx.x >> 5;
+  // one row per 16 lanes: the lanes split the row's tiles, then merge pairwise (fixed tree)
+  const int row = blockIdx.x * 16 + (threadIdx.x >> 4);
+  const int slice = threadIdx.x & 15;
   float m = -INFINITY, z = 0.f;
   if (row < a.total_rows) {
     const int jq = row / a.Hq;
     const int r = find_segment(a.q_start, a.n_req, jq);
     const int tiles = (a.ctx_len[r] + a.tile_keys - 1) / a.tile_keys;
-    for (int t = slice; t < tiles; t += 8) {
+    for (int t = slice; t < tiles; t += 16) {
       float2 p = a.part[(size_t)t * a.total_rows + row];
       float mn = fmaxf(m, p.x);
       z = z * exp2f(m - mn) + p.y * exp2f(p.x - mn);
       m = mn;
     }
   }
-  red[slice][threadIdx.x & 31] = make_float2(m, z);
-  __syncthreads();
-  if (slice == 0 && row < a.total_rows) {
-    for (int s = 1; s < 8; ++s) {
-      float2 p = red[s][threadIdx.x & 31];
-      if (p.y > 0.f) {
-        float mn = fmaxf(m, p.x);
-        z = z * exp2f(m - mn) + p.y * exp2f(p.x - mn);
-        m = mn;
-      }
-    }
-    a.stats[row] = make_float2(m, z > 0.f ? 1.0f / z : 0.f);
+#pragma unroll
+  for (int off = 8; off > 0; off >>= 1) {
+    const float pm = __shfl_xor(m, off, 16), pz = __shfl_xor(z, off, 16);
+    const float mn = fmaxf(m, pm);
+    // a side that saw no tile has (m, z) = (-inf, 0): its factor must not become exp2(nan)
+    const float za = z > 0.f ? z * exp2f(m - mn) : 0.f, zb = pz > 0.f ? pz * exp2f(pm - mn) : 0.f;
+    z = (slice & off) ? zb + za : za + zb;                     // same operand order in both lanes of a pair
+    m = mn;
   }
+  // exp2(l - m) / z = exp2(l - (m + log2 z)): pass B subtracts one number per row
+  if (slice == 0 && row < a.total_rows) a.stats[row] = make_float2(z > 0.f ? m + log2f(z) : INFINITY, 0.f);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -88,8 +85,8 @@ scores_combine_kernel(scores_args a) {
 // rows of the group 64 at a time.
 // ---------------------------------------------------------------------------------------
 constexpr int kD = 128;
-constexpr int kKStride = kD + 8;      // LDS row stride (elements): 272 B, 8 rows cover all 32 banks once
-constexpr size_t kScoresLds = (size_t)kTileKeysMfma * kKStride * sizeof(bf16_t) + 4 * 64 * sizeof(float2) +
+constexpr int kKRowBytes = kD * 2;    // LDS rows are unpadded; their 16-byte pieces are XOR-swizzled
+constexpr size_t kScoresLds = (size_t)kTileKeysMfma * kKRowBytes + 4 * 64 * sizeof(float) +
                               4 * kTileKeysMfma * sizeof(float);
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -108,8 +105,7 @@ template <int PASS>
 __global__ void __launch_bounds__(256, 2)
 scores_bf16_kernel(scores_args a) {
   extern __shared__ __align__(16) unsigned char lds_raw[];
-  bf16_t *Ks = reinterpret_cast<bf16_t *>(lds_raw);                                  // [256][kKStride]
-  float2 *St = reinterpret_cast<float2 *>(Ks + kTileKeysMfma * kKStride);             // [4 waves][64 rows]
+  float *St = reinterpret_cast<float *>(lds_raw + kTileKeysMfma * kKRowBytes);      // after the K tile; [4 waves][64 rows]
   float *red = reinterpret_cast<float *>(St + 4 * 64);                                // [4 waves][256 keys]
 
   const int r = blockIdx.z, g = blockIdx.y;
@@ -126,43 +122,56 @@ scores_bf16_kernel(scores_args a) {
   const bf16_t *__restrict__ Q = (const bf16_t *)a.q;
   const bf16_t *__restrict__ K = (const bf16_t *)a.k;
 
-  // ---- K tile: 256 keys x 128 dims of head g; 16 lanes per 256-byte row ---------------------------------
-  {
-    const int c = tid & 15, kr0 = tid >> 4;
-    uint4 v[16];
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      int row = min(s + i0 + kr0 + 16 * i, a.T - 1);           // tail rows: loaded, masked below
-      v[i] = *reinterpret_cast<const uint4 *>(K + ((size_t)row * a.Hkv + g) * kD + c * 8);
-    }
-#pragma unroll
-    for (int i = 0; i < 16; ++i) *reinterpret_cast<uint4 *>(Ks + (kr0 + 16 * i) * kKStride + c * 8) = v[i];
+  // Q fragments of this wave's first 64 rows: requested before the K tile so that both latencies overlap
+  // (rows past Mg are clamped and ignored later)
+  bf16x8 qf[2][kD / 16];
+  int row_id[2];
+#define A3_LOAD_Q(RB0)                                                                                 \
+  _Pragma("unroll") for (int b = 0; b < 2; ++b) {                                                      \
+    const int m_ = min((RB0) + b * 32 + l32, Mg - 1);                                                  \
+    row_id[b] = (qrow0 + m_ / G) * a.Hq + g * G + m_ % G;      /* row of the [sum q_len * Hq] row space */ \
+    const bf16_t *qp_ = Q + (size_t)row_id[b] * kD + lhi * 8;                                          \
+    _Pragma("unroll") for (int ks = 0; ks < kD / 16; ++ks) qf[b][ks] = *reinterpret_cast<const bf16x8 *>(qp_ + ks * 16); \
   }
-  __syncthreads();
-  const int n_kb = min(8, (N - i0 + 31) / 32);                 // key blocks with at least one real key
-  const bf16_t *kt = Ks + l32 * kKStride + lhi * 8;
+  if (Mg > 0) { A3_LOAD_Q(min(wave * 64, Mg - 1)) }
 
-  float colsum[8];
+  // ---- K tile: 256 keys x 128 dims of head g, global memory -> LDS directly (16 bytes per lane, lane i
+  // lands at base + 16 i).  One wave instruction brings 4 keys x 256 B; instruction j of wave w covers
+  // keys 4 (4 j + w) .. +3.  The lane fetches piece (slot ^ key % 16) of its key, so LDS slot s of key
+  // r holds piece s ^ (r % 16) and the 16 keys a quarter wave reads at one piece index touch all 64
+  // banks once.  Inline assembly: the compiler then does not track these as LDS writes (it would
+  // wait for all of them before every LDS read); the explicit wait below covers them.
+  {
+    const int drow = 4 * wave + (lane >> 4);                   // key of the lane in instruction 0
+    const int dpiece = (lane & 15) ^ (drow & 15);              // (4 (4 j + w) + lane/16) % 16 does not depend on j
+    const uint32_t lds_k = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds_raw;
 #pragma unroll
-  for (int kb = 0; kb < 8; ++kb) colsum[kb] = 0.f;
+    for (int j = 0; j < kTileKeysMfma / 16; ++j) {
+      const int row = min(s + i0 + drow + 16 * j, a.T - 1);    // tail rows: loaded, masked below
+      const bf16_t *gp = K + ((size_t)row * a.Hkv + g) * kD + dpiece * 8;
+      asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
+                   :: "s"(__builtin_amdgcn_readfirstlane(lds_k + 4 * (4 * j + wave) * kKRowBytes)), "v"(gp) : "memory");
+    }
+  }
+  __builtin_amdgcn_s_waitcnt(0);                               // Q fragments and this wave's part of the tile
+  __syncthreads();
+  constexpr int kKB = kTileKeysMfma / 32;                      // 32-key blocks per tile
+  const int n_kb = min(kKB, (N - i0 + 31) / 32);                 // key blocks with at least one real key
+  // fragment read: key 32 kb + l32, piece 2 ks + lhi -> slot (2 ks + lhi) ^ (l32 % 16)
+  const unsigned char *kt = lds_raw + l32 * kKRowBytes;
+  const int kswz = (lhi ^ (l32 & 15)) * 16;
+
+  float colsum[kKB];
+#pragma unroll
+  for (int kb = 0; kb < kKB; ++kb) colsum[kb] = 0.f;
 
   for (int rb0 = wave * 64; rb0 < Mg; rb0 += 256) {            // this wave's rows rb0 .. rb0+63
-    // Q fragments of the two 32-row blocks (rows past Mg are clamped and ignored later)
-    bf16x8 qf[2][kD / 16];
-    int row_id[2];
-#pragma unroll
-    for (int b = 0; b < 2; ++b) {
-      const int m = min(rb0 + b * 32 + l32, Mg - 1);
-      row_id[b] = (qrow0 + m / G) * a.Hq + g * G + m % G;      // row of the [sum q_len * Hq] row space
-      const bf16_t *qp = Q + (size_t)row_id[b] * kD + lhi * 8;
-#pragma unroll
-      for (int ks = 0; ks < kD / 16; ++ks) qf[b][ks] = *reinterpret_cast<const bf16x8 *>(qp + ks * 16);
-    }
+    if (rb0 != wave * 64) { A3_LOAD_Q(rb0) }
     if (PASS == 1) {
-      // (max, 1/sum) of this wave's 64 rows, read back as broadcasts below; rows past Mg contribute 0
+      // max + log2(sum) of this wave's 64 rows, read back as broadcasts below; rows past Mg contribute 0
       const int m = rb0 + lane;
-      float2 st = make_float2(INFINITY, 0.f);                  // exp2(x - inf) * 0 = 0
-      if (m < Mg) st = a.stats[(qrow0 + m / G) * a.Hq + g * G + m % G];
+      float st = INFINITY;                                     // exp2(x - inf) = 0
+      if (m < Mg) st = a.stats[(qrow0 + m / G) * a.Hq + g * G + m % G].x;
       St[wave * 64 + lane] = st;                               // same-wave write/read: no barrier needed
     }
     float run_max[2] = {-INFINITY, -INFINITY}, run_sum[2] = {0.f, 0.f};
@@ -174,7 +183,7 @@ scores_bf16_kernel(scores_args a) {
         for (int x = 0; x < 16; ++x) acc[b][x] = 0.f;
 #pragma unroll
       for (int ks = 0; ks < kD / 16; ++ks) {
-        const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(kt + kb * 32 * kKStride + ks * 16);
+        const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(kt + kb * 32 * kKRowBytes + ((32 * ks) ^ kswz));
 #pragma unroll
         for (int b = 0; b < 2; ++b) {
           if (PASS == 0) acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[b][ks], acc[b], 0, 0, 0);   // C[key][row]
@@ -209,8 +218,8 @@ scores_bf16_kernel(scores_args a) {
         for (int b = 0; b < 2; ++b)
 #pragma unroll
           for (int x = 0; x < 16; ++x) {
-            const float2 st = St[wave * 64 + b * 32 + 8 * (x >> 2) + 4 * lhi + (x & 3)];
-            part += fast_exp2(fmaf(acc[b][x], a.scale2, -st.x)) * st.y;
+            const float st = St[wave * 64 + b * 32 + 8 * (x >> 2) + 4 * lhi + (x & 3)];
+            part += fast_exp2(fmaf(acc[b][x], a.scale2, -st));
           }
         colsum[kb] += part;
       }
@@ -224,15 +233,16 @@ scores_bf16_kernel(scores_args a) {
       }
     }
   }
+#undef A3_LOAD_Q
   if (PASS == 1) {
 #pragma unroll
-    for (int kb = 0; kb < 8; ++kb) {
+    for (int kb = 0; kb < kKB; ++kb) {
       const float v = halves_sum(colsum[kb]);
       if (lhi == 0) red[wave * kTileKeysMfma + kb * 32 + l32] = v;
     }
     __syncthreads();
     const int key = i0 + tid;
-    if (key < N)
+    if (tid < kTileKeysMfma && key < N)
       a.part_scores[(size_t)g * a.T + s + key] = (red[tid] + red[kTileKeysMfma + tid]) +
                                                  (red[2 * kTileKeysMfma + tid] + red[3 * kTileKeysMfma + tid]);
   }
@@ -303,8 +313,7 @@ scores_f32_kernel(scores_args a) {
         for (int off = 32; off > 0; off >>= 1) e += __shfl_xor(e, off, 64);
         if (key == 0 && m < Mg) a.part[(size_t)blockIdx.x * a.total_rows + row_id] = make_float2(mx, e);
       } else if (m < Mg) {
-        float2 st = a.stats[row_id];
-        colsum += exp2f(l - st.x) * st.y;
+        colsum += exp2f(l - a.stats[row_id].x);
       }
     }
   }
@@ -356,7 +365,7 @@ extern "C" a3_status a3_question_scores(const a3_layout *L, const void *q_questi
   a.n_req = L->n_req; a.Hq = L->n_q_heads; a.Hkv = L->n_kv_heads; a.d = L->head_dim; a.T = L->total_tokens;
   a.total_rows = (int)total_rows; a.n_tiles = n_tiles; a.tile_keys = tk;
   a.scale2 = a3_scale_of(L) * kLog2e;
-  dim3 cgrid((unsigned)((total_rows + 31) / 32));
+  dim3 cgrid((unsigned)((total_rows + 15) / 16));
   if (L->dtype == A3_BF16) {
     static bool attr_done = false;
     if (!attr_done) {
