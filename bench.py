@@ -71,6 +71,27 @@ def algorithmic_work(w, act_positions):
     }
 
 
+def measured_traffic(workload_name):
+    """HBM bytes per launch of the attention kernel, from the committed summary of two rocprofv3 --pmc
+    runs (FETCH_SIZE, WRITE_SIZE) scaled by the copy kernel of known size; None if there is none for
+    this workload."""
+    path = os.path.join(ROOT, "profiles", "attention_cfg3_hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    vals = {}
+    for line in open(path):
+        if line.startswith("#") or ":" not in line:
+            continue
+        k, v = line.split(":", 1)
+        vals[k.strip()] = v.strip()
+    if vals.get("workload") != workload_name:
+        return None
+    try:
+        return float(vals["traffic_bytes_per_launch"])
+    except (KeyError, ValueError):
+        return None
+
+
 def cpu_baseline(cfg, max_seconds=60.0):
     """The CPU oracle, as it is, on one layer of the same configuration (host cores)."""
     import numpy as np
@@ -102,6 +123,9 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="workload configuration 1..5 (3 = the 16K-context metric)")
     ap.add_argument("--layers", type=int, default=0, help="independent layer buffer sets to cycle (0 = 32 for config 3)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 256 MiB float32 copy kernel (torch.mul by 1) three times: the known-size "
+                         "dispatch that scales the HBM byte counters of a rocprofv3 --pmc run")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -127,6 +151,14 @@ def main():
     def step(i):
         L, B = layers[i % n_layers], bufs[i % n_layers]
         layer.fuse_layer(lay, B, L["x"], L["k_cat"], L["v"], L["wq"], L["wk"], L["wv"])
+
+    if args.calibrate_copy:
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     for i in range(args.warmup):
         step(i)
@@ -209,6 +241,8 @@ def main():
         "scatter_GBs": work["scatter_bytes"] / (per_call_plain["a3_kv_scatter"]["us_per_step"] * 1e-6) / 1e9,
         "proj_TFLOPs": work["proj_flops"] / (per_call_us["a3_selected_qkv_proj_scatter"]["us_per_step"] * 1e-6) / 1e12,
         "attn_TFLOPs": work["attn_flops"] / (per_call_us["a3_fused_attention"]["us_per_step"] * 1e-6) / 1e12,
+        # both passes form every logit once
+        "scores_TFLOPs": 2 * work["scores_flops"] / (per_call_us["a3_question_scores"]["us_per_step"] * 1e-6) / 1e12,
     }
     result = {
         "metric": "fused-context tokens/sec per layer at 16K ctx" if args.config == 3
@@ -221,12 +255,13 @@ def main():
                    "shape": f"h{s.hidden}/Hq{s.n_q_heads}/Hkv{s.n_kv_heads}/d{s.head_dim}"},
         "roofline": {"bound": "mfma", "kernel": "a3_fused_attention (attn_bf16_kernel)", "achieved": attn_tflops,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": attn_tflops / PEAK_BF16_TFLOPS,
-                     "traffic": None, "avg_launch_ms": attn_ms, "flops_per_launch": work["attn_flops"]},
+                     "traffic": measured_traffic(w.name), "avg_launch_ms": attn_ms, "flops_per_launch": work["attn_flops"]},
         "per_call_us": per_call_us,
         "per_call_us_plain_sequence": per_call_plain,
         "derived": {k: round(v, 2) for k, v in derived.items()},
         "fraction_of_peak": {
             "realign_hbm": derived["realign_GBs"] / PEAK_HBM_GBS, "scores_hbm": derived["scores_GBs"] / PEAK_HBM_GBS,
+            "scores_mfma": derived["scores_TFLOPs"] / PEAK_BF16_TFLOPS,
             "scatter_hbm": derived["scatter_GBs"] / PEAK_HBM_GBS, "proj_mfma": derived["proj_TFLOPs"] / PEAK_BF16_TFLOPS,
             "attn_mfma": derived["attn_TFLOPs"] / PEAK_BF16_TFLOPS},
     }
