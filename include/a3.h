@@ -112,6 +112,15 @@ a3_status a3_rope_realign(const a3_layout *layout, const void *k_cat, void *k_fu
 a3_status a3_question_scores(const a3_layout *layout, const void *q_question, const void *k_fused,
                              float *scores, void *ws, size_t ws_bytes, void *stream);
 
+/* Steps 1 and 2 in one call: Eq. 2 followed by Eq. 3, first line.  Same results as a3_rope_realign
+ * (k_cat -> k_fused, bit for bit) followed by a3_question_scores on k_fused; on the bf16 path the first
+ * scoring pass does the rotation itself, so the stale cache is read once instead of the realigned cache
+ * being written, then read.  k_cat: keys at chunk-local positions [T, n_kv_heads, head_dim]; k_fused: same
+ * shape, may be k_cat itself (in place), otherwise no overlap; as with a3_rope_realign only context rows
+ * are written.  Other arguments and errors as for a3_question_scores. */
+a3_status a3_realign_scores(const a3_layout *layout, const void *q_question, const void *k_cat, void *k_fused,
+                            float *scores, void *ws, size_t ws_bytes, void *stream);
+
 /* Step 3, Eq. 3 second line (Re = top_p(s)).  For request r the k_r = sel_start[r+1] -
  * sel_start[r] context rows with the largest scores; equal scores go to the lowest row;
  * sel_idx[sel_start[r] .. sel_start[r+1]) receives packed rows in ascending order.

@@ -19,7 +19,7 @@ A3_OK, A3_ERR_INVALID_ARG, A3_ERR_UNSUPPORTED, A3_ERR_WORKSPACE, A3_ERR_HIP = 0,
 A3_F32, A3_BF16 = 0, 1
 A3_ROPE_INTERLEAVED, A3_ROPE_HALF = 0, 1
 
-EXPORTS = ["a3_workspace_bytes", "a3_layout_prepare", "a3_rope_realign", "a3_question_scores", "a3_topk_select",
+EXPORTS = ["a3_workspace_bytes", "a3_layout_prepare", "a3_rope_realign", "a3_question_scores", "a3_realign_scores", "a3_topk_select",
            "a3_selected_qkv_proj", "a3_selected_qkv_proj_scatter", "a3_kv_scatter", "a3_fused_attention", "a3_active_rows", "a3_strerror", "a3_last_error", "a3_version"]
 
 
@@ -60,13 +60,14 @@ def lib() -> C.CDLL:
     L.a3_layout_prepare.argtypes = [P, V]
     L.a3_rope_realign.argtypes = [P, V, V, V]
     L.a3_question_scores.argtypes = [P, V, V, V, V, C.c_size_t, V]
+    L.a3_realign_scores.argtypes = [P, V, V, V, V, V, C.c_size_t, V]
     L.a3_topk_select.argtypes = [P, V, V, I, V, V, C.c_size_t, V]
     L.a3_selected_qkv_proj.argtypes = [P, V, V, I, V, V, V, V, V, V, V, V, V, V]
     L.a3_selected_qkv_proj_scatter.argtypes = [P, V, V, I, V, V, V, V, V, V, V, V, V, V]
     L.a3_kv_scatter.argtypes = [P, V, V, V, I, V, V, V]
     L.a3_fused_attention.argtypes = [P, V, V, I, V, V, V, V, C.c_size_t, V]
     L.a3_active_rows.argtypes = [P, V, V, I, V, V]
-    for name in ("a3_selected_qkv_proj_scatter", "a3_active_rows", "a3_layout_prepare", "a3_rope_realign", "a3_question_scores", "a3_topk_select",
+    for name in ("a3_realign_scores", "a3_selected_qkv_proj_scatter", "a3_active_rows", "a3_layout_prepare", "a3_rope_realign", "a3_question_scores", "a3_topk_select",
                  "a3_selected_qkv_proj", "a3_selected_qkv_proj_scatter", "a3_kv_scatter", "a3_fused_attention"):
         getattr(L, name).restype = I
     L.a3_strerror.restype = C.c_char_p
@@ -179,6 +180,12 @@ def a3_question_scores(layout: Layout, q_question: torch.Tensor, k_fused: torch.
                        ws: torch.Tensor, stream=None) -> None:
     _check(lib().a3_question_scores(layout.ref, _ptr(q_question), _ptr(k_fused), _ptr(scores), _ptr(ws),
                                     ws.numel() if ws is not None else 0, _stream(stream)), "a3_question_scores")
+
+
+def a3_realign_scores(layout: Layout, q_question: torch.Tensor, k_cat: torch.Tensor, k_fused: torch.Tensor,
+                      scores: torch.Tensor, ws: torch.Tensor, stream=None) -> None:
+    _check(lib().a3_realign_scores(layout.ref, _ptr(q_question), _ptr(k_cat), _ptr(k_fused), _ptr(scores), _ptr(ws),
+                                   ws.numel() if ws is not None else 0, _stream(stream)), "a3_realign_scores")
 
 
 def a3_topk_select(layout: Layout, scores: torch.Tensor, sel_start: torch.Tensor, total_k: int,

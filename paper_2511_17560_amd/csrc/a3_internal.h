@@ -39,6 +39,13 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 __device__ __forceinline__ float a3_bf2f(bf16_t x) { return (float)x; }
 __device__ __forceinline__ bf16_t a3_f2bf(float x) { return (bf16_t)x; }   // round-to-nearest-even
 
+// (x0, x1) turned by the angle whose (cos, sin) is cs.  One definition, with the contraction written out,
+// for every kernel that realigns cached keys (Eq. 2): they then round alike, bit for bit.
+__device__ __forceinline__ void a3_rotate_pair(float x0, float x1, float2 cs, float &y0, float &y1) {
+  y0 = __fmaf_rn(x0, cs.x, -__fmul_rn(x1, cs.y));
+  y1 = __fmaf_rn(x0, cs.y, __fmul_rn(x1, cs.x));
+}
+
 template <typename T> struct a3_elem;
 template <> struct a3_elem<float> {
   static constexpr int kVec = 4;   // elements per 16-byte vector

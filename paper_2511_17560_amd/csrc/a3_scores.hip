@@ -41,6 +41,12 @@ struct scores_args {
   float *part_scores;       // [Hkv, T] bf16 path: per KV head partial scores
   int n_req, Hq, Hkv, d, T, total_rows, n_tiles, tile_keys;
   float scale2;             // sm_scale * log2(e)
+  // fused position recovery (first pass of the bf16 path only): stale keys in, realigned keys out
+  const void *k_cat;        // [T, Hkv, d] keys at chunk-local positions
+  void *k_out;              // [T, Hkv, d] realigned keys (may be k_cat itself)
+  const int *tok_chunk;     // [T] chunk of a context row, -1 for question rows
+  const float2 *chunk_cs;   // [n_chunks, d/2] (cos, sin) of chunk offset x theta_i
+  int rope_layout;
 };
 
 // ---------------------------------------------------------------------------------------
@@ -101,7 +107,7 @@ __device__ __forceinline__ float halves_sum(float x) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-template <int PASS>
+template <int PASS, bool REALIGN>
 __global__ void __launch_bounds__(256, 2)
 scores_bf16_kernel(scores_args a) {
   extern __shared__ __align__(16) unsigned char lds_raw[];
@@ -141,7 +147,7 @@ scores_bf16_kernel(scores_args a) {
   // r holds piece s ^ (r % 16) and the 16 keys a quarter wave reads at one piece index touch all 64
   // banks once.  Inline assembly: the compiler then does not track these as LDS writes (it would
   // wait for all of them before every LDS read); the explicit wait below covers them.
-  {
+  if (!REALIGN) {
     const int drow = 4 * wave + (lane >> 4);                   // key of the lane in instruction 0
     const int dpiece = (lane & 15) ^ (drow & 15);              // (4 (4 j + w) + lane/16) % 16 does not depend on j
     const uint32_t lds_k = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds_raw;
@@ -151,6 +157,73 @@ scores_bf16_kernel(scores_args a) {
       const bf16_t *gp = K + ((size_t)row * a.Hkv + g) * kD + dpiece * 8;
       asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
                    :: "s"(__builtin_amdgcn_readfirstlane(lds_k + 4 * (4 * j + wave) * kKRowBytes)), "v"(gp) : "memory");
+    }
+  } else {
+    // Position recovery (Eq. 2) on the way in: the tile comes from the stale cache through registers,
+    // every pair is turned by its chunk's offset, and the rounded result goes both to the realigned cache
+    // and, in the same swizzled layout as above, to LDS.  A lane owns the 16-byte pieces c and c + 8 of
+    // a key: in either pairing (adjacent coordinates, or i with i + 64) it then holds whole pairs.
+    const bf16_t *Kc = (const bf16_t *)a.k_cat;               // may be the same buffer as k_out
+    bf16_t *Ko = (bf16_t *)a.k_out;
+    const int c = tid & 7, kr0 = tid >> 3;                     // 32 keys per round, 8 rounds
+    constexpr int kRounds = kTileKeysMfma / 32;
+    // all loads of the stale keys and of their chunk numbers are issued before the first rotation
+    bf16x8 lo[kRounds], hi[kRounds];
+    int chunk[kRounds];
+#pragma unroll
+    for (int j = 0; j < kRounds; ++j) {
+      const int key = kr0 + 32 * j;
+      const int row = min(s + i0 + key, a.T - 1);              // tail rows: loaded, never stored to the cache
+      const size_t off = ((size_t)row * a.Hkv + g) * kD;
+      lo[j] = *reinterpret_cast<const bf16x8 *>(Kc + off + 8 * c);
+      hi[j] = *reinterpret_cast<const bf16x8 *>(Kc + off + 64 + 8 * c);
+      chunk[j] = i0 + key < N ? a.tok_chunk[row] : -1;
+    }
+    // the eight (cos, sin) pairs of this lane's coordinates are reloaded only when the chunk changes
+    // from one of its keys to the next (rarely: a tile spans few chunks)
+    const bool inter = a.rope_layout == A3_ROPE_INTERLEAVED;
+    float2 csr[8];
+    int cur = -1;
+#pragma unroll
+    for (int j = 0; j < kRounds; ++j) {
+      const int key = kr0 + 32 * j;
+      const bool real = i0 + key < N;
+      const int row = min(s + i0 + key, a.T - 1);
+      const size_t off = ((size_t)row * a.Hkv + g) * kD;
+      bf16x8 rlo = lo[j], rhi = hi[j];
+      if (chunk[j] >= 0) {
+        if (chunk[j] != cur) {
+          const float2 *cs = a.chunk_cs + (size_t)chunk[j] * (kD / 2);
+#pragma unroll
+          for (int e = 0; e < 8; ++e)                          // interleaved: pairs 4c..4c+3 and 32+4c..; half: 8c..8c+7
+            csr[e] = inter ? cs[(e < 4 ? 4 * c : 28 + 4 * c) + e] : cs[8 * c + e];
+          cur = chunk[j];
+        }
+        if (inter) {
+#pragma unroll
+          for (int p2 = 0; p2 < 4; ++p2) {
+            float y0, y1;
+            a3_rotate_pair(a3_bf2f(lo[j][2 * p2]), a3_bf2f(lo[j][2 * p2 + 1]), csr[p2], y0, y1);
+            rlo[2 * p2] = a3_f2bf(y0); rlo[2 * p2 + 1] = a3_f2bf(y1);
+            a3_rotate_pair(a3_bf2f(hi[j][2 * p2]), a3_bf2f(hi[j][2 * p2 + 1]), csr[4 + p2], y0, y1);
+            rhi[2 * p2] = a3_f2bf(y0); rhi[2 * p2 + 1] = a3_f2bf(y1);
+          }
+        } else {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {                        // coordinate 8c+e pairs with 64+8c+e
+            float y0, y1;
+            a3_rotate_pair(a3_bf2f(lo[j][e]), a3_bf2f(hi[j][e]), csr[e], y0, y1);
+            rlo[e] = a3_f2bf(y0); rhi[e] = a3_f2bf(y1);
+          }
+        }
+      }
+      if (real) {
+        *reinterpret_cast<bf16x8 *>(Ko + off + 8 * c) = rlo;
+        *reinterpret_cast<bf16x8 *>(Ko + off + 64 + 8 * c) = rhi;
+      }
+      unsigned char *ld = lds_raw + key * kKRowBytes;
+      *reinterpret_cast<bf16x8 *>(ld + ((c ^ (key & 15)) * 16)) = rlo;
+      *reinterpret_cast<bf16x8 *>(ld + (((c + 8) ^ (key & 15)) * 16)) = rhi;
     }
   }
   __builtin_amdgcn_s_waitcnt(0);                               // Q fragments and this wave's part of the tile
@@ -338,8 +411,10 @@ size_t a3_scores_ws_bytes(const a3_layout *L) {
          a3_align_up((size_t)L->n_kv_heads * L->total_tokens * sizeof(float), 256) + 256;
 }
 
-extern "C" a3_status a3_question_scores(const a3_layout *L, const void *q_question, const void *k_fused, float *scores,
-                                        void *ws, size_t ws_bytes, void *stream) {
+// k_cat != nullptr: the first pass of the bf16 path also realigns (k_cat -> k_fused); the fp32 path runs the
+// realign kernel first.
+static a3_status scores_launch(const a3_layout *L, const void *q_question, const void *k_cat, void *k_fused,
+                               float *scores, void *ws, size_t ws_bytes, void *stream) {
   a3_status s = a3_check_layout(L, "a3_question_scores", true);
   if (s != A3_OK) return s;
   A3_REQUIRE(q_question && k_fused && scores, A3_ERR_INVALID_ARG, "a3_question_scores: NULL tensor");
@@ -365,22 +440,33 @@ extern "C" a3_status a3_question_scores(const a3_layout *L, const void *q_questi
   a.n_req = L->n_req; a.Hq = L->n_q_heads; a.Hkv = L->n_kv_heads; a.d = L->head_dim; a.T = L->total_tokens;
   a.total_rows = (int)total_rows; a.n_tiles = n_tiles; a.tile_keys = tk;
   a.scale2 = a3_scale_of(L) * kLog2e;
+  a.k_cat = k_cat; a.k_out = k_fused; a.tok_chunk = L->tok_chunk; a.chunk_cs = (const float2 *)L->rope_chunk_cs;
+  a.rope_layout = L->rope_layout;
+  const bool fuse = k_cat != nullptr && L->dtype == A3_BF16 && L->n_chunks > 0;
+  if (k_cat != nullptr && !fuse) {
+    s = a3_rope_realign(L, k_cat, k_fused, stream);
+    if (s != A3_OK) return s;
+  }
   dim3 cgrid((unsigned)((total_rows + 15) / 16));
   if (L->dtype == A3_BF16) {
     static bool attr_done = false;
     if (!attr_done) {
-      hipError_t e0 = hipFuncSetAttribute((const void *)scores_bf16_kernel<0>, hipFuncAttributeMaxDynamicSharedMemorySize,
+      hipError_t e0 = hipFuncSetAttribute((const void *)scores_bf16_kernel<0, false>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                           (int)kScoresLds);
-      hipError_t e1 = hipFuncSetAttribute((const void *)scores_bf16_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize,
+      hipError_t e1 = hipFuncSetAttribute((const void *)scores_bf16_kernel<1, false>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                           (int)kScoresLds);
+      hipError_t e2 = hipFuncSetAttribute((const void *)scores_bf16_kernel<0, true>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                          (int)kScoresLds);
+      if (e2 != hipSuccess) e0 = e2;
       if (e0 != hipSuccess || e1 != hipSuccess)
         return a3_fail(A3_ERR_HIP, "a3_question_scores: cannot raise the dynamic LDS limit");
       attr_done = true;
     }
     dim3 grid(n_tiles, L->n_kv_heads, L->n_req);
-    hipLaunchKernelGGL(scores_bf16_kernel<0>, grid, dim3(256), kScoresLds, st, a);
+    if (fuse) hipLaunchKernelGGL((scores_bf16_kernel<0, true>), grid, dim3(256), kScoresLds, st, a);
+    else hipLaunchKernelGGL((scores_bf16_kernel<0, false>), grid, dim3(256), kScoresLds, st, a);
     hipLaunchKernelGGL(scores_combine_kernel, cgrid, dim3(256), 0, st, a);
-    hipLaunchKernelGGL(scores_bf16_kernel<1>, grid, dim3(256), kScoresLds, st, a);
+    hipLaunchKernelGGL((scores_bf16_kernel<1, false>), grid, dim3(256), kScoresLds, st, a);
     hipLaunchKernelGGL(scores_head_sum_kernel, dim3((L->total_tokens + 255) / 256), dim3(256), 0, st, a, L->tok_chunk);
   } else {
     dim3 grid(n_tiles, L->n_req);
@@ -390,4 +476,16 @@ extern "C" a3_status a3_question_scores(const a3_layout *L, const void *q_questi
   }
   A3_CHECK_LAUNCH("a3_question_scores");
   return A3_OK;
+}
+
+extern "C" a3_status a3_question_scores(const a3_layout *L, const void *q_question, const void *k_fused, float *scores,
+                                        void *ws, size_t ws_bytes, void *stream) {
+  return scores_launch(L, q_question, nullptr, const_cast<void *>(k_fused), scores, ws, ws_bytes, stream);
+}
+
+extern "C" a3_status a3_realign_scores(const a3_layout *L, const void *q_question, const void *k_cat, void *k_fused,
+                                       float *scores, void *ws, size_t ws_bytes, void *stream) {
+  if (k_cat == nullptr) return a3_fail(A3_ERR_INVALID_ARG, "a3_realign_scores: k_cat is NULL");
+  if (!a3_aligned16(k_cat)) return a3_fail(A3_ERR_INVALID_ARG, "a3_realign_scores: tensors must be 16-byte aligned");
+  return scores_launch(L, q_question, k_cat, k_fused, scores, ws, ws_bytes, stream);
 }

@@ -133,9 +133,7 @@ rope_realign_kernel(const T *k_cat, T *k_fused,   /* may alias: each item reads 
       unpack<T, VEC>(va[u], x);
 #pragma unroll
       for (int p = 0; p < VEC / 2; ++p) {
-        float2 c = cs[p];
-        y[2 * p] = x[2 * p] * c.x - x[2 * p + 1] * c.y;
-        y[2 * p + 1] = x[2 * p] * c.y + x[2 * p + 1] * c.x;
+        a3_rotate_pair(x[2 * p], x[2 * p + 1], cs[p], y[2 * p], y[2 * p + 1]);
       }
       *reinterpret_cast<uint4 *>(k_fused + offa[u]) = pack<T, VEC>(y);
     } else {
@@ -144,9 +142,7 @@ rope_realign_kernel(const T *k_cat, T *k_fused,   /* may alias: each item reads 
       unpack<T, VEC>(vb[u], xb);
 #pragma unroll
       for (int p = 0; p < VEC; ++p) {
-        float2 c = cs[p];
-        ya[p] = xa[p] * c.x - xb[p] * c.y;
-        yb[p] = xa[p] * c.y + xb[p] * c.x;
+        a3_rotate_pair(xa[p], xb[p], cs[p], ya[p], yb[p]);
       }
       *reinterpret_cast<uint4 *>(k_fused + offa[u]) = pack<T, VEC>(ya);
       *reinterpret_cast<uint4 *>(k_fused + offb[u]) = pack<T, VEC>(yb);

@@ -67,14 +67,16 @@ def make_buffers(layout: api.Layout, sel_start: np.ndarray, q_rows: np.ndarray, 
 
 
 def fuse_layer(layout: api.Layout, b: LayerBuffers, x_cur: torch.Tensor, k_cat: torch.Tensor, v_cache: torch.Tensor,
-               wq: torch.Tensor, wk: torch.Tensor, wv: torch.Tensor, stream=None, fused_scatter: bool = True) -> None:
+               wq: torch.Tensor, wk: torch.Tensor, wv: torch.Tensor, stream=None, fused_scatter: bool = True,
+               fused_realign: bool = True) -> None:
     """Runs steps 1-5 for one layer.  ``k_cat`` is read, ``b.k_fused`` and ``v_cache`` (in place)
     hold the fused cache afterwards, ``b.out`` the attention output of the active rows.
 
     ``fused_scatter`` (default) lets the projections write the fresh K/V straight into the caches
     (a3_selected_qkv_proj_scatter); otherwise the plain sequence a3_selected_qkv_proj ->
     a3_kv_scatter is used.  Both give the same cache: the question rows are written before the
-    realign, which only writes context rows, and the selected rows after the scores were read."""
+    realign, which only writes context rows, and the selected rows after the scores were read.
+    ``fused_realign`` (default) runs steps 1 and 2 as one call (a3_realign_scores)."""
     nq = b.n_act - b.total_k
     k = b.total_k
     if b.single:
@@ -86,8 +88,11 @@ def fuse_layer(layout: api.Layout, b: LayerBuffers, x_cur: torch.Tensor, k_cat: 
                                      v_out=b.v_act[k:], stream=stream)
     else:
         api.a3_selected_qkv_proj(layout, x_cur, b.q_rows, nq, wq, None, None, q_out=b.q_question, stream=stream)
-    api.a3_rope_realign(layout, k_cat, b.k_fused, stream=stream)
-    api.a3_question_scores(layout, b.q_question, b.k_fused, b.scores, b.ws, stream=stream)
+    if fused_realign:
+        api.a3_realign_scores(layout, b.q_question, k_cat, b.k_fused, b.scores, b.ws, stream=stream)
+    else:
+        api.a3_rope_realign(layout, k_cat, b.k_fused, stream=stream)
+        api.a3_question_scores(layout, b.q_question, b.k_fused, b.scores, b.ws, stream=stream)
     api.a3_topk_select(layout, b.scores, b.sel_start, k, b.sel_idx, stream=stream)
     rows, n_rows = (b.sel_idx, k) if b.single else (b.act_idx, b.n_act)
     if not b.single:

@@ -197,6 +197,39 @@ def test_question_scores(name):
     assert np.all(np.isneginf(got[w.question_rows()]))
 
 
+@pytest.mark.parametrize("inplace", [False, True])
+@pytest.mark.parametrize("name", NAMES)
+def test_realign_scores_single_call(name, inplace):
+    """a3_realign_scores = a3_rope_realign then a3_question_scores: the realigned cache must equal the one
+    a3_rope_realign writes bit for bit, the scores meet the same bar as test_question_scores."""
+    c = ctx_of(name)
+    w, b, res, lay = c["w"], c["b"], c["res"], c["lay"]
+    dt = w.shape.dtype
+    qq = to_dev(res["q_question"], dt)
+    k_cat = to_dev(b["k_cat"], dt)
+    k_two = torch.zeros_like(k_cat)
+    api.a3_rope_realign(lay, k_cat, k_two)
+    k_one = k_cat.clone() if inplace else torch.zeros_like(k_cat)
+    scores = torch.zeros(w.total_tokens, dtype=torch.float32, device="cuda")
+    ws = lay.workspace(w.total_k + w.total_q)
+    api.a3_realign_scores(lay, qq, k_one if inplace else k_cat, k_one, scores, ws)
+    ctx = np.concatenate([w.ctx_rows(r) for r in range(w.n_req)])
+    assert np.array_equal(to_host(k_one)[ctx], to_host(k_two)[ctx])
+    q = w.question_rows()
+    assert np.array_equal(to_host(k_one)[q], np.asarray(b["k_cat"][q], dtype=np.float64) if inplace else np.zeros_like(to_host(k_one)[q]))
+    got = scores.cpu().numpy().astype(np.float64)
+    # the oracle scored its own realigned keys; ours differ from those by at most one rounding
+    for r in range(w.n_req):
+        rows = w.ctx_rows(r)
+        assert max_abs_rel(got[rows], res["scores"][rows]) <= (1e-4 if dt == "f32" else 2e-2)
+        assert abs(got[rows].sum() - w.shape.n_q_heads * w.q_lens[r]) <= 1e-3 * w.shape.n_q_heads * w.q_lens[r]
+    # and exactly what the two separate calls give
+    scores2 = torch.zeros_like(scores)
+    api.a3_question_scores(lay, qq, k_two, scores2, ws)
+    assert torch.equal(scores, scores2)
+    assert np.all(np.isneginf(got[q]))
+
+
 @pytest.mark.parametrize("name", NAMES)
 def test_topk_select_bit_exact_on_oracle_scores(name):
     c = ctx_of(name)
@@ -259,13 +292,14 @@ def test_fused_attention_with_short_key_segments(name, seg, monkeypatch):
 
 @pytest.mark.parametrize("name", ["cfg1", "ragged-bf16", "batched-bf16-half", "cfg2"])
 def test_chained_layer_plain_six_call_sequence(name):
-    """Same as test_chained_layer, through a3_selected_qkv_proj + a3_kv_scatter instead of the fused
-    projection-and-scatter call."""
-    test_chained_layer(name, fused_scatter=False)
+    """Same as test_chained_layer, through the six plain calls: a3_rope_realign and a3_question_scores
+    instead of a3_realign_scores, a3_selected_qkv_proj + a3_kv_scatter instead of the projection that
+    writes into the caches."""
+    test_chained_layer(name, fused_scatter=False, fused_realign=False)
 
 
 @pytest.mark.parametrize("name", NAMES)
-def test_chained_layer(name, fused_scatter=True):
+def test_chained_layer(name, fused_scatter=True, fused_realign=True):
     """All steps on the GPU's own intermediates.  The selected set must equal the oracle's up to
     near-ties: a row in the symmetric difference must score within 1e-3 (relative) of the
     oracle's k-th score.  Planted rows must be selected.  Downstream tensors are compared on the
@@ -278,7 +312,7 @@ def test_chained_layer(name, fused_scatter=True):
     x = to_dev(t.x_cur, dt)
     k_cat, v_cache = to_dev(b["k_cat"], dt), to_dev(b["v_cat"], dt)
     wq, wk, wv = to_dev(t.wq, dt), to_dev(t.wk, dt), to_dev(t.wv, dt)
-    layer.fuse_layer(lay, bufs, x, k_cat, v_cache, wq, wk, wv, fused_scatter=fused_scatter)
+    layer.fuse_layer(lay, bufs, x, k_cat, v_cache, wq, wk, wv, fused_scatter=fused_scatter, fused_realign=fused_realign)
     torch.cuda.synchronize()
     got_act = bufs.act_idx.cpu().numpy()[:bufs.n_act]
     want_act = res["act_idx"]
