@@ -25,7 +25,7 @@ namespace {
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr int kD = 128;
-constexpr int kAttnWaves = 8;        // waves per workgroup: 0-3 stage V, 4-7 issue the K loads
+constexpr int kAttnWaves = 8;        // waves per workgroup: 0-3 also stage the next K/V tile
 constexpr int kAttnThreads = 64 * kAttnWaves;
 constexpr int kTM = 32 * kAttnWaves; // packed (row, head) pairs per work item: 32 per wave
 constexpr int kTK = 64;             // keys per tile
@@ -181,10 +181,10 @@ attn_bf16_kernel(attn_args a) {
   const float c2 = a.scale2;
 
   // K tile: global memory -> LDS directly (global_load_lds, 16 bytes per lane, lane i lands at base + 16 i).
-  // One wave instruction brings 4 keys x 256 B; instruction j of wave 4 + w covers keys 4 (4 j + w) .. +3.
+  // One wave instruction brings 4 keys x 256 B; instruction j of wave w < 4 covers keys 4 (4 j + w) .. +3.
   // The lane fetches piece (slot ^ key % 16) of its key, so LDS slot s of key r holds piece s ^ (r % 16)
   // and the 16 keys a quarter wave reads at one piece index touch all 64 banks once.
-  const int dwave = wave & 3;                                // K loads are issued by waves 4..7
+  const int dwave = wave & 3;                                // K loads are issued by waves 0..3
   const int drow = 4 * dwave + (lane >> 4);                  // key of the lane in instruction 0
   const int dpiece = (lane & 15) ^ (drow & 15);              // (4 (4 j + w) + lane/16) % 16 does not depend on j
   const uint32_t lds_k = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds_raw;
@@ -193,7 +193,9 @@ attn_bf16_kernel(attn_args a) {
   // V tile: lane = (4 keys, 8 dims), transposed in registers on its way into LDS.
   // 16 consecutive lanes take 16 different key groups: their 8-byte transposed stores land in 128
   // contiguous bytes of one V^T row (all 32 LDS banks) instead of 16 rows at a bank-aligned stride
-  const int vkg = tid & 15, vc = (tid & 255) >> 4;           // V is staged by waves 0..3
+  // Both tiles are staged by waves 0..3: the SIMD serves the older of its two waves first, so these
+  // waves run ahead of waves 4..7 and would otherwise idle at the barrier of every tile
+  const int vkg = tid & 15, vc = (tid & 255) >> 4;
   const int vpos = ((4 * vkg) & ~12) | (((4 * vkg) & 4) << 1) | (((4 * vkg) & 8) >> 1);   // swap key bits 2 and 3
 
   for (;;) {
@@ -285,9 +287,8 @@ attn_bf16_kernel(attn_args a) {
     if (k_begin < k_end) {
       if (wave < 4) {
         A3_GLOAD(k_begin)
-        A3_LSTORE(0)
-      } else {
         A3_KDMA(0, k_begin)
+        A3_LSTORE(0)
       }
     }
     // Everything loaded so far (Q fragments, first tile) has arrived: inside the loop the compiler's
@@ -301,8 +302,7 @@ attn_bf16_kernel(attn_args a) {
       const bool more = k0 + kTK < k_end;
       if (wave < 4) {
         A3_GLOAD(k0 + kTK)                                   // next tile: in flight during everything below
-      } else if (more) {
-        A3_KDMA(buf ^ 1, k0 + kTK)
+        if (more) { A3_KDMA(buf ^ 1, k0 + kTK) }
       }
       const unsigned char *kt = reinterpret_cast<const unsigned char *>(Ks) + buf * (kKTile * 2) + kfrag;
       const bf16_t *vt = Vt + buf * kVTile + l32 * kVStride + lhi * 8;
@@ -396,8 +396,10 @@ attn_bf16_kernel(attn_args a) {
           o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[step & 1][db], pf, o[db], 0, 0, 0);
       }
       if (more) {
-        if (wave < 4) { A3_LSTORE(buf ^ 1) }
-        else __builtin_amdgcn_s_waitcnt(0x0f70);            // vmcnt(0): this wave's K loads have landed
+        if (wave < 4) {
+          A3_LSTORE(buf ^ 1)
+          __builtin_amdgcn_s_waitcnt(0x0f70);               // vmcnt(0): this wave's K loads have landed
+        }
       }
       __syncthreads();
     }
