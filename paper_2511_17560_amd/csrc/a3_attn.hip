@@ -37,20 +37,26 @@ constexpr size_t kAttnLds = (size_t)2 * (kKTile + kVTile) * sizeof(bf16_t);   //
 constexpr int kPlanThreads = 1024;
 
 // Work decomposition written by the plan kernel.
-//   tile  = 128 consecutive packed (row, head) pairs of one request and one KV head group
-//   item  = one tile restricted to a key segment [k_begin, k_end); a tile whose last row sees more
-//           than 1.5 segments of keys is cut into equal segments so that no item is much longer
-//           than the per-CU share of the work; partial results of cut tiles are merged afterwards
+//   tile  = 256 consecutive packed (row, head) pairs of one request and one KV head group; it needs
+//           ceil(visible keys of its last row / 64) key steps
+//   The key steps of all tiles, laid end to end, are cut into P equal shares, one per workgroup of a
+//   KV head (P = workgroups per head, at most one share per 8 steps): every workgroup gets the same
+//   amount of work whatever the mix of short and long tiles.
+//   item  = the part of one share that lies in one tile: (tile, k_begin, k_end).  A tile that lies inside
+//           one share is finished by that workgroup; the others are cut into 2 or more items whose
+//           unnormalised partial results are merged afterwards, in key order.
 struct attn_plan {
   int *a_lo;         // [n_req+1] first active row of each request
   int *tile_start;   // [n_req+1] first tile of each request
   int4 *tile_a;      // [max_tiles] (request, first m, visible keys of the last row, rows*G of the request)
-  int2 *tile_b;      // [max_tiles] (first item, number of segments)
-  int4 *items;       // [max_items] (tile, k_begin, k_end, segment) - longest tiles first
-  int *counters;     // [Hkv] work queue heads, then n_tiles, n_items
-  float *part_o;     // [Hkv * max_items][128][128] unnormalised partial O of cut tiles
-  float2 *part_ml;   // [Hkv * max_items][128]      (exponent reference in the exp2 domain, sum)
-  int max_tiles, max_items, seg_len;
+  int2 *tile_b;      // [max_tiles] (first item, number of items)
+  int *tile_pre;     // [max_tiles+1] key steps of all earlier tiles
+  int4 *items;       // [max_items] (tile, k_begin, k_end, 0), in work order
+  int *wg_start;     // [max_wgs+1] first item of each workgroup of a head
+  int *counters;     // n_tiles, n_items, P
+  float *part_o;     // [Hkv * max_items][256][128] unnormalised partial O of cut tiles
+  float2 *part_ml;   // [Hkv * max_items][256]      (exponent reference in the exp2 domain, sum)
+  int max_tiles, max_items, max_wgs;
 };
 
 __device__ __forceinline__ int lower_bound_i32(const int *__restrict__ a, int n, int x) {
@@ -61,13 +67,38 @@ __device__ __forceinline__ int lower_bound_i32(const int *__restrict__ a, int n,
   }
   return lo;
 }
+__device__ __forceinline__ int upper_bound_i32(const int *a, int n, int x) {
+  int lo = 0, hi = n;            // first index with a[i] > x
+  while (lo < hi) {
+    int mid = (lo + hi) >> 1;
+    if (a[mid] <= x) lo = mid + 1; else hi = mid;
+  }
+  return lo;
+}
+
+// exclusive prefix sum over the workgroup (threads in tid order); *total receives the sum
+__device__ __forceinline__ int plan_scan(int v, int *wave_tot, int *total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int inc = v;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    int x = __shfl_up(inc, off, 64);
+    if (lane >= off) inc += x;
+  }
+  __syncthreads();               // wave_tot may still be read by a previous scan
+  if (lane == 63) wave_tot[wave] = inc;
+  __syncthreads();
+  int before = 0, all = 0;
+  for (int w2 = 0; w2 < kPlanThreads / 64; ++w2) { if (w2 < wave) before += wave_tot[w2]; all += wave_tot[w2]; }
+  *total = all;
+  return before + inc - v;
+}
 
 __global__ void __launch_bounds__(kPlanThreads)
 attn_plan_kernel(attn_plan p, const int *__restrict__ act_idx, int n_act, const int *__restrict__ seg_start,
-                 int n_req, int G, int Hkv) {
+                 int n_req, int G, int wgs_per_head) {
   __shared__ int wave_tot[kPlanThreads / 64];
-  __shared__ int carry;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x;
   // active rows are ascending, so the rows of request r are a contiguous range found by bisection
   for (int r = tid; r <= n_req; r += kPlanThreads)
     p.a_lo[r] = r == n_req ? n_act : lower_bound_i32(act_idx, n_act, seg_start[r]);
@@ -79,57 +110,74 @@ attn_plan_kernel(attn_plan p, const int *__restrict__ act_idx, int n_act, const 
       t += ((p.a_lo[r + 1] - p.a_lo[r]) * G + kTM - 1) / kTM;
     }
     p.tile_start[n_req] = t;
-    carry = 0;
   }
   __syncthreads();
   const int n_tiles = min(p.tile_start[n_req], p.max_tiles);
-  // items are numbered with the tiles in reverse order: within a request later tiles see more keys
+
+  // ---- tiles and the running number of key steps -----------------------------------------
+  int carry = 0;
   for (int base = 0; base < n_tiles; base += kPlanThreads) {
-    const int i = base + tid;
-    int nseg = 0, t = 0, r = 0, j = 0, kv = 0, part = 0;
-    if (i < n_tiles) {
-      t = n_tiles - 1 - i;
-      // request of tile t: last r with tile_start[r] <= t
-      int lo = 0, hi = n_req;
-      while (lo < hi) { int mid = (lo + hi) >> 1; if (p.tile_start[mid] <= t) lo = mid + 1; else hi = mid; }
-      r = lo - 1;
-      j = t - p.tile_start[r];
+    const int t = base + tid;
+    int steps = 0;
+    if (t < n_tiles) {
+      const int r = upper_bound_i32(p.tile_start, n_req, t) - 1;     // last r with tile_start[r] <= t
+      const int j = t - p.tile_start[r];
       const int nr = p.a_lo[r + 1] - p.a_lo[r];
       int last = ((j + 1) * kTM - 1) / G;
       if (last > nr - 1) last = nr - 1;
-      kv = act_idx[p.a_lo[r] + last] - seg_start[r] + 1;
-      nseg = 2 * kv <= 3 * p.seg_len ? 1 : (kv + p.seg_len - 1) / p.seg_len;
-      part = (((kv + nseg - 1) / nseg) + kTK - 1) / kTK * kTK;
+      const int kv = act_idx[p.a_lo[r] + last] - seg_start[r] + 1;
+      steps = (kv + kTK - 1) / kTK;
       p.tile_a[t] = make_int4(r, j * kTM, kv, nr * G);
     }
-    // workgroup exclusive scan of nseg
-    int inc = nseg;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-      int x = __shfl_up(inc, off, 64);
-      if (lane >= off) inc += x;
+    int total;
+    const int before = plan_scan(steps, wave_tot, &total);
+    if (t < n_tiles) p.tile_pre[t] = carry + before;
+    carry += total;
+  }
+  const int W = carry;                                       // key steps of one head, >= n_tiles
+  if (tid == 0) p.tile_pre[n_tiles] = W;
+  __syncthreads();
+
+  // ---- equal shares ------------------------------------------------------------------------
+  int P = (W + 7) / 8;
+  if (P > wgs_per_head) P = wgs_per_head;
+  if (P > p.max_wgs) P = p.max_wgs;
+  if (P < 1) P = 1;
+  int t0 = 0, cnt = 0;
+  long long s_beg = 0, s_end = 0;
+  if (tid < P && W > 0) {
+    s_beg = (long long)tid * W / P;
+    s_end = (long long)(tid + 1) * W / P;
+    if (s_end > s_beg) {
+      t0 = upper_bound_i32(p.tile_pre, n_tiles + 1, (int)s_beg) - 1;
+      const int t1 = lower_bound_i32(p.tile_pre, n_tiles + 1, (int)s_end) - 1;
+      cnt = t1 - t0 + 1;
     }
-    if (lane == 63) wave_tot[wave] = inc;
-    __syncthreads();
-    int before = carry;
-    for (int w2 = 0; w2 < wave; ++w2) before += wave_tot[w2];
-    const int item0 = before + inc - nseg;
-    if (i < n_tiles) {
-      p.tile_b[t] = make_int2(item0, nseg);
-      for (int sgm = 0; sgm < nseg; ++sgm) {
-        if (item0 + sgm >= p.max_items) break;
-        int kb = min(kv, sgm * part), ke = min(kv, (sgm + 1) * part);
-        p.items[item0 + sgm] = make_int4(t, kb, ke, sgm);
-      }
-    }
-    __syncthreads();
-    if (tid == kPlanThreads - 1) carry = before + inc;
-    __syncthreads();
+  }
+  int n_items;
+  const int first = plan_scan(cnt, wave_tot, &n_items);
+  if (tid < P) p.wg_start[tid] = min(first, p.max_items);
+  if (tid == 0) p.wg_start[P] = min(n_items, p.max_items);
+  for (int i = 0; i < cnt; ++i) {
+    const int t = t0 + i, idx = first + i;
+    if (idx >= p.max_items) break;
+    const int pre = p.tile_pre[t], nxt = p.tile_pre[t + 1];
+    const int it_b = (int)(s_beg > pre ? s_beg - pre : 0), it_e = (int)((s_end < nxt ? s_end : nxt) - pre);
+    const int kv = p.tile_a[t].z;
+    p.items[idx] = make_int4(t, it_b * kTK, min(kv, it_e * kTK), 0);
+    if (it_b == 0) p.tile_b[t].x = idx;
+  }
+  // items of a tile = share boundaries strictly inside it + 1; boundary q lies at floor(q W / P)
+  for (int t = tid; t < n_tiles; t += kPlanThreads) {
+    const long long x = p.tile_pre[t], y = p.tile_pre[t + 1];
+    const long long ub = ((x + 1) * P + W - 1) / W;          // first q with floor(q W / P) > x
+    const long long lb = (y * P + W - 1) / W;                // first q with floor(q W / P) >= y
+    p.tile_b[t].y = (int)(lb > ub ? lb - ub : 0) + 1;
   }
   if (tid == 0) {
-    for (int g = 0; g < Hkv; ++g) p.counters[g] = 0;
-    p.counters[Hkv] = n_tiles;
-    p.counters[Hkv + 1] = min(carry, p.max_items);
+    p.counters[0] = n_tiles;
+    p.counters[1] = min(n_items, p.max_items);
+    p.counters[2] = P;
   }
 }
 
@@ -162,16 +210,16 @@ __device__ __forceinline__ float halves_sum(float x) {
 __device__ __forceinline__ uint32_t pack_lo(uint32_t a, uint32_t b) { return (a & 0xffffu) | (b << 16); }
 __device__ __forceinline__ uint32_t pack_hi(uint32_t a, uint32_t b) { return (a >> 16) | (b & 0xffff0000u); }
 
-// Persistent workgroups: each pops items of its KV head from the head's queue until it is empty.
+// One workgroup per share of a KV head's work: it runs the items of its share in order.
 __global__ void __launch_bounds__(kAttnThreads, 1)
 attn_bf16_kernel(attn_args a) {
   extern __shared__ __align__(16) unsigned char lds_raw[];
   bf16_t *Ks = reinterpret_cast<bf16_t *>(lds_raw);          // [2][64][128], swizzled
   bf16_t *Vt = Ks + 2 * kKTile;                              // [2][128][kVStride]
-  __shared__ int sh_item;
 
-  const int g = blockIdx.x % a.Hkv;
-  const int n_items = a.plan.counters[a.Hkv + 1];
+  const int g = blockIdx.x % a.Hkv, wg = blockIdx.x / a.Hkv;
+  if (wg >= a.plan.counters[2]) return;
+  const int item_begin = a.plan.wg_start[wg], item_end = a.plan.wg_start[wg + 1];
   const int G = a.Hq / a.Hkv;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, lhi = lane >> 5;
@@ -198,12 +246,8 @@ attn_bf16_kernel(attn_args a) {
   const int vkg = tid & 15, vc = (tid & 255) >> 4;
   const int vpos = ((4 * vkg) & ~12) | (((4 * vkg) & 4) << 1) | (((4 * vkg) & 8) >> 1);   // swap key bits 2 and 3
 
-  for (;;) {
-    if (tid == 0) sh_item = atomicAdd(&a.plan.counters[g], 1);
-    __syncthreads();
-    const int item = sh_item;
-    __syncthreads();
-    if (item >= n_items) break;                            // uniform over the workgroup
+  for (int item = item_begin; item < item_end; ++item) {
+    __syncthreads();                                       // the LDS tiles of the previous item are free
     const int4 it = a.plan.items[item];
     const int4 ta = a.plan.tile_a[it.x];
     const int nseg = a.plan.tile_b[it.x].y;
@@ -447,7 +491,7 @@ attn_bf16_kernel(attn_args a) {
 __global__ void __launch_bounds__(256)
 attn_combine_kernel(attn_args a) {
   const int t = blockIdx.x, g = blockIdx.y;
-  if (t >= a.plan.counters[a.Hkv]) return;
+  if (t >= a.plan.counters[0]) return;
   const int2 tb = a.plan.tile_b[t];
   const int nseg = tb.y;
   if (nseg <= 1) return;
@@ -559,23 +603,18 @@ int attn_max_tiles(const a3_layout *L, int n_act) {
   return (int)(((long long)n_act * G + kTM - 1) / kTM) + L->n_req;
 }
 
-// Segment length for cutting long tiles: 4096 keys, or 1/8 of the longest request if that is more.
-int attn_seg_len(const a3_layout *L) {
-  const int max_len = L->max_ctx_len + L->max_q_len;
-  int seg = ((max_len + 7) / 8 + kTK - 1) / kTK * kTK;
-  int floor_len = 4096;
-  if (const char *e = getenv("A3_ATTN_SEG")) {          // tuning override, multiple of 64
+// Workgroups per KV head: one per CU over all heads (256 CUs), or the tuning override A3_ATTN_WGS.
+int attn_wgs_per_head(const a3_layout *L) {
+  int w = (256 + L->n_kv_heads - 1) / L->n_kv_heads;
+  if (const char *e = getenv("A3_ATTN_WGS")) {
     int v = atoi(e);
-    if (v >= 256) floor_len = v / kTK * kTK;
+    if (v >= 1 && v <= kPlanThreads) w = v;
   }
-  return seg > floor_len ? seg : floor_len;
+  return w;
 }
 
-int attn_max_items(const a3_layout *L, int n_act) {
-  const int max_len = L->max_ctx_len + L->max_q_len;
-  const int seg = attn_seg_len(L);
-  return attn_max_tiles(L, n_act) * ((max_len + seg - 1) / seg);
-}
+// every tile starts an item, every share boundary inside a tile starts another
+int attn_max_items(const a3_layout *L, int n_act) { return attn_max_tiles(L, n_act) + attn_wgs_per_head(L); }
 
 }  // namespace
 
@@ -584,7 +623,8 @@ size_t a3_attn_ws_bytes(const a3_layout *L, int max_active_rows) {
   const size_t per_req = a3_align_up((size_t)(L->n_req + 1) * sizeof(int), 256);
   const size_t tiles = attn_max_tiles(L, max_active_rows), items = attn_max_items(L, max_active_rows);
   return 2 * per_req + a3_align_up(tiles * sizeof(int4), 256) + a3_align_up(tiles * sizeof(int2), 256) +
-         a3_align_up(items * sizeof(int4), 256) + a3_align_up((size_t)(L->n_kv_heads + 2) * sizeof(int), 256) +
+         a3_align_up((tiles + 1) * sizeof(int), 256) + a3_align_up(items * sizeof(int4), 256) +
+         a3_align_up((size_t)(attn_wgs_per_head(L) + 1) * sizeof(int), 256) + 256 +
          a3_align_up(items * L->n_kv_heads * kTM * kD * sizeof(float), 256) +
          a3_align_up(items * L->n_kv_heads * kTM * sizeof(float2), 256) + 2048;
 }
@@ -619,23 +659,23 @@ extern "C" a3_status a3_fused_attention(const a3_layout *L, const void *q_act, c
       attr_done = true;
     }
     const int max_tiles = attn_max_tiles(L, n_act), max_items = attn_max_items(L, n_act);
+    const int wgs_per_head = attn_wgs_per_head(L);
     const int Hkv = L->n_kv_heads;
     a3_ws_cursor cur(ws, ws_bytes);
     a.plan.a_lo = (int *)cur.take((size_t)(L->n_req + 1) * sizeof(int));
     a.plan.tile_start = (int *)cur.take((size_t)(L->n_req + 1) * sizeof(int));
     a.plan.tile_a = (int4 *)cur.take((size_t)max_tiles * sizeof(int4));
     a.plan.tile_b = (int2 *)cur.take((size_t)max_tiles * sizeof(int2));
+    a.plan.tile_pre = (int *)cur.take((size_t)(max_tiles + 1) * sizeof(int));
     a.plan.items = (int4 *)cur.take((size_t)max_items * sizeof(int4));
-    a.plan.counters = (int *)cur.take((size_t)(Hkv + 2) * sizeof(int));
+    a.plan.wg_start = (int *)cur.take((size_t)(wgs_per_head + 1) * sizeof(int));
+    a.plan.counters = (int *)cur.take(4 * sizeof(int));
     a.plan.part_o = (float *)cur.take((size_t)max_items * Hkv * kTM * kD * sizeof(float));
     a.plan.part_ml = (float2 *)cur.take((size_t)max_items * Hkv * kTM * sizeof(float2));
-    a.plan.max_tiles = max_tiles; a.plan.max_items = max_items; a.plan.seg_len = attn_seg_len(L);
+    a.plan.max_tiles = max_tiles; a.plan.max_items = max_items; a.plan.max_wgs = wgs_per_head;
     hipLaunchKernelGGL(attn_plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, a.plan, act_idx, n_act, L->seg_start,
-                       L->n_req, L->n_q_heads / L->n_kv_heads, Hkv);
-    // persistent workgroups, one per CU; blockIdx % Hkv = KV head, so with 8 KV heads each XCD's L2
-    // serves the K/V of one head
-    int wgs_per_head = (256 + Hkv - 1) / Hkv;
-    if (wgs_per_head > max_items) wgs_per_head = max_items;
+                       L->n_req, L->n_q_heads / L->n_kv_heads, wgs_per_head);
+    // blockIdx % Hkv = KV head, so with 8 KV heads each XCD's L2 serves the K/V of one head
     hipLaunchKernelGGL(attn_bf16_kernel, dim3((unsigned)wgs_per_head * Hkv), dim3(kAttnThreads), kAttnLds, st, a);
     hipLaunchKernelGGL(attn_combine_kernel, dim3((unsigned)max_tiles, Hkv, kTM / 32), dim3(256), 0, st, a);
   } else {

@@ -273,12 +273,14 @@ def test_fused_attention(name):
     assert max_abs_rel(to_host(out), res["out"]) <= tol(w)
 
 
-@pytest.mark.parametrize("seg", ["256", "512"])
-@pytest.mark.parametrize("name", ["ragged-bf16", "batched-bf16-half", "g7-bf16", "cfg2"])
-def test_fused_attention_with_short_key_segments(name, seg, monkeypatch):
-    """Forces the split of tiles into key segments (normally only beyond ~6K visible keys) on the
-    small workloads: partial results, rows that see nothing of a later segment, ordered merge."""
-    monkeypatch.setenv("A3_ATTN_SEG", seg)
+@pytest.mark.parametrize("wgs", ["1", "3", "37", "300"])
+@pytest.mark.parametrize("name", ["ragged-bf16", "batched-bf16-half", "g7-bf16", "cfg2", "long-bf16"])
+def test_fused_attention_with_other_share_counts(name, wgs, monkeypatch):
+    """The key steps of all tiles are cut into one equal share per workgroup of a KV head.  Other
+    numbers of workgroups move the cuts: none at all (1), a few long shares, many short ones (tiles
+    cut into several items, items that start or end exactly on a tile boundary, rows that see nothing
+    of a later item, ordered merge of the partial results)."""
+    monkeypatch.setenv("A3_ATTN_WGS", wgs)
     c = ctx_of(name)
     w, res, lay = c["w"], c["res"], c["lay"]
     s = w.shape
