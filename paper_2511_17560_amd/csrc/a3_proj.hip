@@ -80,6 +80,12 @@ proj_bf16_kernel(proj_args a) {
   const int hp = xcd + 8 * (q / a.n_tok_tiles), tt = q % a.n_tok_tiles;
   if (hp >= a.n_pairs) return;
   const int n_heads = a.Hq + 2 * a.Hkv;
+  {
+    // a pair whose two heads both have no output (Q-only or K/V-only calls) has nothing to do
+    const head_sel h0 = select_head(min(2 * hp, n_heads - 1), a.Hq, a.Hkv);
+    const head_sel h1 = select_head(min(2 * hp + 1, n_heads - 1), a.Hq, a.Hkv);
+    if (a.out[h0.which] == nullptr && (2 * hp + 1 >= n_heads || a.out[h1.which] == nullptr)) return;
+  }
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, lhi = lane >> 5;
   const int fh = wave & 1, th = wave >> 1;
@@ -153,8 +159,10 @@ proj_bf16_kernel(proj_args a) {
     _Pragma("unroll") for (int fb = 0; fb < 4; ++fb)                                                         \
       WF[fb] = *reinterpret_cast<const bf16x8 *>((ST) + frag_w + fb * 32 * kRowBytes + (SLOT));              \
   }
+  // (a wave whose head has no output multiplies all the same: its partner in the pair sets the pace, and
+  // a guard around the MFMAs turns into execution-mask juggling and branches between them)
 #define A3_MFMAS(WF, XF)                                                                                     \
-  if (compute) {                                                                                             \
+  {                                                                                                          \
     _Pragma("unroll") for (int fb = 0; fb < 4; ++fb)                                                         \
       _Pragma("unroll") for (int tb = 0; tb < TB; ++tb)                                                      \
         acc[fb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(WF[fb], XF[tb], acc[fb][tb], 0, 0, 0);         \
@@ -173,10 +181,27 @@ proj_bf16_kernel(proj_args a) {
   __builtin_amdgcn_s_barrier();                                     // ... and everybody's
   A3_ISSUE(kStages - 1, min((kStages - 1) * kBK, k_last))
   A3_FRAGS(wf0, xf0, lds, slot_k0)
+  // A wave that issues an LDS read or a vector-memory instruction is held until the unit takes it, and
+  // with one wave per SIMD nothing else fills that time: a batch of seven reads in front of twelve
+  // MFMAs costs about a sixth of their run time (measured on a register-only copy of this loop).  So
+  // every read and every load is issued on its own, right after an MFMA, whose 32 cycles in the matrix
+  // pipe cover it.  A3_FENCE keeps the compiler from regrouping them.
+#define A3_FENCE __builtin_amdgcn_sched_barrier(0);
+#define A3_FRAG1(I, WF, XF, ST, SLOT)                                                                          \
+  if ((I) < TB) XF[(I) < TB ? (I) : 0] = *reinterpret_cast<const bf16x8 *>((ST) + frag_x + ((I) < TB ? (I) : 0) * 32 * kRowBytes + (SLOT)); \
+  else if ((I) < TB + 4) WF[(I) - TB < 4 && (I) >= TB ? (I) - TB : 0] = *reinterpret_cast<const bf16x8 *>((ST) + frag_w + ((I) - TB < 4 && (I) >= TB ? (I) - TB : 0) * 32 * kRowBytes + (SLOT));
   for (int sl = 0; sl < n_slabs; ++sl) {
     const unsigned char *st = lds + (sl % kStages) * kStageBytes;
-    A3_FRAGS(wf1, xf1, st, slot_k1)
-    A3_MFMAS(wf0, xf0)
+    // first k-step of the slab; the fragments of its second k-step are read underneath
+    A3_FENCE
+#pragma unroll
+    for (int i = 0; i < 4 * TB; ++i) {
+      const int fb = i / TB, tb = i % TB;
+      acc[fb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf0[fb], xf0[tb], acc[fb][tb], 0, 0, 0);
+      A3_FENCE
+      A3_FRAG1(i, wf1, xf1, st, slot_k1)
+      A3_FENCE
+    }
     // Slab sl+1: this wave's loads have landed once only the 2 younger slabs are outstanding, and
     // after the barrier everybody's have.  The barrier also says that every wave has fetched its last
     // fragments of slab sl (lgkmcnt(0) first), whose stage the loads issued next will overwrite.
@@ -184,21 +209,26 @@ proj_bf16_kernel(proj_args a) {
     __builtin_amdgcn_s_waitcnt(vmcnt_imm((kStages - 2) * kLoads) & ~(15 << 8));
     __builtin_amdgcn_s_barrier();
     const unsigned char *sn = lds + ((sl + 1) % kStages) * kStageBytes;
-    A3_FRAGS(wf0, xf0, sn, slot_k0)                             // past the last slab: re-reads a stale stage, unused
-    // the loads of slab sl+4 are spread between the MFMAs instead of hitting the address unit in
-    // one burst from all four waves right after the barrier
+    // second k-step; underneath, the fragments of the next slab's first k-step (past the last slab: a
+    // stale stage, unused) and the loads of slab sl+4
     {
       const uint32_t st_ = ((sl + kStages) % kStages) * kStageBytes;
       const size_t kb_ = (size_t)min((sl + kStages) * kBK, k_last) * sizeof(bf16_t);
+      A3_FENCE
 #pragma unroll
       for (int i = 0; i < 4 * TB; ++i) {
         const int fb = i / TB, tb = i % TB;
-        if (compute) acc[fb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf1[fb], xf1[tb], acc[fb][tb], 0, 0, 0);
+        acc[fb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf1[fb], xf1[tb], acc[fb][tb], 0, 0, 0);
+        A3_FENCE
+        A3_FRAG1(i, wf0, xf0, sn, slot_k0)
         if (i < 4) A3_DMA(wsrc[i] + kb_, st_ + 16 * (4 * i + wave) * kRowBytes);
         else if (i < kLoads) A3_DMA(xsrc[i - 4] + kb_, st_ + kWBytes + 16 * (4 * (i - 4) + wave) * kRowBytes);
+        A3_FENCE
       }
     }
   }
+#undef A3_FENCE
+#undef A3_FRAG1
   __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));                   // drain the tail loads before LDS is released
 #undef A3_DMA
 #undef A3_ISSUE
