@@ -234,66 +234,100 @@ proj_bf16_kernel(proj_args a) {
 #undef A3_ISSUE
 #undef A3_FRAGS
 #undef A3_MFMAS
-  if (!compute) return;
-
   // ---- epilogue: bias, RoPE, one rounding, store -------------------------------------------------------
-  // accumulator block (fb, tb), register r of this lane: feature 32 fb + 8 (r/4) + 4 lhi + r%4,
-  // row tok0 + 32 tb + lane%32
+  // In the accumulators a lane holds one row and, per register quad, 4 consecutive features: stored
+  // from there, every instruction would touch 64 different cache lines, and the (cos, sin) reads
+  // likewise.  Each wave therefore turns its tile through its own piece of the (now free) LDS, one
+  // 32-row block at a time: fp32 [32 rows][128 features], row stride padded to 528 bytes.  Read back,
+  // a lane holds features 4c..4c+3 and 64+4c..64+4c+3 of one row (both RoPE pairings stay inside the
+  // lane), 16 lanes cover a row, and every global access of the wave is made of whole 128-byte runs.
+  __syncthreads();                                           // every wave's tail loads have landed
+  if (!compute) return;
+  constexpr int kEpiStride = 528;                            // bytes per LDS row: 512 + 16 (bank spread)
+  unsigned char *epi = lds + wave * (32 * kEpiStride);
   const int which = hs.which, head = hs.head, heads_out = hs.heads_out;
-  const int fq = lhi * 4;
   const bf16_t *bias = a.bias[which];
+  const int ec = lane & 15, er = lane >> 4;                  // read-back role: chunk of 4 features, row er + 4 j
+  const bool inter = a.rope_layout == A3_ROPE_INTERLEAVED;
+  // rows of this lane in the read-back role and their (cos, sin) table rows, for all blocks at once: the
+  // two dependent index loads of every row are in flight together
+  int src_row[TB][8];
+  const float2 *csrow[TB][8];
+#pragma unroll
+  for (int tb = 0; tb < TB; ++tb)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int tok = min(tok0 + tb * 32 + er + 4 * j, a.n_rows - 1);
+      src_row[tb][j] = a.row_idx ? a.row_idx[tok] : tok;
+    }
+#pragma unroll
+  for (int tb = 0; tb < TB; ++tb)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) csrow[tb][j] = a.pos_cs + (size_t)a.tok_pos[src_row[tb][j]] * (kHeadDim / 2);
+  float bl[4], bh[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    bl[e] = bias ? a3_bf2f(bias[head * kHeadDim + 4 * ec + e]) : 0.f;
+    bh[e] = bias ? a3_bf2f(bias[head * kHeadDim + 64 + 4 * ec + e]) : 0.f;
+  }
 #pragma unroll
   for (int tb = 0; tb < TB; ++tb) {
-    const int tok = tok0 + tb * 32 + l32;
-    if (tok >= a.n_rows) continue;
-    if (bias) {
-#pragma unroll
-      for (int fb = 0; fb < 4; ++fb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r)
-          acc[fb][tb][r] += a3_bf2f(bias[head * kHeadDim + 32 * fb + 8 * (r >> 2) + fq + (r & 3)]);
-    }
-    if (which != 2) {
-      const int src_row = a.row_idx ? a.row_idx[tok] : tok;
-      const float2 *cs = a.pos_cs + (size_t)a.tok_pos[src_row] * (kHeadDim / 2);
-      if (a.rope_layout == A3_ROPE_INTERLEAVED) {
-#pragma unroll
-        for (int fb = 0; fb < 4; ++fb)
-#pragma unroll
-          for (int q4 = 0; q4 < 4; ++q4) {
-            const int f = 32 * fb + 8 * q4 + fq;               // first of 4 consecutive features
-            const float4 t = *reinterpret_cast<const float4 *>(cs + (f >> 1));   // pairs f/2 and f/2+1
-            float x0 = acc[fb][tb][4 * q4], x1 = acc[fb][tb][4 * q4 + 1], x2 = acc[fb][tb][4 * q4 + 2],
-                  x3 = acc[fb][tb][4 * q4 + 3];
-            acc[fb][tb][4 * q4] = x0 * t.x - x1 * t.y;
-            acc[fb][tb][4 * q4 + 1] = x0 * t.y + x1 * t.x;
-            acc[fb][tb][4 * q4 + 2] = x2 * t.z - x3 * t.w;
-            acc[fb][tb][4 * q4 + 3] = x2 * t.w + x3 * t.z;
-          }
-      } else {
-#pragma unroll
-        for (int fb = 0; fb < 2; ++fb)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int p = 32 * fb + 8 * (r >> 2) + fq + (r & 3);  // pair index = feature in the first half
-            const float2 t = cs[p];
-            float xlo = acc[fb][tb][r], xhi = acc[fb + 2][tb][r];
-            acc[fb][tb][r] = xlo * t.x - xhi * t.y;
-            acc[fb + 2][tb][r] = xlo * t.y + xhi * t.x;
-          }
-      }
-    }
-    const int out_row = (a.scatter_kv && which != 0) ? (a.row_idx ? a.row_idx[tok] : tok) : tok;
-    bf16_t *orow = out + ((size_t)out_row * heads_out + head) * kHeadDim;
+    // accumulator block (fb, tb), register r of this lane: feature 32 fb + 8 (r/4) + 4 lhi + r%4, row l32
 #pragma unroll
     for (int fb = 0; fb < 4; ++fb)
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {
-        bf16x4 v;
+        f32x4 v;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = a3_f2bf(acc[fb][tb][4 * q4 + e]);
-        *reinterpret_cast<bf16x4 *>(orow + 32 * fb + 8 * q4 + fq) = v;
+        for (int e = 0; e < 4; ++e) v[e] = acc[fb][tb][4 * q4 + e];
+        *reinterpret_cast<f32x4 *>(epi + l32 * kEpiStride + (32 * fb + 8 * q4 + 4 * lhi) * 4) = v;
       }
+    // (same wave writes and reads: the compiler's wait for the LDS writes is all the ordering needed)
+    // all (cos, sin) reads of the block first, then the arithmetic and the stores
+    float4 t0[8], t1[8];
+    if (which != 2) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        // interleaved: pairs 2 ec, 2 ec + 1 and 32 + 2 ec, ..; half: pairs 4 ec .. 4 ec + 3
+        t0[j] = *reinterpret_cast<const float4 *>(csrow[tb][j] + (inter ? 2 * ec : 4 * ec));
+        t1[j] = *reinterpret_cast<const float4 *>(csrow[tb][j] + (inter ? 32 + 2 * ec : 4 * ec + 2));
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int row = er + 4 * j;
+      const int tok = tok0 + tb * 32 + row;
+      f32x4 lo = *reinterpret_cast<const f32x4 *>(epi + row * kEpiStride + ec * 16);          // features 4 ec ..
+      f32x4 hi = *reinterpret_cast<const f32x4 *>(epi + row * kEpiStride + 256 + ec * 16);    // features 64 + 4 ec ..
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { lo[e] += bl[e]; hi[e] += bh[e]; }
+      if (which != 2) {
+        const float4 c0 = t0[j], c1 = t1[j];
+        if (inter) {
+          f32x4 x = lo;
+          lo[0] = x[0] * c0.x - x[1] * c0.y; lo[1] = x[0] * c0.y + x[1] * c0.x;
+          lo[2] = x[2] * c0.z - x[3] * c0.w; lo[3] = x[2] * c0.w + x[3] * c0.z;
+          x = hi;
+          hi[0] = x[0] * c1.x - x[1] * c1.y; hi[1] = x[0] * c1.y + x[1] * c1.x;
+          hi[2] = x[2] * c1.z - x[3] * c1.w; hi[3] = x[2] * c1.w + x[3] * c1.z;
+        } else {
+          const f32x4 xl = lo, xh = hi;
+          lo[0] = xl[0] * c0.x - xh[0] * c0.y; hi[0] = xl[0] * c0.y + xh[0] * c0.x;
+          lo[1] = xl[1] * c0.z - xh[1] * c0.w; hi[1] = xl[1] * c0.w + xh[1] * c0.z;
+          lo[2] = xl[2] * c1.x - xh[2] * c1.y; hi[2] = xl[2] * c1.y + xh[2] * c1.x;
+          lo[3] = xl[3] * c1.z - xh[3] * c1.w; hi[3] = xl[3] * c1.w + xh[3] * c1.z;
+        }
+      }
+      if (tok < a.n_rows) {
+        const int out_row = (a.scatter_kv && which != 0) ? src_row[tb][j] : tok;
+        bf16_t *orow = out + ((size_t)out_row * heads_out + head) * kHeadDim;
+        bf16x4 vlo, vhi;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { vlo[e] = a3_f2bf(lo[e]); vhi[e] = a3_f2bf(hi[e]); }
+        *reinterpret_cast<bf16x4 *>(orow + 4 * ec) = vlo;
+        *reinterpret_cast<bf16x4 *>(orow + 64 + 4 * ec) = vhi;
+      }
+    }
   }
 }
 
