@@ -161,20 +161,40 @@ topk_select_reg_kernel(const float *__restrict__ scores, const int *__restrict__
   int *__restrict__ out = sel_idx + sel_start[r];
   const float *__restrict__ sc = scores + s;
 
-  // one pad word per 32 keys: a lane reads a contiguous run, and without the pad the runs of all
-  // lanes would start in the same few LDS banks
-  for (int i = tid; i < N; i += kBlock) keys[i + (i >> 5)] = score_key(sc[i]);
-  __syncthreads();
   const int per = (N + kBlock - 1) / kBlock;                 // <= KPT (checked by the host)
   const int first = min(N, tid * per), nv = min(N, first + per) - first;
   uint32_t key[KPT];
   uint32_t mn = 0xffffffffu, mx = 0u;
+  if (per % 4 == 0 && (reinterpret_cast<uintptr_t>(sc) & 15) == 0) {
+    // a lane's run starts on a 16-byte boundary: four scores per load, straight into the registers
 #pragma unroll
-  for (int j = 0; j < KPT; ++j) {
-    const int i = first + min(j, max(nv - 1, 0));
-    key[j] = nv > 0 ? keys[i + (i >> 5)] : 0u;
-    if (j < nv) { mn = min(mn, key[j]); mx = max(mx, key[j]); }
+    for (int q = 0; q < KPT / 4; ++q) {
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (4 * q < nv) {
+        if (4 * q + 4 <= nv) v = *reinterpret_cast<const float4 *>(sc + first + 4 * q);
+        else {                                               // last lane with scores: the run ends inside this vector
+          v.x = sc[first + 4 * q];
+          if (4 * q + 1 < nv) v.y = sc[first + 4 * q + 1];
+          if (4 * q + 2 < nv) v.z = sc[first + 4 * q + 2];
+        }
+      }
+      key[4 * q] = score_key(v.x); key[4 * q + 1] = score_key(v.y);
+      key[4 * q + 2] = score_key(v.z); key[4 * q + 3] = score_key(v.w);
+    }
+  } else {
+    // coalesced through LDS.  One pad word per 32 keys: a lane reads a contiguous run, and without the pad
+    // the runs of all lanes would start in the same few LDS banks
+    for (int i = tid; i < N; i += kBlock) keys[i + (i >> 5)] = score_key(sc[i]);
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < KPT; ++j) {
+      const int i = first + min(j, max(nv - 1, 0));
+      key[j] = nv > 0 ? keys[i + (i >> 5)] : 0u;
+    }
   }
+#pragma unroll
+  for (int j = 0; j < KPT; ++j)
+    if (j < nv) { mn = min(mn, key[j]); mx = max(mx, key[j]); }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) {
     mn = min(mn, (uint32_t)__shfl_xor((int)mn, off, 64));

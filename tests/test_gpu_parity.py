@@ -345,15 +345,20 @@ def test_chained_layer(name, fused_scatter=True, fused_realign=True):
     assert np.array_equal(to_host(v_cache)[stale], res["v_fused"][stale])
 
 
-@pytest.mark.parametrize("case", ["ties", "all-equal", "k-zero-and-full", "long-global-path", "negatives"])
+@pytest.mark.parametrize("case", ["ties", "all-equal", "k-zero-and-full", "long-global-path", "negatives", "vector-tail-4k", "vector-tail-16k"])
 def test_topk_select_edge_cases(case):
     """Top-p on hand-made score arrays, bit-exact against the oracle: heavy ties across the cut,
     all-equal scores (lowest rows win), k = 0 and k = N per request, a request longer than the
-    LDS-staged limit (global re-read path), and scores of both signs with +-0."""
+    register-resident limit (global re-read path), scores of both signs with +-0, and lengths that end
+    inside a lane's vector load."""
     rng = np.random.default_rng(99)
     shape = synth.ModelShape("topk", "f32", 32, 1, 1, 64, 1e4)
     if case == "long-global-path":
         w = synth.custom(shape, [[20000, 20001], [777]], [3, 2], ratio=(10, 100))
+    elif case == "vector-tail-4k":       # 16-byte aligned runs of 4 scores per lane, the last one cut short
+        w = synth.custom(shape, [[4001]], [3], ratio=(10, 100))
+    elif case == "vector-tail-16k":      # runs of 16, the last lane with scores holds 11
+        w = synth.custom(shape, [[8000, 8379]], [2], ratio=(10, 100))
     elif case == "k-zero-and-full":
         w = synth.custom(shape, [[300], [1025, 40], [64]], [2, 2, 2], ratio=(100, 100))
     else:
