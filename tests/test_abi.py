@@ -93,6 +93,18 @@ def test_bad_arguments_are_rejected_before_launch():
         == api.A3_ERR_INVALID_ARG
     assert L.a3_fused_attention(p, None, None, 0, None, None, None, None, 0, None) == api.A3_OK
     assert L.a3_active_rows(p, None, None, 5, None, None) == api.A3_ERR_INVALID_ARG
+    # the single-launch variants check what their plain counterparts check
+    assert L.a3_realign_scores(p, 0x1000, None, 0x1000, 0x1000, 0x1000, 1 << 40, None) == api.A3_ERR_INVALID_ARG
+    assert L.a3_realign_scores(p, 0x1000, 0x1008, 0x1000, 0x1000, 0x1000, 1 << 40, None) == api.A3_ERR_INVALID_ARG
+    assert L.a3_realign_scores(p, 0x1000, 0x1000, None, 0x1000, 0x1000, 1 << 40, None) == api.A3_ERR_INVALID_ARG
+    assert L.a3_realign_scores(p, 0x1000, 0x1000, 0x1000, 0x1000, None, 0, None) == api.A3_ERR_WORKSPACE
+    assert L.a3_realign_scores(p, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 16, None) == api.A3_ERR_WORKSPACE
+    assert L.a3_selected_qkv_proj_scatter(p, 0x1000, None, -3, *([0x1000] * 3), *([None] * 3), *([0x1000] * 3), None) \
+        == api.A3_ERR_INVALID_ARG
+    assert L.a3_selected_qkv_proj_scatter(p, 0x1000, None, 5, None, None, None, *([None] * 3), 0x1000, None, None,
+                                          None) == api.A3_ERR_INVALID_ARG
+    assert L.a3_selected_qkv_proj_scatter(p, 0x1000, None, 0, *([0x1000] * 3), *([None] * 3), *([0x1000] * 3), None) \
+        == api.A3_OK
     f32_d64 = _host_layout(dtype=api.A3_F32, head_dim=64)
     assert L.a3_rope_realign(C.byref(f32_d64), None, None, None) == api.A3_ERR_INVALID_ARG
     bf16_d64 = _host_layout(head_dim=64)
