@@ -63,7 +63,7 @@ def algorithmic_work(w, act_positions):
     return {
         "realign_bytes": 2 * N * row,
         "scores_bytes": N * row,
-        "scores_flops": 2 * N * nq * s.n_q_heads * s.head_dim,
+        "scores_flops": 2 * sum(int(c) * int(q) for c, q in zip(w.ctx_len, w.q_lens)) * s.n_q_heads * s.head_dim,
         "proj_flops": 2 * n_act * s.hidden * (s.n_q_heads + 2 * s.n_kv_heads) * s.head_dim,
         "scatter_bytes": 4 * n_act * row,
         "attn_flops": 4 * s.n_q_heads * s.head_dim * visible,
