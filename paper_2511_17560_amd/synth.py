@@ -17,7 +17,7 @@ All generators are NumPy PCG64 streams seeded with ``1000 * cfg + layer``.
 """
 from __future__ import annotations
 
-from dataclasses import dataclass, field
+from dataclasses import dataclass, field, replace
 from typing import List, Tuple
 
 import numpy as np
@@ -36,15 +36,17 @@ class ModelShape:
     head_dim: int
     rope_base: float
     rope_layout: int = ROPE_INTERLEAVED
+    ffn: int = 0                      # width of the gated MLP (only the layer stack uses it)
+    rms_eps: float = 1e-5
 
     @property
     def group(self) -> int:
         return self.n_q_heads // self.n_kv_heads
 
 
-TINY = ModelShape("tiny", "f32", 512, 8, 8, 64, 10000.0)
-LLAMA3_8B = ModelShape("llama3-8b", "bf16", 4096, 32, 8, 128, 500000.0)
-QWEN25_7B = ModelShape("qwen2.5-7b", "bf16", 3584, 28, 4, 128, 1000000.0)
+TINY = ModelShape("tiny", "f32", 512, 8, 8, 64, 10000.0, ffn=1024)
+LLAMA3_8B = ModelShape("llama3-8b", "bf16", 4096, 32, 8, 128, 500000.0, ffn=14336)
+QWEN25_7B = ModelShape("qwen2.5-7b", "bf16", 3584, 28, 4, 128, 1000000.0, ffn=18944, rms_eps=1e-6)
 
 
 @dataclass
@@ -187,8 +189,7 @@ def config(cfg: int, layer: int = 0, rope_layout: int = ROPE_INTERLEAVED) -> Wor
     lay = np.random.Generator(np.random.PCG64(1000 * cfg + 500_000))   # layout stream: layer independent
 
     def with_layout(s: ModelShape) -> ModelShape:
-        return ModelShape(s.name, s.dtype, s.hidden, s.n_q_heads, s.n_kv_heads, s.head_dim,
-                          s.rope_base, rope_layout)
+        return replace(s, rope_layout=rope_layout)
 
     if cfg == 1:
         return Workload(with_layout(TINY), [_fixed_chunks(4, 128)], [32], (15, 100), 4, seed, "cfg1-tiny-f32")
@@ -282,3 +283,32 @@ def draw_cache(w: Workload, which: str) -> np.ndarray:
     sigma = np.float32(0.02 * np.sqrt(s.hidden))
     x = rng.standard_normal((w.total_tokens, s.n_kv_heads, s.head_dim), dtype=np.float32) * sigma
     return round_to_storage(x, s.dtype)
+
+
+def draw_stack_weights(w: Workload, n_layers: int) -> dict:
+    """Weights of ``n_layers`` decoder blocks and the embedding output of every packed row, all rounded
+    once to the storage type: projections and MLP ~ N(0, 0.02^2) (the output projections wo and w_down
+    scaled by 1/sqrt(2 n_layers), the usual residual-branch scaling), norm weights 1 + 0.1 z, embedding
+    rows ~ N(0,1) with the common question component of ``draw_tensors``.
+    Returns dict(resid0 [T,h], g_final [h], layers=[dict(wq, wk, wv, wo, g_in, g_post, w_gate, w_up, w_down)])."""
+    s = w.shape
+    assert s.ffn > 0
+    rng = np.random.Generator(np.random.PCG64(w.seed + 333_000))
+    T, h, f = w.total_tokens, s.hidden, s.ffn
+    r2s = lambda a: round_to_storage(a, s.dtype)
+    resid0 = rng.standard_normal((T, h), dtype=np.float32)
+    for r in range(w.n_req):
+        rows = w.question_rows(r)
+        u = rng.standard_normal((1, h), dtype=np.float32)
+        resid0[rows] = np.float32(0.7) * u + np.float32(0.7) * rng.standard_normal((len(rows), h), dtype=np.float32)
+    branch = np.float32(1.0 / np.sqrt(2.0 * n_layers))
+    nrm = lambda *shape: rng.standard_normal(shape, dtype=np.float32) * np.float32(0.02)
+    gain = lambda: np.float32(1.0) + np.float32(0.1) * rng.standard_normal(h, dtype=np.float32)
+    layers = []
+    for _ in range(n_layers):
+        layers.append(dict(
+            wq=r2s(nrm(s.n_q_heads * s.head_dim, h)), wk=r2s(nrm(s.n_kv_heads * s.head_dim, h)),
+            wv=r2s(nrm(s.n_kv_heads * s.head_dim, h)), wo=r2s(nrm(h, s.n_q_heads * s.head_dim) * branch),
+            g_in=r2s(gain()), g_post=r2s(gain()),
+            w_gate=r2s(nrm(f, h)), w_up=r2s(nrm(f, h)), w_down=r2s(nrm(h, f) * branch)))
+    return dict(resid0=r2s(resid0), g_final=r2s(gain()), layers=layers)
