@@ -175,6 +175,45 @@ a3_status a3_fused_attention(const a3_layout *layout, const void *q_act, const i
 a3_status a3_active_rows(const a3_layout *layout, const int *sel_idx, const int *sel_start, int n_act,
                          int *act_idx, void *stream);
 
+/* ---- the layer stack around the hot path (Eq. 5, first line: X_l = H(O_{l-1})) -------------------------
+ *
+ * H(.) takes the attention output of a layer to the input of the next one.  The paper gives it as the
+ * layer normalisation and feed-forward network applied to the attention output; taken here as the
+ * pre-norm block of the model families it evaluates:
+ *     r1 = r0 + O Wo^T,   r2 = r1 + (silu(n1 Wg^T) * (n1 Wu^T)) Wd^T  with n1 = RMSNorm(r1; g_post),
+ *     x' = RMSNorm(r2; g_next),        RMSNorm(x; g) = g * x / sqrt(mean(x^2) + eps).
+ * All weights are device pointers in the layout's dtype, [out, in] row-major, 16-byte aligned; the
+ * caller owns them. */
+typedef struct a3_block_weights {
+  const void *wo;      /* [hidden, n_q_heads * head_dim] */
+  const void *g_post;  /* [hidden]  norm in front of the MLP */
+  const void *w_gate;  /* [ffn, hidden] */
+  const void *w_up;    /* [ffn, hidden] */
+  const void *w_down;  /* [hidden, ffn] */
+  const void *g_next;  /* [hidden]  input norm of the next block, or the final norm */
+  int ffn;
+  float eps;
+} a3_block_weights;
+
+/* Bytes of workspace a3_block_tail needs for n_rows rows (host only; 0 on a bad argument). */
+size_t a3_block_tail_ws_bytes(const a3_layout *layout, int ffn, int n_rows);
+
+/* H(.) for the active rows.  attn_out: [n_act, n_q_heads, head_dim] as written by a3_fused_attention;
+ * act_idx: device int32 [n_act], no duplicates (NULL: rows 0 .. n_act-1).  resid: [total_tokens, hidden],
+ * the residual stream; its rows act_idx are read (r0) and overwritten (r2).  hidden_next:
+ * [total_tokens, hidden]; its rows act_idx receive x'.  Other rows of both are left alone.
+ * bf16 needs hidden % 128 == 0 and ffn % 64 == 0.  Errors: A3_ERR_INVALID_ARG, A3_ERR_UNSUPPORTED,
+ * A3_ERR_WORKSPACE before anything is launched. */
+a3_status a3_block_tail(const a3_layout *layout, const void *attn_out, const int *act_idx, int n_act,
+                        const a3_block_weights *w, void *resid, void *hidden_next,
+                        void *ws, size_t ws_bytes, void *stream);
+
+/* RMSNorm of listed rows (the input norm of block 0, in front of the first projection):
+ * out[row_idx[i]] = g * x[row_idx[i]] / sqrt(mean(x[row_idx[i]]^2) + eps), x and out [total_tokens, hidden]
+ * (may be the same buffer); row_idx NULL: rows 0 .. n_rows-1. */
+a3_status a3_rms_norm(const a3_layout *layout, const void *x, const int *row_idx, int n_rows, const void *g,
+                      float eps, void *out, void *stream);
+
 const char *a3_strerror(a3_status status);
 /* Text of the last error raised on the calling thread ("" if none). */
 const char *a3_last_error(void);

@@ -20,7 +20,8 @@ A3_F32, A3_BF16 = 0, 1
 A3_ROPE_INTERLEAVED, A3_ROPE_HALF = 0, 1
 
 EXPORTS = ["a3_workspace_bytes", "a3_layout_prepare", "a3_rope_realign", "a3_question_scores", "a3_realign_scores", "a3_topk_select",
-           "a3_selected_qkv_proj", "a3_selected_qkv_proj_scatter", "a3_kv_scatter", "a3_fused_attention", "a3_active_rows", "a3_strerror", "a3_last_error", "a3_version"]
+           "a3_selected_qkv_proj", "a3_selected_qkv_proj_scatter", "a3_kv_scatter", "a3_fused_attention", "a3_active_rows",
+           "a3_block_tail_ws_bytes", "a3_block_tail", "a3_rms_norm", "a3_strerror", "a3_last_error", "a3_version"]
 
 
 class A3Error(RuntimeError):
@@ -40,6 +41,11 @@ class a3_layout(C.Structure):
         ("tok_pos", C.c_void_p), ("tok_req", C.c_void_p), ("tok_chunk", C.c_void_p), ("q_start", C.c_void_p),
         ("rope_chunk_cs", C.c_void_p), ("rope_pos_cs", C.c_void_p),
     ]
+
+
+class a3_block_weights(C.Structure):
+    _fields_ = [("wo", C.c_void_p), ("g_post", C.c_void_p), ("w_gate", C.c_void_p), ("w_up", C.c_void_p),
+                ("w_down", C.c_void_p), ("g_next", C.c_void_p), ("ffn", C.c_int), ("eps", C.c_float)]
 
 
 _lib = None
@@ -67,6 +73,12 @@ def lib() -> C.CDLL:
     L.a3_kv_scatter.argtypes = [P, V, V, V, I, V, V, V]
     L.a3_fused_attention.argtypes = [P, V, V, I, V, V, V, V, C.c_size_t, V]
     L.a3_active_rows.argtypes = [P, V, V, I, V, V]
+    L.a3_block_tail_ws_bytes.restype = C.c_size_t
+    L.a3_block_tail_ws_bytes.argtypes = [P, I, I]
+    L.a3_block_tail.argtypes = [P, V, V, I, C.POINTER(a3_block_weights), V, V, V, C.c_size_t, V]
+    L.a3_rms_norm.argtypes = [P, V, V, I, V, C.c_float, V, V]
+    L.a3_block_tail.restype = I
+    L.a3_rms_norm.restype = I
     for name in ("a3_realign_scores", "a3_selected_qkv_proj_scatter", "a3_active_rows", "a3_layout_prepare", "a3_rope_realign", "a3_question_scores", "a3_topk_select",
                  "a3_selected_qkv_proj", "a3_selected_qkv_proj_scatter", "a3_kv_scatter", "a3_fused_attention"):
         getattr(L, name).restype = I
@@ -228,3 +240,23 @@ def a3_active_rows(layout: Layout, sel_idx: Optional[torch.Tensor], sel_start: t
                    act_idx: torch.Tensor, stream=None) -> None:
     _check(lib().a3_active_rows(layout.ref, _ptr(sel_idx), _ptr(sel_start), int(n_act), _ptr(act_idx),
                                 _stream(stream)), "a3_active_rows")
+
+
+def a3_block_tail_ws_bytes(layout: Layout, ffn: int, n_rows: int) -> int:
+    return int(lib().a3_block_tail_ws_bytes(layout.ref, int(ffn), int(n_rows)))
+
+
+def a3_block_tail(layout: Layout, attn_out: torch.Tensor, act_idx: Optional[torch.Tensor], n_act: int, wo, g_post,
+                  w_gate, w_up, w_down, g_next, eps: float, resid: torch.Tensor, hidden_next: torch.Tensor,
+                  ws: torch.Tensor, stream=None) -> None:
+    w = a3_block_weights(_ptr(wo), _ptr(g_post), _ptr(w_gate), _ptr(w_up), _ptr(w_down), _ptr(g_next),
+                         int(w_gate.shape[0]), float(eps))
+    _check(lib().a3_block_tail(layout.ref, _ptr(attn_out), _ptr(act_idx), int(n_act), C.byref(w), _ptr(resid),
+                               _ptr(hidden_next), _ptr(ws), ws.numel() if ws is not None else 0, _stream(stream)),
+           "a3_block_tail")
+
+
+def a3_rms_norm(layout: Layout, x: torch.Tensor, row_idx: Optional[torch.Tensor], n_rows: int, g: torch.Tensor,
+                eps: float, out: torch.Tensor, stream=None) -> None:
+    _check(lib().a3_rms_norm(layout.ref, _ptr(x), _ptr(row_idx), int(n_rows), _ptr(g), float(eps), _ptr(out),
+                             _stream(stream)), "a3_rms_norm")

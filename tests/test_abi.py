@@ -105,10 +105,43 @@ def test_bad_arguments_are_rejected_before_launch():
                                           None) == api.A3_ERR_INVALID_ARG
     assert L.a3_selected_qkv_proj_scatter(p, 0x1000, None, 0, *([0x1000] * 3), *([None] * 3), *([0x1000] * 3), None) \
         == api.A3_OK
+    # layer-stack entry points
+    bw = api.a3_block_weights(*([0x1000] * 6), 14336, 1e-5)
+    wp = C.byref(bw)
+    need = L.a3_block_tail_ws_bytes(p, 14336, 1702)
+    assert need >= 1702 * (4096 + 14336) * 2 and L.a3_block_tail_ws_bytes(p, 0, 10) == 0
+    assert L.a3_block_tail_ws_bytes(None, 14336, 10) == 0
+    assert L.a3_block_tail(p, 0x1000, None, 0, wp, 0x1000, 0x1000, None, 0, None) == api.A3_OK        # nothing to do
+    assert L.a3_block_tail(p, 0x1000, None, -1, wp, 0x1000, 0x1000, 0x1000, need, None) == api.A3_ERR_INVALID_ARG
+    assert L.a3_block_tail(p, 0x1000, None, 10, None, 0x1000, 0x1000, 0x1000, need, None) == api.A3_ERR_INVALID_ARG
+    assert L.a3_block_tail(p, None, None, 10, wp, 0x1000, 0x1000, 0x1000, need, None) == api.A3_ERR_INVALID_ARG
+    assert L.a3_block_tail(p, 0x1000, None, 1702, wp, 0x1000, 0x1000, None, 0, None) == api.A3_ERR_WORKSPACE
+    assert L.a3_block_tail(p, 0x1000, None, 1702, wp, 0x1000, 0x1000, 0x1000, need - 1, None) == api.A3_ERR_WORKSPACE
+    no_gate = api.a3_block_weights(0x1000, 0x1000, None, 0x1000, 0x1000, 0x1000, 14336, 1e-5)
+    assert L.a3_block_tail(p, 0x1000, None, 10, C.byref(no_gate), 0x1000, 0x1000, 0x1000, need, None) \
+        == api.A3_ERR_INVALID_ARG
+    odd_ffn = api.a3_block_weights(*([0x1000] * 6), 1000, 1e-5)
+    assert L.a3_block_tail(p, 0x1000, None, 10, C.byref(odd_ffn), 0x1000, 0x1000, 0x1000, need, None) \
+        == api.A3_ERR_UNSUPPORTED
+    neg_eps = api.a3_block_weights(*([0x1000] * 6), 14336, -1.0)
+    assert L.a3_block_tail(p, 0x1000, None, 10, C.byref(neg_eps), 0x1000, 0x1000, 0x1000, need, None) \
+        == api.A3_ERR_INVALID_ARG
+    assert L.a3_rms_norm(p, 0x1000, None, 0, 0x1000, 1e-5, 0x1000, None) == api.A3_OK
+    assert L.a3_rms_norm(p, None, None, 5, 0x1000, 1e-5, 0x1000, None) == api.A3_ERR_INVALID_ARG
+    assert L.a3_rms_norm(p, 0x1000, None, 5, 0x1000, -1.0, 0x1000, None) == api.A3_ERR_INVALID_ARG
+    assert L.a3_rms_norm(p, 0x1004, None, 5, 0x1000, 1e-5, 0x1000, None) == api.A3_ERR_INVALID_ARG
     f32_d64 = _host_layout(dtype=api.A3_F32, head_dim=64)
     assert L.a3_rope_realign(C.byref(f32_d64), None, None, None) == api.A3_ERR_INVALID_ARG
     bf16_d64 = _host_layout(head_dim=64)
     assert L.a3_rope_realign(C.byref(bf16_d64), 0x1000, 0x1000, None) == api.A3_ERR_UNSUPPORTED
+
+
+def test_block_weights_struct_matches_header_order():
+    text = open(os.path.join(ROOT, "include", "a3.h")).read()
+    body = text[text.index("typedef struct a3_block_weights {"):text.index("} a3_block_weights;")]
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    fields = re.findall(r"\b\*?\s*([a-z_]+)\s*;", body)
+    assert fields == [f[0] for f in api.a3_block_weights._fields_]
 
 
 def test_struct_layout_matches_header_order():

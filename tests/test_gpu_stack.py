@@ -1,0 +1,179 @@
+"""GPU parity of the layer-stack entry points (a3_rms_norm, a3_block_tail) and of the whole A^3 schedule
+over a small stack (paper_2511_17560_amd.stack.fuse_stack) against the stack oracle.
+
+Tolerances (max |a-b| / max |b| per tensor unless stated):
+  RMSNorm                      fp32 1e-5; bf16 one rounding of the stored value (2^-7)
+  H(.) (a3_block_tail)         fp32 2e-5; bf16 2e-2 (five stored tensors in a row, each rounded once, and
+                               K up to 14336 products per sum), mean |a-b| <= 2e-3 of the scale
+  stack                        fp32 1e-4; bf16 4e-2 after four blocks, mean |a-b| <= 4e-3 of the scale
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import a3_oracle as ora
+from oracle import stack_oracle as st
+from paper_2511_17560_amd import api, stack, synth
+from gpu_util import idev, max_abs_rel, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+F64 = np.float64
+
+
+def _layout(shape, T):
+    """A one-request layout with T rows; the stack entry points only read sizes from it."""
+    w = synth.custom(shape, [[T - 1]], [1])
+    return api.Layout.from_workload(w)
+
+
+def _mean_rel(got, want):
+    return float(np.abs(got - want).mean()) / float(np.abs(want).max())
+
+
+@pytest.mark.parametrize("dtype,h,T,n", [("f32", 96, 50, 17), ("bf16", 256, 300, 123), ("bf16", 4096, 700, 700),
+                                          ("f32", 512, 9, 9)])
+def test_rms_norm(dtype, h, T, n):
+    rng = np.random.default_rng(7)
+    shape = synth.ModelShape("n", dtype, h, 2, 1, 128 if dtype == "bf16" else 64, 1e4)
+    lay = _layout(shape, T)
+    x = synth.round_to_storage(rng.standard_normal((T, h)).astype(np.float32) * 3.0, dtype)
+    g = synth.round_to_storage(1 + 0.2 * rng.standard_normal(h).astype(np.float32), dtype)
+    idx = np.sort(rng.choice(T, size=n, replace=False)).astype(np.int32)
+    eps = 1e-5
+    want = st.rms_norm(x.astype(F64)[idx], g.astype(F64), eps)
+    xd, gd = to_dev(x, dtype), to_dev(g, dtype)
+    out = torch.full_like(xd, 7.0)
+    api.a3_rms_norm(lay, xd, idev(idx) if n < T else None, n, gd, eps, out)
+    torch.cuda.synchronize()
+    got = to_host(out)
+    assert max_abs_rel(got[idx], want) <= (1e-5 if dtype == "f32" else 2.0 ** -7)
+    rest = np.setdiff1d(np.arange(T), idx)
+    assert np.all(got[rest] == 7.0)
+    # in place
+    api.a3_rms_norm(lay, xd, idev(idx) if n < T else None, n, gd, eps, xd)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_host(xd)[idx], got[idx])
+
+
+TAIL_CASES = {
+    # name: (dtype, hidden, Hq, head_dim, ffn, T, n_act)
+    "f32-tiny": ("f32", 512, 8, 64, 1024, 300, 77),
+    "f32-odd": ("f32", 96, 3, 64, 80, 40, 40),
+    "bf16-small": ("bf16", 1024, 8, 128, 1536, 700, 333),
+    "bf16-ragged-tiles": ("bf16", 384, 3, 128, 448, 500, 261),      # last feature tiles half empty
+    "bf16-one-row": ("bf16", 256, 2, 128, 512, 10, 1),
+    "bf16-llama": ("bf16", 4096, 32, 128, 14336, 2000, 450),
+    "bf16-all-rows": ("bf16", 512, 4, 128, 1024, 640, 640),          # act_idx NULL
+}
+
+
+@pytest.mark.parametrize("case", list(TAIL_CASES))
+def test_block_tail(case):
+    dtype, h, Hq, d, f, T, n = TAIL_CASES[case]
+    rng = np.random.default_rng(sum(map(ord, case)))
+    shape = synth.ModelShape(case, dtype, h, Hq, 8 if Hq % 8 == 0 else 1, d, 1e4, ffn=f)
+    lay = _layout(shape, T)
+    r2s = lambda a: synth.round_to_storage(np.asarray(a, dtype=np.float32), dtype)
+    nrm = lambda *s: rng.standard_normal(s).astype(np.float32)
+    lw = dict(wo=r2s(nrm(h, Hq * d) * 0.02), g_post=r2s(1 + 0.1 * nrm(h)), w_gate=r2s(nrm(f, h) * 0.03),
+              w_up=r2s(nrm(f, h) * 0.03), w_down=r2s(nrm(h, f) * 0.02))
+    g_next = r2s(1 + 0.1 * nrm(h))
+    attn = r2s(nrm(n, Hq, d))
+    resid = r2s(nrm(T, h))
+    idx = np.sort(rng.choice(T, size=n, replace=False)).astype(np.int32)
+    eps = 1e-5
+    want = st.block_tail(attn.astype(F64), resid.astype(F64)[idx], {k: v.astype(F64) for k, v in lw.items()},
+                         g_next.astype(F64), eps, dtype)
+    dev = {k: to_dev(v, dtype) for k, v in lw.items()}
+    resid_d, hid_d = to_dev(resid, dtype), torch.full((T, h), 5.0, dtype=api.torch_dtype(dtype), device="cuda")
+    ws = torch.empty(api.a3_block_tail_ws_bytes(lay, f, n), dtype=torch.uint8, device="cuda")
+    api.a3_block_tail(lay, to_dev(attn, dtype), idev(idx) if n < T else None, n, dev["wo"], dev["g_post"],
+                      dev["w_gate"], dev["w_up"], dev["w_down"], to_dev(g_next, dtype), eps, resid_d, hid_d, ws)
+    torch.cuda.synchronize()
+    got_r, got_x = to_host(resid_d), to_host(hid_d)
+    tol, mtol = (2e-5, 2e-6) if dtype == "f32" else (2e-2, 2e-3)
+    assert max_abs_rel(got_r[idx], want["resid"]) <= tol
+    assert max_abs_rel(got_x[idx], want["hidden_next"]) <= tol
+    assert _mean_rel(got_r[idx], want["resid"]) <= mtol and _mean_rel(got_x[idx], want["hidden_next"]) <= mtol
+    # the MLP branch alone (what the second residual added), so that a slip there cannot hide behind r1
+    assert max_abs_rel(got_r[idx] - want["resid_mid"], want["resid"] - want["resid_mid"]) <= (1e-4 if dtype == "f32" else 6e-2)
+    rest = np.setdiff1d(np.arange(T), idx)
+    assert np.array_equal(got_r[rest], resid.astype(F64)[rest]) and np.all(got_x[rest] == 5.0)
+    # too small a workspace is an error, not a launch
+    with pytest.raises(api.A3Error):
+        api.a3_block_tail(lay, to_dev(attn, dtype), None, n, dev["wo"], dev["g_post"], dev["w_gate"], dev["w_up"],
+                          dev["w_down"], to_dev(g_next, dtype), eps, resid_d, hid_d, ws[:256])
+
+
+STACK_CASES = {
+    "tiny-f32": (synth.ModelShape("tiny-stack", "f32", 128, 4, 2, 64, 10000.0, synth.ROPE_HALF, ffn=192),
+                 [[60, 41, 77]], [9], (20, 100), 3),
+    "batched-f32": (synth.ModelShape("tiny-stack", "f32", 128, 4, 2, 64, 10000.0, synth.ROPE_INTERLEAVED, ffn=192),
+                    [[30, 45], [64]], [5, 7], (30, 100), 4),
+    "small-bf16": (synth.ModelShape("small-stack", "bf16", 256, 4, 2, 128, 500000.0, synth.ROPE_HALF, ffn=512),
+                   [[100, 37, 300, 65]], [19], (15, 100), 4),
+    "batched-bf16": (synth.ModelShape("small-stack", "bf16", 256, 8, 2, 128, 500000.0, synth.ROPE_HALF, ffn=384),
+                     [[130, 70], [33], [257, 64, 90]], [5, 33, 12], (20, 100), 3),
+}
+
+
+@pytest.mark.parametrize("case", list(STACK_CASES))
+def test_fuse_stack(case):
+    """Block 0 on every row, selection at layer 1 on the true keys, rows [Re, Q] afterwards, on caches
+    that a chunk-wise prefill of the same stack produced (oracle, CPU).  The selection must equal the
+    oracle's up to near-ties; the oracle is then run on the GPU's selection and every layer's attention
+    output, the residual stream and the final hidden states are compared on the active rows."""
+    shape, chunk_lens, q_lens, ratio, n_layers = STACK_CASES[case]
+    dt = shape.dtype
+    w = synth.custom(shape, chunk_lens, q_lens, ratio=ratio, seed=77)
+    sw = synth.draw_stack_weights(w, n_layers)
+    # wider query/key weights than the draw's 0.02: at these small widths the logits would otherwise be
+    # nearly flat and every score a near-tie
+    for lw in sw["layers"]:
+        for k in ("wq", "wk"):
+            lw[k] = synth.round_to_storage(lw[k] * np.float32(5.0), dt)
+    layers64 = [{k: v.astype(F64) for k, v in lw.items()} for lw in sw["layers"]]
+    sh = dict(n_q_heads=shape.n_q_heads, n_kv_heads=shape.n_kv_heads, head_dim=shape.head_dim, base=shape.rope_base,
+              layout=shape.rope_layout, sm_scale=1.0 / np.sqrt(shape.head_dim), eps=shape.rms_eps)
+    idx = dict(seg_start=w.seg_start, ctx_len=w.ctx_len, q_len=w.q_lens, chunk_start=w.chunk_start,
+               chunk_len=w.chunk_len, chunk_delta=w.chunk_delta, sel_start=w.sel_start, positions=w.token_positions())
+    r0 = sw["resid0"].astype(F64)
+    g_final = sw["g_final"].astype(F64)
+    k_cat, v_cat = st.precompute_stack_caches(r0, w.chunk_start, w.chunk_len, layers64, g_final, sh, dt)
+    want = st.fuse_stack(r0, k_cat, v_cat, layers64, g_final, sh, storage=dt, **idx)
+
+    lay = api.Layout.from_workload(w)
+    dev_layers = [{k: to_dev(v, dt) for k, v in lw.items()} for lw in sw["layers"]]
+    resid = to_dev(sw["resid0"], dt)
+    got = stack.fuse_stack(lay, shape, dev_layers, to_dev(sw["g_final"], dt), resid, [to_dev(k, dt) for k in k_cat],
+                           [to_dev(v, dt) for v in v_cat], w.sel_start, w.question_rows(), keep=True)
+    torch.cuda.synchronize()
+    got_act = got["act_idx"].cpu().numpy()
+    assert np.all(np.diff(got_act) > 0) and got["n_act"] == len(want["act_idx"])
+    flips = set(got_act.tolist()) ^ set(want["act_idx"].tolist())
+    for r in range(w.n_req):
+        k_r = int(w.sel_start[r + 1] - w.sel_start[r])
+        rows = w.ctx_rows(r)
+        if k_r == 0 or k_r == len(rows):
+            continue
+        kth = np.sort(want["scores"][rows])[::-1][k_r - 1]
+        for row in flips:
+            if rows[0] <= row <= rows[-1]:
+                assert abs(want["scores"][row] - kth) <= 2e-3 * abs(kth), (row, want["scores"][row], kth)
+    assert len(flips) <= max(2, len(got_act) // 25)
+    sc_tol = 1e-4 if dt == "f32" else 2e-2
+    ctx = np.concatenate([w.ctx_rows(r) for r in range(w.n_req)])
+    assert max_abs_rel(to_host(got["scores"])[ctx], want["scores"][ctx]) <= sc_tol
+    if flips:   # same selection on both sides from here on
+        want = st.fuse_stack(r0, k_cat, v_cat, layers64, g_final, sh, storage=dt,
+                             forced_sel_idx=got["sel_idx"].cpu().numpy(), **idx)
+    tol, mtol = (1e-4, 1e-5) if dt == "f32" else (4e-2, 4e-3)
+    for l in range(n_layers):
+        g_out = to_host(got["per_layer"][l]["out"])
+        assert max_abs_rel(g_out, want["per_layer"][l]["out"]) <= tol, l
+        if l >= 1:
+            assert max_abs_rel(to_host(got["per_layer"][l]["k"])[got_act], want["per_layer"][l]["k"][got_act]) <= tol, l
+    g_res, g_hid = to_host(got["resid"])[got_act], to_host(got["hidden"])[got_act]
+    assert max_abs_rel(g_res, want["resid"]) <= tol and _mean_rel(g_res, want["resid"]) <= mtol
+    assert max_abs_rel(g_hid, want["hidden"]) <= tol and _mean_rel(g_hid, want["hidden"]) <= mtol
