@@ -115,6 +115,87 @@ def cpu_baseline(cfg, max_seconds=60.0):
     }
 
 
+def stack_main(args):
+    """--stack L: the A^3 schedule over L decoder blocks (block 0 on every row, selection at layer 1, rows
+    [Re, Q] afterwards) against the plain prefill of the same stack, both through the same library.  Weights,
+    embedding output and chunk caches are drawn on the device (N(0, 0.02^2) weights, N(0, 1) rows, caches with
+    the matched standard deviation)."""
+    import numpy as np
+    import torch
+    from paper_2511_17560_amd import api, stack, synth
+
+    w = synth.config(args.config)
+    s = w.shape
+    dt = api.torch_dtype(s.dtype)
+    lay = api.Layout.from_workload(w)
+    T, h, f, qd, kd = w.total_tokens, s.hidden, s.ffn, s.n_q_heads * s.head_dim, s.n_kv_heads * s.head_dim
+    g = torch.Generator(device="cuda").manual_seed(1000 * args.config + 7)
+    mk = lambda *shape, std=0.02: (torch.randn(*shape, device="cuda", generator=g) * std).to(dt)
+    branch = 1.0 / (2.0 * args.stack) ** 0.5
+    layers = [dict(wq=mk(qd, h), wk=mk(kd, h), wv=mk(kd, h), wo=mk(h, qd, std=0.02 * branch), g_in=mk(h, std=0.1) + 1,
+                   g_post=mk(h, std=0.1) + 1, w_gate=mk(f, h), w_up=mk(f, h), w_down=mk(h, f, std=0.02 * branch))
+              for _ in range(args.stack)]
+    g_final = mk(h, std=0.1) + 1
+    resid0 = mk(T, h, std=1.0)
+    sigma = 0.02 * h ** 0.5
+    k_cat = [None, None] + [mk(T, s.n_kv_heads, s.head_dim, std=sigma) for _ in range(args.stack - 2)]
+    v_cat = [None, None] + [mk(T, s.n_kv_heads, s.head_dim, std=sigma) for _ in range(args.stack - 2)]
+    q_rows = w.question_rows()
+    resid = torch.empty_like(resid0)
+
+    def timed(fn, steps, warmup):
+        ms = []
+        for i in range(warmup + steps):
+            resid.copy_(resid0)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            out = fn()
+            e1.record()
+            torch.cuda.synchronize()
+            if i >= warmup:
+                ms.append(e0.elapsed_time(e1))
+        return float(np.mean(ms)), out
+
+    steps, warmup = max(1, min(args.steps, 16)), max(1, min(args.warmup, 2))
+    fuse_ms, out = timed(lambda: stack.fuse_stack(lay, s, layers, g_final, resid, k_cat, v_cat, w.sel_start, q_rows),
+                         steps, warmup)
+    act = out["act_idx"].cpu().numpy()
+    assert out["n_act"] == w.total_k + w.total_q and np.all(np.diff(act) > 0)
+    assert bool(torch.isfinite(out["hidden"][out["act_idx"].long()].float()).all())
+    full_ms, _ = timed(lambda: stack.prefill_stack(lay, s, layers, g_final, resid), max(1, steps // 4), 1)
+    n_act = out["n_act"]
+    # H(.) alone at the active rows: the call that dominates a layer once the rows are few
+    attn_out = mk(n_act, s.n_q_heads, s.head_dim, std=1.0)
+    ws = torch.empty(api.a3_block_tail_ws_bytes(lay, f, n_act), dtype=torch.uint8, device="cuda")
+    lw = layers[2 % args.stack]
+    hid = torch.empty_like(resid)
+    call = lambda: api.a3_block_tail(lay, attn_out, out["act_idx"], n_act, lw["wo"], lw["g_post"], lw["w_gate"],
+                                     lw["w_up"], lw["w_down"], g_final, s.rms_eps, resid, hid, ws)
+    for _ in range(3):
+        call()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(20):
+        call()
+    e1.record()
+    torch.cuda.synchronize()
+    tail_us = e0.elapsed_time(e1) * 1e3 / 20
+    tail_flops = 2.0 * n_act * (qd * h + 3 * h * f)
+    print(json.dumps({
+        "metric": f"time of the A^3 schedule over {args.stack} decoder blocks (embedding output to final hidden "
+                  "states of the rows [Re, Q])",
+        "value": fuse_ms, "unit": "ms", "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": fuse_ms,
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": s.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "blocks": args.stack, "ctx_tokens": w.total_ctx, "question_tokens": w.total_q,
+                   "selected_tokens": w.total_k, "requests": w.n_req,
+                   "shape": f"h{s.hidden}/Hq{s.n_q_heads}/Hkv{s.n_kv_heads}/d{s.head_dim}/ffn{s.ffn}"},
+        "full_prefill_ms": full_ms, "speedup_over_full_prefill": full_ms / fuse_ms,
+        "block_tail": {"us_per_call": round(tail_us, 1), "rows": n_act, "flops_per_call": tail_flops,
+                       "achieved_TFLOPs": round(tail_flops / tail_us / 1e6, 1),
+                       "frac_of_mfma_peak": tail_flops / tail_us / 1e6 / PEAK_BF16_TFLOPS},
+    }))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -123,6 +204,9 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="workload configuration 1..5 (3 = the 16K-context metric)")
     ap.add_argument("--layers", type=int, default=0, help="independent layer buffer sets to cycle (0 = 32 for config 3)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--stack", type=int, default=0,
+                    help="L >= 2: time the A^3 schedule over L decoder blocks against the plain prefill of the same "
+                         "stack instead of the per-layer hot path (not the headline metric)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB float32 copy kernel (torch.mul by 1) three times: the known-size "
                          "dispatch that scales the HBM byte counters of a rocprofv3 --pmc run")
@@ -130,6 +214,11 @@ def main():
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         sys.exit(2)
+    if args.stack:
+        if args.stack < 2:
+            print("bench.py: --stack needs at least 2 blocks", file=sys.stderr)
+            sys.exit(2)
+        return stack_main(args)
 
     import numpy as np
     import torch

@@ -341,7 +341,8 @@ gemm_f32_kernel(gemm_args_f32 a) {
   }
 }
 
-// rows per workgroup (64 TB): useful rows / padded rows x how evenly the workgroups fill 256 CUs x a bonus
+// rows per workgroup (64 TB): useful rows / padded rows x how evenly the workgroups fill 256 CUs (the
+// busiest CU sets the time; two co-resident 128-row workgroups share their CU's matrix pipes) x a bonus
 // for the lower cache traffic of larger tiles
 int pick_tb(int n_rows, int n_ftiles) {
   int best_tb = 2;
@@ -349,9 +350,8 @@ int pick_tb(int n_rows, int n_ftiles) {
   for (int c = 2; c <= 4; ++c) {
     const int tiles = (n_rows + 64 * c - 1) / (64 * c);
     const long wgs = (long)tiles * n_ftiles;
-    const int per_cu = c == 2 ? 2 : 1;
-    const long rounds = (wgs + 256L * per_cu - 1) / (256L * per_cu);
-    const double fill = (double)wgs / (double)(rounds * 256L * per_cu);
+    const long rounds = (wgs + 255) / 256;
+    const double fill = (double)wgs / (double)(rounds * 256L);
     const double pad = (double)n_rows / (double)(tiles * 64 * c);
     const double traffic = 256.0 * 64 * c / (256.0 + 64 * c) / 128.0;
     const double score = pad * fill * (0.5 + 0.5 * traffic);

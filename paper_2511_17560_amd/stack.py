@@ -103,3 +103,40 @@ def fuse_stack(layout: api.Layout, shape, layers: Sequence[Dict[str, torch.Tenso
             kept.append(dict(k=k_l.clone(), v=v_cat[l].clone(), out=out[:n_act].clone()))
     return dict(sel_idx=sel_idx[:total_k], act_idx=act_idx[:n_act], n_act=n_act, scores=scores, resid=resid, hidden=x,
                 per_layer=kept)
+
+
+def prefill_stack(layout: api.Layout, shape, layers: Sequence[Dict[str, torch.Tensor]], g_final: torch.Tensor,
+                  resid: torch.Tensor, stream=None, keep_kv: bool = False) -> dict:
+    """Every block on every row: the plain prefill the schedule above is measured against (and, run on one
+    chunk alone, the precompute of Eq. 1 that produces a chunk's per-layer K/V).  ``resid`` [T, h] holds the
+    embedding output and is overwritten.  Returns dict(resid, hidden, k=[...], v=[...] if keep_kv)."""
+    dev, dt = layout.device, api.torch_dtype(layout.dtype)
+    T, h = layout.total_tokens, shape.hidden
+    Hq, Hkv, d = shape.n_q_heads, shape.n_kv_heads, shape.head_dim
+    n_layers = len(layers)
+    eps = float(shape.rms_eps)
+    ffn = int(layers[0]["w_gate"].shape[0])
+    ws_attn = layout.workspace(T)
+    ws_tail = torch.empty(max(api.a3_block_tail_ws_bytes(layout, ffn, T), 256), dtype=torch.uint8, device=dev)
+    x = torch.empty((T, h), dtype=dt, device=dev)
+    all_idx = torch.arange(T, dtype=torch.int32, device=dev)
+    q_all = torch.empty((T, Hq, d), dtype=dt, device=dev)
+    out_all = torch.empty((T, Hq, d), dtype=dt, device=dev)
+    k_l = torch.empty((T, Hkv, d), dtype=dt, device=dev)
+    v_l = torch.empty((T, Hkv, d), dtype=dt, device=dev)
+    ks, vs = [], []
+    api.a3_rms_norm(layout, resid, None, T, layers[0]["g_in"], eps, x, stream=stream)
+    for l, lw in enumerate(layers):
+        if keep_kv and l > 0:
+            k_l, v_l = torch.empty_like(k_l), torch.empty_like(v_l)
+        api.a3_selected_qkv_proj_scatter(layout, x, None, T, lw["wq"], lw["wk"], lw["wv"], bq=lw.get("bq"),
+                                         bk=lw.get("bk"), bv=lw.get("bv"), q_out=q_all, k_fused=k_l, v_fused=v_l,
+                                         stream=stream)
+        api.a3_fused_attention(layout, q_all, all_idx, T, k_l, v_l, out_all, ws_attn, stream=stream)
+        g_next = layers[l + 1]["g_in"] if l + 1 < n_layers else g_final
+        api.a3_block_tail(layout, out_all, None, T, lw["wo"], lw["g_post"], lw["w_gate"], lw["w_up"], lw["w_down"],
+                          g_next, eps, resid, x, ws_tail, stream=stream)
+        if keep_kv:
+            ks.append(k_l)
+            vs.append(v_l)
+    return dict(resid=resid, hidden=x, k=ks, v=vs)

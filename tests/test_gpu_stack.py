@@ -106,6 +106,43 @@ def test_block_tail(case):
                           dev["w_down"], to_dev(g_next, dtype), eps, resid_d, hid_d, ws[:256])
 
 
+@pytest.mark.parametrize("n", [1702, 16448])
+def test_block_tail_full_size_sampled_rows(n):
+    """The Llama-3-8B shape at the 16K configuration's row counts (the 1702 active rows of a fused layer; all
+    16448 rows of block 0), in the launch configuration the benchmark times.  H(.) treats rows independently,
+    so the oracle is run on 96 sampled rows (first and last rows of the list included)."""
+    dtype, h, Hq, d, f, T = "bf16", 4096, 32, 128, 14336, 16448
+    rng = np.random.default_rng(1234 + n)
+    shape = synth.ModelShape("llama", dtype, h, Hq, 8, d, 5e5, ffn=f)
+    lay = _layout(shape, T)
+    r2s = lambda a: synth.round_to_storage(a, dtype)
+    nrm = lambda *s: rng.standard_normal(s, dtype=np.float32)
+    lw = dict(wo=r2s(nrm(h, Hq * d) * np.float32(0.02)), g_post=r2s(1 + np.float32(0.1) * nrm(h)),
+              w_gate=r2s(nrm(f, h) * np.float32(0.03)), w_up=r2s(nrm(f, h) * np.float32(0.03)),
+              w_down=r2s(nrm(h, f) * np.float32(0.02)))
+    g_next = r2s(1 + np.float32(0.1) * nrm(h))
+    attn, resid = r2s(nrm(n, Hq * d)), r2s(nrm(T, h))
+    idx = np.sort(rng.choice(T, size=n, replace=False)).astype(np.int32)
+    pick = np.unique(np.concatenate([[0, n - 1], rng.choice(n, size=94, replace=False)]))
+    want = st.block_tail(attn[pick].astype(F64), resid[idx[pick]].astype(F64), {k: v.astype(F64) for k, v in lw.items()},
+                         g_next.astype(F64), 1e-5, dtype)
+    dev = {k: to_dev(v, dtype) for k, v in lw.items()}
+    resid_d, hid_d = to_dev(resid, dtype), torch.full((T, h), 5.0, dtype=torch.bfloat16, device="cuda")
+    ws = torch.empty(api.a3_block_tail_ws_bytes(lay, f, n), dtype=torch.uint8, device="cuda")
+    api.a3_block_tail(lay, to_dev(attn, dtype), idev(idx) if n < T else None, n, dev["wo"], dev["g_post"],
+                      dev["w_gate"], dev["w_up"], dev["w_down"], to_dev(g_next, dtype), 1e-5, resid_d, hid_d, ws)
+    torch.cuda.synchronize()
+    rows = torch.as_tensor(idx[pick].astype(np.int64), device="cuda")
+    got_r, got_x = to_host(resid_d[rows]), to_host(hid_d[rows])
+    assert max_abs_rel(got_r, want["resid"]) <= 2e-2 and _mean_rel(got_r, want["resid"]) <= 2e-3
+    assert max_abs_rel(got_x, want["hidden_next"]) <= 2e-2 and _mean_rel(got_x, want["hidden_next"]) <= 2e-3
+    assert max_abs_rel(got_r - want["resid_mid"], want["resid"] - want["resid_mid"]) <= 6e-2
+    # rows outside the list are untouched (checked on the device: no 270 MB round trip)
+    mask = torch.ones(T, dtype=torch.bool, device="cuda")
+    mask[torch.as_tensor(idx.astype(np.int64), device="cuda")] = False
+    assert bool((hid_d[mask] == 5.0).all()) and bool((resid_d[mask] == to_dev(resid, dtype)[mask]).all())
+
+
 STACK_CASES = {
     "tiny-f32": (synth.ModelShape("tiny-stack", "f32", 128, 4, 2, 64, 10000.0, synth.ROPE_HALF, ffn=192),
                  [[60, 41, 77]], [9], (20, 100), 3),
@@ -177,3 +214,43 @@ def test_fuse_stack(case):
     g_res, g_hid = to_host(got["resid"])[got_act], to_host(got["hidden"])[got_act]
     assert max_abs_rel(g_res, want["resid"]) <= tol and _mean_rel(g_res, want["resid"]) <= mtol
     assert max_abs_rel(g_hid, want["hidden"]) <= tol and _mean_rel(g_hid, want["hidden"]) <= mtol
+
+
+@pytest.mark.parametrize("case", ["tiny-f32", "batched-bf16"])
+def test_prefill_stack(case):
+    """Every block on every row against the oracle's full prefill; and, on one chunk alone, Eq. 1: the
+    chunk's per-layer K/V at chunk-local positions."""
+    shape, chunk_lens, q_lens, ratio, n_layers = STACK_CASES[case]
+    dt = shape.dtype
+    w = synth.custom(shape, chunk_lens, q_lens, ratio=ratio, seed=78)
+    sw = synth.draw_stack_weights(w, n_layers)
+    for lw in sw["layers"]:
+        for k in ("wq", "wk"):
+            lw[k] = synth.round_to_storage(lw[k] * np.float32(5.0), dt)
+    layers64 = [{k: v.astype(F64) for k, v in lw.items()} for lw in sw["layers"]]
+    sh = dict(n_q_heads=shape.n_q_heads, n_kv_heads=shape.n_kv_heads, head_dim=shape.head_dim, base=shape.rope_base,
+              layout=shape.rope_layout, sm_scale=1.0 / np.sqrt(shape.head_dim), eps=shape.rms_eps)
+    want = st.full_prefill_stack(sw["resid0"].astype(F64), w.token_positions(), w.seg_start, layers64,
+                                 sw["g_final"].astype(F64), sh, dt)
+    lay = api.Layout.from_workload(w)
+    dev_layers = [{k: to_dev(v, dt) for k, v in lw.items()} for lw in sw["layers"]]
+    got = stack.prefill_stack(lay, shape, dev_layers, to_dev(sw["g_final"], dt), to_dev(sw["resid0"], dt), keep_kv=True)
+    torch.cuda.synchronize()
+    tol, mtol = (1e-4, 1e-5) if dt == "f32" else (4e-2, 4e-3)
+    for l in range(n_layers):
+        assert max_abs_rel(to_host(got["k"][l]), want["k"][l]) <= tol, l
+        assert max_abs_rel(to_host(got["v"][l]), want["v"][l]) <= tol, l
+    assert max_abs_rel(to_host(got["hidden"]), want["hidden"]) <= tol
+    assert _mean_rel(to_host(got["hidden"]), want["hidden"]) <= mtol
+    # one chunk on its own (the second of the first request)
+    s0, n = int(w.chunk_start[1]), int(w.chunk_len[1])
+    w1 = synth.custom(shape, [[n - 1]], [1])
+    lay1 = api.Layout.from_workload(w1)
+    alone = stack.prefill_stack(lay1, shape, dev_layers, to_dev(sw["g_final"], dt),
+                                to_dev(sw["resid0"][s0:s0 + n], dt), keep_kv=True)
+    torch.cuda.synchronize()
+    k_cat, v_cat = st.precompute_stack_caches(sw["resid0"].astype(F64), w.chunk_start, w.chunk_len, layers64,
+                                              sw["g_final"].astype(F64), sh, dt)
+    for l in range(n_layers):
+        assert max_abs_rel(to_host(alone["k"][l]), k_cat[l][s0:s0 + n]) <= tol, l
+        assert max_abs_rel(to_host(alone["v"][l]), v_cat[l][s0:s0 + n]) <= tol, l
