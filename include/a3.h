@@ -54,6 +54,7 @@ typedef enum { A3_F32 = 0, A3_BF16 = 1 } a3_dtype;
 /* Which coordinates form a rotated pair.  INTERLEAVED = (2i, 2i+1), the block-diagonal matrix
  * printed in section "Position Recovery"; HALF = (i, i + head_dim/2). */
 typedef enum { A3_ROPE_INTERLEAVED = 0, A3_ROPE_HALF = 1 } a3_rope;
+typedef enum { A3_POOL_MAX = 0, A3_POOL_AVG = 1 } a3_pool;
 
 typedef struct a3_layout {
   /* ---- model (host scalars) ---- */
@@ -213,6 +214,41 @@ a3_status a3_block_tail(const a3_layout *layout, const void *attn_out, const int
  * (may be the same buffer); row_idx NULL: rows 0 .. n_rows-1. */
 a3_status a3_rms_norm(const a3_layout *layout, const void *x, const int *row_idx, int n_rows, const void *g,
                       float eps, void *out, void *stream);
+
+/* ---- variants of the selection score and the eviction extension (Method, "Extention") -----------------
+ *
+ * Eq. 3, first line, with the softmax of a question token taken over every key it sees: the context keys of
+ * its request and the question keys up to itself (the literal reading of the equation's denominator;
+ * a3_question_scores normalises over the context keys only).  Same arguments as a3_question_scores; the
+ * question rows of k_fused must hold the question's keys of this layer. */
+a3_status a3_question_scores_causal(const a3_layout *layout, const void *q_question, const void *k_fused,
+                                    float *scores, void *ws, size_t ws_bytes, void *stream);
+
+/* Extension, ranking step: votes[g, t] = sum over the query heads of KV head g and over the question tokens
+ * of the attention weight context row t receives (softmax over everything the question token sees, as
+ * above).  votes: float [n_kv_heads, total_tokens]; entries of question rows are not written.
+ * ws: at least a3_workspace_bytes(layout, 0) bytes. */
+a3_status a3_window_votes(const a3_layout *layout, const void *q_question, const void *k_fused, float *votes,
+                          void *ws, size_t ws_bytes, void *stream);
+
+/* Extension, retention step.  For request r and KV head g, keep_idx[g, keep_start[r] .. keep_start[r+1])
+ * receives, in ascending packed-row order: the first sys_len[r] context rows (system prompt), the
+ * budget_r = keep_start[r+1] - keep_start[r] - sys_len[r] - q_len[r] best other context rows by votes[g]
+ * (ties to the lowest row), and the q_len[r] question rows.  The caller sizes keep_start from the capacity C:
+ * budget_r = min(max(C - sys_len[r] - q_len[r], 0), ctx_len[r] - sys_len[r]).
+ * votes: float [n_kv_heads, total_tokens]; sys_len: device int32 [n_req]; keep_start: device int32
+ * [n_req+1]; total_keep = keep_start[n_req] (host value); keep_idx: device int32 [n_kv_heads, total_keep].
+ * pool_width > 1 first smooths the votes along the context rows of each request (odd width <= 63;
+ * A3_POOL_MAX, or A3_POOL_AVG with zero padding) into ws (a3_evict_ws_bytes(layout) bytes). */
+size_t a3_evict_ws_bytes(const a3_layout *layout);
+a3_status a3_evict_select(const a3_layout *layout, const float *votes, const int *sys_len, const int *keep_start,
+                          int total_keep, int pool_width, int pool_mode, int *keep_idx,
+                          void *ws, size_t ws_bytes, void *stream);
+
+/* Extension, the eviction itself: k_out[slot, g] = k_fused[keep_idx[g, slot], g], same for V.
+ * k_out, v_out: [total_keep, n_kv_heads, head_dim]. */
+a3_status a3_evict_compact(const a3_layout *layout, const void *k_fused, const void *v_fused, const int *keep_idx,
+                           int total_keep, void *k_out, void *v_out, void *stream);
 
 const char *a3_strerror(a3_status status);
 /* Text of the last error raised on the calling thread ("" if none). */

@@ -18,10 +18,12 @@ LIB_PATH = os.path.join(_HERE, "liba3.so")
 A3_OK, A3_ERR_INVALID_ARG, A3_ERR_UNSUPPORTED, A3_ERR_WORKSPACE, A3_ERR_HIP = 0, -1, -2, -3, -4
 A3_F32, A3_BF16 = 0, 1
 A3_ROPE_INTERLEAVED, A3_ROPE_HALF = 0, 1
+A3_POOL_MAX, A3_POOL_AVG = 0, 1
 
 EXPORTS = ["a3_workspace_bytes", "a3_layout_prepare", "a3_rope_realign", "a3_question_scores", "a3_realign_scores", "a3_topk_select",
            "a3_selected_qkv_proj", "a3_selected_qkv_proj_scatter", "a3_kv_scatter", "a3_fused_attention", "a3_active_rows",
-           "a3_block_tail_ws_bytes", "a3_block_tail", "a3_rms_norm", "a3_strerror", "a3_last_error", "a3_version"]
+           "a3_block_tail_ws_bytes", "a3_block_tail", "a3_rms_norm", "a3_question_scores_causal", "a3_window_votes",
+           "a3_evict_ws_bytes", "a3_evict_select", "a3_evict_compact", "a3_strerror", "a3_last_error", "a3_version"]
 
 
 class A3Error(RuntimeError):
@@ -78,6 +80,14 @@ def lib() -> C.CDLL:
     L.a3_block_tail.argtypes = [P, V, V, I, C.POINTER(a3_block_weights), V, V, V, C.c_size_t, V]
     L.a3_rms_norm.argtypes = [P, V, V, I, V, C.c_float, V, V]
     L.a3_block_tail.restype = I
+    L.a3_question_scores_causal.argtypes = [P, V, V, V, V, C.c_size_t, V]
+    L.a3_window_votes.argtypes = [P, V, V, V, V, C.c_size_t, V]
+    L.a3_evict_ws_bytes.restype = C.c_size_t
+    L.a3_evict_ws_bytes.argtypes = [P]
+    L.a3_evict_select.argtypes = [P, V, V, V, I, I, I, V, V, C.c_size_t, V]
+    L.a3_evict_compact.argtypes = [P, V, V, V, I, V, V, V]
+    for name in ("a3_question_scores_causal", "a3_window_votes", "a3_evict_select", "a3_evict_compact"):
+        getattr(L, name).restype = I
     L.a3_rms_norm.restype = I
     for name in ("a3_realign_scores", "a3_selected_qkv_proj_scatter", "a3_active_rows", "a3_layout_prepare", "a3_rope_realign", "a3_question_scores", "a3_topk_select",
                  "a3_selected_qkv_proj", "a3_selected_qkv_proj_scatter", "a3_kv_scatter", "a3_fused_attention"):
@@ -260,3 +270,34 @@ def a3_rms_norm(layout: Layout, x: torch.Tensor, row_idx: Optional[torch.Tensor]
                 eps: float, out: torch.Tensor, stream=None) -> None:
     _check(lib().a3_rms_norm(layout.ref, _ptr(x), _ptr(row_idx), int(n_rows), _ptr(g), float(eps), _ptr(out),
                              _stream(stream)), "a3_rms_norm")
+
+
+def a3_question_scores_causal(layout: Layout, q_question: torch.Tensor, k_fused: torch.Tensor, scores: torch.Tensor,
+                              ws: torch.Tensor, stream=None) -> None:
+    _check(lib().a3_question_scores_causal(layout.ref, _ptr(q_question), _ptr(k_fused), _ptr(scores), _ptr(ws),
+                                           ws.numel() if ws is not None else 0, _stream(stream)),
+           "a3_question_scores_causal")
+
+
+def a3_window_votes(layout: Layout, q_question: torch.Tensor, k_fused: torch.Tensor, votes: torch.Tensor,
+                    ws: torch.Tensor, stream=None) -> None:
+    _check(lib().a3_window_votes(layout.ref, _ptr(q_question), _ptr(k_fused), _ptr(votes), _ptr(ws),
+                                 ws.numel() if ws is not None else 0, _stream(stream)), "a3_window_votes")
+
+
+def a3_evict_ws_bytes(layout: Layout) -> int:
+    return int(lib().a3_evict_ws_bytes(layout.ref))
+
+
+def a3_evict_select(layout: Layout, votes: torch.Tensor, sys_len: torch.Tensor, keep_start: torch.Tensor,
+                    total_keep: int, keep_idx: torch.Tensor, pool_width: int = 1, pool_mode: int = A3_POOL_MAX,
+                    ws: Optional[torch.Tensor] = None, stream=None) -> None:
+    _check(lib().a3_evict_select(layout.ref, _ptr(votes), _ptr(sys_len), _ptr(keep_start), int(total_keep),
+                                 int(pool_width), int(pool_mode), _ptr(keep_idx), _ptr(ws),
+                                 ws.numel() if ws is not None else 0, _stream(stream)), "a3_evict_select")
+
+
+def a3_evict_compact(layout: Layout, k_fused: torch.Tensor, v_fused: torch.Tensor, keep_idx: torch.Tensor,
+                     total_keep: int, k_out: torch.Tensor, v_out: torch.Tensor, stream=None) -> None:
+    _check(lib().a3_evict_compact(layout.ref, _ptr(k_fused), _ptr(v_fused), _ptr(keep_idx), int(total_keep),
+                                  _ptr(k_out), _ptr(v_out), _stream(stream)), "a3_evict_compact")

@@ -47,7 +47,49 @@ struct scores_args {
   const int *tok_chunk;     // [T] chunk of a context row, -1 for question rows
   const float2 *chunk_cs;   // [n_chunks, d/2] (cos, sin) of chunk offset x theta_i
   int rope_layout;
+  // the softmax of a question token also runs over the question keys up to itself (their (max, sum) sits
+  // in the extra partial slot n_tiles): the literal denominator of Eq. 3 and the window votes of the
+  // eviction extension
+  int causal_q;
 };
+
+// ---------------------------------------------------------------------------------------
+// (max, sum exp) of a question row over the question keys it sees (itself and the earlier ones of its
+// request): one wave per (question token, query head), lanes over keys.  A few hundred short dot products.
+// ---------------------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(256)
+scores_question_stats_kernel(scores_args a) {
+  const int lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= a.total_rows) return;
+  const int jq = row / a.Hq, hq = row % a.Hq;
+  const int r = find_segment(a.q_start, a.n_req, jq);
+  const int j = jq - a.q_start[r];
+  if (j >= a.q_len[r]) return;                                 // rows past the last request's question
+  const int g = hq / (a.Hq / a.Hkv);
+  const T *__restrict__ Q = (const T *)a.q + (size_t)row * a.d;
+  const T *__restrict__ K = (const T *)a.k;
+  const int key0 = a.seg_start[r] + a.ctx_len[r];
+  float m = -INFINITY, z = 0.f;
+  for (int u = lane; u <= j; u += 64) {
+    const T *kp = K + ((size_t)(key0 + u) * a.Hkv + g) * a.d;
+    float dot = 0.f;
+    for (int c = 0; c < a.d; ++c) dot = fmaf((float)Q[c], (float)kp[c], dot);
+    const float l = dot * a.scale2;
+    const float mn = fmaxf(m, l);
+    z = z * exp2f(m - mn) + exp2f(l - mn);                     // m = -inf, z = 0 on the first key: 0 * 0
+    m = mn;
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    const float pm = __shfl_xor(m, off), pz = __shfl_xor(z, off);
+    const float mn = fmaxf(m, pm);
+    const float za = z > 0.f ? z * exp2f(m - mn) : 0.f, zb = pz > 0.f ? pz * exp2f(pm - mn) : 0.f;
+    z = (lane & off) ? zb + za : za + zb;
+    m = mn;
+  }
+  if (lane == 0) a.part[(size_t)a.n_tiles * a.total_rows + row] = make_float2(m, z);
+}
 
 // ---------------------------------------------------------------------------------------
 // combine partial row statistics (shared by both element types)
@@ -69,6 +111,12 @@ scores_combine_kernel(scores_args a) {
       float2 p = a.part[(size_t)t * a.total_rows + row];
       float mn = fmaxf(m, p.x);
       z = z * exp2f(m - mn) + p.y * exp2f(p.x - mn);
+      m = mn;
+    }
+    if (a.causal_q && slice == 15) {                           // the question keys' share (slice 15 has the fewest tiles)
+      float2 p = a.part[(size_t)a.n_tiles * a.total_rows + row];
+      float mn = fmaxf(m, p.x);
+      z = (z > 0.f ? z * exp2f(m - mn) : 0.f) + p.y * exp2f(p.x - mn);
       m = mn;
     }
   }
@@ -351,15 +399,16 @@ scores_f32_kernel(scores_args a) {
   const int key = tid & 63, slice = tid >> 6;
   const int s = a.seg_start[r];
   const int nq = a.q_len[r];
-  if (PASS == 1 && blockIdx.x == 0)
+  if (PASS == 1 && blockIdx.x == 0 && a.scores)
     for (int j = tid; j < nq; j += 256) a.scores[s + N + j] = -INFINITY;
   if (i0 >= N) return;
   const int d = a.d, G = a.Hq / a.Hkv, Mg = nq * G, qrow0 = a.q_start[r];
   const float *__restrict__ Q = (const float *)a.q;
   const float *__restrict__ K = (const float *)a.k;
-  float colsum = 0.f;
+  float total = 0.f;                     // PASS 1, tid < kTileKeys: the key's score over all heads so far
 
   for (int g = 0; g < a.Hkv; ++g) {
+    float colsum = 0.f;
     __syncthreads();
     for (int i = tid; i < kTileKeys * d; i += 256) {
       int kr = i / d, c = i % d;
@@ -389,13 +438,19 @@ scores_f32_kernel(scores_args a) {
         colsum += exp2f(l - a.stats[row_id].x);
       }
     }
+    if (PASS == 1) {
+      // this head's column sums: the four row slices in a fixed order, then the heads in order
+      __syncthreads();
+      red[slice][key] = colsum;
+      __syncthreads();
+      if (tid < kTileKeys && i0 + tid < N) {
+        const float v = (red[0][tid] + red[1][tid]) + (red[2][tid] + red[3][tid]);
+        if (a.part_scores) a.part_scores[(size_t)g * a.T + s + i0 + tid] = v;
+        total += v;
+      }
+    }
   }
-  if (PASS == 1) {
-    red[slice][key] = colsum;
-    __syncthreads();
-    if (tid < kTileKeys && i0 + tid < N)
-      a.scores[s + i0 + tid] = (red[0][tid] + red[1][tid]) + (red[2][tid] + red[3][tid]);
-  }
+  if (PASS == 1 && a.scores && tid < kTileKeys && i0 + tid < N) a.scores[s + i0 + tid] = total;
 }
 
 }  // namespace
@@ -407,17 +462,20 @@ size_t a3_scores_ws_bytes(const a3_layout *L) {
   const size_t total_rows = (size_t)L->n_req * L->max_q_len * L->n_q_heads;
   const int tk = scores_tile_keys(L);
   const size_t n_tiles = (size_t)(L->max_ctx_len + tk - 1) / tk;
-  return a3_align_up(n_tiles * total_rows * sizeof(float2), 256) + a3_align_up(total_rows * sizeof(float2), 256) +
+  return a3_align_up((n_tiles + 1) * total_rows * sizeof(float2), 256) + a3_align_up(total_rows * sizeof(float2), 256) +
          a3_align_up((size_t)L->n_kv_heads * L->total_tokens * sizeof(float), 256) + 256;
 }
 
 // k_cat != nullptr: the first pass of the bf16 path also realigns (k_cat -> k_fused); the fp32 path runs the
 // realign kernel first.
+// causal_q: the question keys a question token sees join its softmax denominator.  votes != nullptr: the per
+// KV head column sums [Hkv, T] go there; scores may then be NULL (no sum over heads).
 static a3_status scores_launch(const a3_layout *L, const void *q_question, const void *k_cat, void *k_fused,
-                               float *scores, void *ws, size_t ws_bytes, void *stream) {
+                               float *scores, void *ws, size_t ws_bytes, void *stream, int causal_q = 0,
+                               float *votes = nullptr) {
   a3_status s = a3_check_layout(L, "a3_question_scores", true);
   if (s != A3_OK) return s;
-  A3_REQUIRE(q_question && k_fused && scores, A3_ERR_INVALID_ARG, "a3_question_scores: NULL tensor");
+  A3_REQUIRE(q_question && k_fused && (scores || votes), A3_ERR_INVALID_ARG, "a3_question_scores: NULL tensor");
   A3_REQUIRE(a3_aligned16(q_question) && a3_aligned16(k_fused), A3_ERR_INVALID_ARG,
              "a3_question_scores: tensors must be 16-byte aligned");
   A3_REQUIRE(ws != nullptr, A3_ERR_WORKSPACE, "a3_question_scores: workspace is NULL");
@@ -433,9 +491,12 @@ static a3_status scores_launch(const a3_layout *L, const void *q_question, const
   scores_args a;
   a.q = q_question; a.k = k_fused;
   a.seg_start = L->seg_start; a.ctx_len = L->ctx_len; a.q_len = L->q_len; a.q_start = L->q_start;
-  a.part = (float2 *)cur.take((size_t)n_tiles * total_rows * sizeof(float2));
+  a.part = (float2 *)cur.take((size_t)(n_tiles + 1) * total_rows * sizeof(float2));
   a.stats = (float2 *)cur.take(total_rows * sizeof(float2));
   a.part_scores = (float *)cur.take((size_t)L->n_kv_heads * L->total_tokens * sizeof(float));
+  if (votes) a.part_scores = votes;
+  else if (L->dtype != A3_BF16) a.part_scores = nullptr;       // fp32 path adds the heads itself
+  a.causal_q = causal_q;
   a.scores = scores;
   a.n_req = L->n_req; a.Hq = L->n_q_heads; a.Hkv = L->n_kv_heads; a.d = L->head_dim; a.T = L->total_tokens;
   a.total_rows = (int)total_rows; a.n_tiles = n_tiles; a.tile_keys = tk;
@@ -448,6 +509,11 @@ static a3_status scores_launch(const a3_layout *L, const void *q_question, const
     if (s != A3_OK) return s;
   }
   dim3 cgrid((unsigned)((total_rows + 15) / 16));
+  if (causal_q) {
+    const dim3 qgrid((unsigned)((total_rows + 3) / 4));
+    if (L->dtype == A3_BF16) hipLaunchKernelGGL(scores_question_stats_kernel<bf16_t>, qgrid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL(scores_question_stats_kernel<float>, qgrid, dim3(256), 0, st, a);
+  }
   if (L->dtype == A3_BF16) {
     static bool attr_done = false;
     if (!attr_done) {
@@ -467,7 +533,8 @@ static a3_status scores_launch(const a3_layout *L, const void *q_question, const
     else hipLaunchKernelGGL((scores_bf16_kernel<0, false>), grid, dim3(256), kScoresLds, st, a);
     hipLaunchKernelGGL(scores_combine_kernel, cgrid, dim3(256), 0, st, a);
     hipLaunchKernelGGL((scores_bf16_kernel<1, false>), grid, dim3(256), kScoresLds, st, a);
-    hipLaunchKernelGGL(scores_head_sum_kernel, dim3((L->total_tokens + 255) / 256), dim3(256), 0, st, a, L->tok_chunk);
+    if (scores)
+      hipLaunchKernelGGL(scores_head_sum_kernel, dim3((L->total_tokens + 255) / 256), dim3(256), 0, st, a, L->tok_chunk);
   } else {
     dim3 grid(n_tiles, L->n_req);
     hipLaunchKernelGGL(scores_f32_kernel<0>, grid, dim3(256), 0, st, a);
@@ -488,4 +555,19 @@ extern "C" a3_status a3_realign_scores(const a3_layout *L, const void *q_questio
   if (k_cat == nullptr) return a3_fail(A3_ERR_INVALID_ARG, "a3_realign_scores: k_cat is NULL");
   if (!a3_aligned16(k_cat)) return a3_fail(A3_ERR_INVALID_ARG, "a3_realign_scores: tensors must be 16-byte aligned");
   return scores_launch(L, q_question, k_cat, k_fused, scores, ws, ws_bytes, stream);
+}
+
+// Eq. 3, first line, with the softmax of a question token taken over every key it sees: the context keys
+// and the question keys up to itself (the literal reading of the equation's denominator).
+extern "C" a3_status a3_question_scores_causal(const a3_layout *L, const void *q_question, const void *k_fused,
+                                               float *scores, void *ws, size_t ws_bytes, void *stream) {
+  A3_REQUIRE(scores != nullptr, A3_ERR_INVALID_ARG, "a3_question_scores_causal: scores is NULL");
+  return scores_launch(L, q_question, nullptr, const_cast<void *>(k_fused), scores, ws, ws_bytes, stream, 1);
+}
+
+// Eviction extension: votes of the question window per KV head (same normalisation, no sum over KV heads).
+extern "C" a3_status a3_window_votes(const a3_layout *L, const void *q_question, const void *k_fused, float *votes,
+                                     void *ws, size_t ws_bytes, void *stream) {
+  A3_REQUIRE(votes != nullptr, A3_ERR_INVALID_ARG, "a3_window_votes: votes is NULL");
+  return scores_launch(L, q_question, nullptr, const_cast<void *>(k_fused), nullptr, ws, ws_bytes, stream, 1, votes);
 }

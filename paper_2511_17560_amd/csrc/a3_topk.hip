@@ -77,23 +77,46 @@ __device__ __forceinline__ void find_bin(const uint32_t *hist, uint32_t need, ui
   }
 }
 
+// What one workgroup ranks.  Selection of Eq. 3: the context rows of request blockIdx.x, k from sel_start.
+// Eviction extension (skip != nullptr): blockIdx.y is a KV head with its own score row and output row; the
+// first skip[r] context rows (system prompt) and the question rows are retained anyway and written by
+// another kernel, so the candidates start behind the system prompt, the count leaves them out, and the
+// output starts behind the system prompt's slots.
+struct topk_problem {
+  const int *seg_start, *ctx_len, *sel_start;
+  const int *skip, *q_len;
+  long score_stride, out_stride;
+};
+
+struct topk_range { int s, N, k; const float *sc; int *out; };
+
+__device__ __forceinline__ topk_range topk_range_of(const topk_problem &p, const float *scores, int *sel_idx) {
+  const int r = blockIdx.x;
+  const int sk = p.skip ? p.skip[r] : 0;
+  topk_range t;
+  t.s = p.seg_start[r] + sk;
+  t.N = max(p.ctx_len[r] - sk, 0);
+  t.k = p.sel_start[r + 1] - p.sel_start[r] - (p.skip ? sk + p.q_len[r] : 0);
+  if (t.k > t.N) t.k = t.N;
+  t.sc = scores + (size_t)blockIdx.y * p.score_stride + t.s;
+  t.out = sel_idx + (size_t)blockIdx.y * p.out_stride + p.sel_start[r] + sk;
+  return t;
+}
+
 // Requests longer than the register kernel holds: 4 x 8-bit passes from the top byte, every pass
 // re-reads the scores from global memory.
 __global__ void __launch_bounds__(kBlock)
-topk_select_kernel(const float *__restrict__ scores, const int *__restrict__ seg_start,
-                   const int *__restrict__ ctx_len, const int *__restrict__ sel_start, int *__restrict__ sel_idx) {
+topk_select_kernel(const float *__restrict__ scores, topk_problem prob, int *__restrict__ sel_idx) {
   __shared__ uint32_t hist[256];
   __shared__ int wave_tot[kWaves];
   __shared__ uint32_t sh_bin, sh_need;
 
-  const int r = blockIdx.x, tid = threadIdx.x;
-  const int s = seg_start[r];
-  const int N = ctx_len[r];
-  int k = sel_start[r + 1] - sel_start[r];
-  if (k > N) k = N;
+  const int tid = threadIdx.x;
+  const topk_range rg = topk_range_of(prob, scores, sel_idx);
+  const int s = rg.s, N = rg.N, k = rg.k;
   if (k <= 0) return;                    // uniform over the workgroup
-  int *__restrict__ out = sel_idx + sel_start[r];
-  const float *__restrict__ sc = scores + s;
+  int *__restrict__ out = rg.out;
+  const float *__restrict__ sc = rg.sc;
   auto key_at = [&](int i) -> uint32_t { return score_key(sc[i]); };
 
   // ---- radix select: key of the k-th largest score -------------------------------------
@@ -144,22 +167,19 @@ topk_select_kernel(const float *__restrict__ scores, const int *__restrict__ seg
 // from there into the registers of their owners; every later step works on registers.
 template <int KPT>
 __global__ void __launch_bounds__(kBlock)
-topk_select_reg_kernel(const float *__restrict__ scores, const int *__restrict__ seg_start,
-                       const int *__restrict__ ctx_len, const int *__restrict__ sel_start, int *__restrict__ sel_idx) {
+topk_select_reg_kernel(const float *__restrict__ scores, topk_problem prob, int *__restrict__ sel_idx) {
   extern __shared__ uint32_t keys[];                         // [N + N/32]
   __shared__ uint32_t hist[256];
   __shared__ uint32_t wave_min[kWaves], wave_max[kWaves];
   __shared__ int wave_gt[kWaves], wave_eq[kWaves];
   __shared__ uint32_t sh_bin, sh_need;
 
-  const int r = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int s = seg_start[r];
-  const int N = ctx_len[r];
-  int k = sel_start[r + 1] - sel_start[r];
-  if (k > N) k = N;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const topk_range rg = topk_range_of(prob, scores, sel_idx);
+  const int s = rg.s, N = rg.N, k = rg.k;
   if (k <= 0) return;                    // uniform over the workgroup
-  int *__restrict__ out = sel_idx + sel_start[r];
-  const float *__restrict__ sc = scores + s;
+  int *__restrict__ out = rg.out;
+  const float *__restrict__ sc = rg.sc;
 
   const int per = (N + kBlock - 1) / kBlock;                 // <= KPT (checked by the host)
   const int first = min(N, tid * per), nv = min(N, first + per) - first;
@@ -262,6 +282,87 @@ topk_select_reg_kernel(const float *__restrict__ scores, const int *__restrict__
 
 constexpr int kMaxLdsKeys = 36 * 1024;   // 148.5 KB of padded keys next to the small static arrays
 
+// One launch of the ranking kernels over grid (requests, heads).
+a3_status topk_launch(const a3_layout *L, const float *scores, const topk_problem &prob, int n_heads, int *sel_idx,
+                      hipStream_t st, const char *who) {
+  const dim3 grid(L->n_req, n_heads);
+  if (L->max_ctx_len <= kMaxLdsKeys) {
+    const size_t lds = ((size_t)L->max_ctx_len + L->max_ctx_len / 32 + 1) * sizeof(uint32_t);
+    static bool attr_done = false;
+    if (!attr_done) {
+      const int cap = (int)((kMaxLdsKeys + kMaxLdsKeys / 32 + 1) * sizeof(uint32_t));
+      hipError_t e1 = hipFuncSetAttribute((const void *)topk_select_reg_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, cap);
+      hipError_t e2 = hipFuncSetAttribute((const void *)topk_select_reg_kernel<16>, hipFuncAttributeMaxDynamicSharedMemorySize, cap);
+      hipError_t e3 = hipFuncSetAttribute((const void *)topk_select_reg_kernel<36>, hipFuncAttributeMaxDynamicSharedMemorySize, cap);
+      if (e1 != hipSuccess || e2 != hipSuccess || e3 != hipSuccess)
+        return a3_fail(A3_ERR_HIP, "%s: cannot raise the dynamic LDS limit", who);
+      attr_done = true;
+    }
+    const int per = (L->max_ctx_len + kBlock - 1) / kBlock;  // keys per lane of the longest request
+    if (per <= 4) hipLaunchKernelGGL(topk_select_reg_kernel<4>, grid, dim3(kBlock), lds, st, scores, prob, sel_idx);
+    else if (per <= 16) hipLaunchKernelGGL(topk_select_reg_kernel<16>, grid, dim3(kBlock), lds, st, scores, prob, sel_idx);
+    else hipLaunchKernelGGL(topk_select_reg_kernel<36>, grid, dim3(kBlock), lds, st, scores, prob, sel_idx);
+  } else {
+    hipLaunchKernelGGL(topk_select_kernel, grid, dim3(kBlock), 0, st, scores, prob, sel_idx);
+  }
+  A3_CHECK_LAUNCH(who);
+  return A3_OK;
+}
+
+// ---------------------------------------------------------------------------------------
+// eviction extension: pooling of the votes, the rows that are always retained, compaction
+// ---------------------------------------------------------------------------------------
+// 1-D pooling of stride 1 along the context rows of a request, per head.  mode 0: maximum over the rows
+// inside the request's context; mode 1: sum / width (rows outside count as zero).  Other rows are copied.
+__global__ void __launch_bounds__(256)
+pool_votes_kernel(const float *__restrict__ in, float *__restrict__ out, const int *__restrict__ tok_req,
+                  const int *__restrict__ tok_chunk, const int *__restrict__ seg_start,
+                  const int *__restrict__ ctx_len, int T, int width, int mode) {
+  const int t = blockIdx.x * 256 + threadIdx.x;
+  if (t >= T) return;
+  const float *row = in + (size_t)blockIdx.y * T;
+  float v = row[t];
+  if (tok_chunk[t] >= 0) {
+    const int r = tok_req[t];
+    const int s = seg_start[r], e = s + ctx_len[r];
+    const int lo = max(s, t - width / 2), hi = min(e, t + width / 2 + 1);
+    if (mode == 0) {
+      for (int u = lo; u < hi; ++u) v = fmaxf(v, row[u]);
+    } else {
+      float sum = 0.f;
+      for (int u = lo; u < hi; ++u) sum += row[u];           // ascending row order
+      v = sum / (float)width;
+    }
+  }
+  out[(size_t)blockIdx.y * T + t] = v;
+}
+
+// keep_idx[g][keep_start[r] + i] for the system-prompt rows (i < skip[r]) and the question rows (the last
+// q_len[r] slots of the request)
+__global__ void __launch_bounds__(256)
+evict_fixed_rows_kernel(topk_problem p, int *__restrict__ keep_idx) {
+  const int r = blockIdx.x;
+  int *out = keep_idx + (size_t)blockIdx.y * p.out_stride;
+  const int s = p.seg_start[r], N = p.ctx_len[r], nq = p.q_len[r], sk = p.skip[r];
+  const int o0 = p.sel_start[r], o1 = p.sel_start[r + 1];
+  for (int i = threadIdx.x; i < sk; i += 256) out[o0 + i] = s + i;
+  for (int j = threadIdx.x; j < nq; j += 256) out[o1 - nq + j] = s + N + j;
+}
+
+// out[slot, g, :] = in[keep_idx[g][slot], g, :] for K and V; 16 bytes per lane
+__global__ void __launch_bounds__(256)
+evict_compact_kernel(const uint4 *__restrict__ k, const uint4 *__restrict__ v, const int *__restrict__ keep_idx,
+                     int total_keep, int Hkv, int vec_per_head, uint4 *__restrict__ k_out, uint4 *__restrict__ v_out) {
+  const long i = (long)blockIdx.x * 256 + threadIdx.x;
+  const long per_slot = (long)Hkv * vec_per_head;
+  if (i >= (long)total_keep * per_slot) return;
+  const int slot = (int)(i / per_slot), rem = (int)(i % per_slot);
+  const int g = rem / vec_per_head;
+  const long src = (long)keep_idx[(size_t)g * total_keep + slot] * per_slot + rem;
+  k_out[i] = k[src];
+  v_out[i] = v[src];
+}
+
 }  // namespace
 
 extern "C" a3_status a3_topk_select(const a3_layout *L, const float *scores, const int *sel_start, int total_k,
@@ -275,32 +376,62 @@ extern "C" a3_status a3_topk_select(const a3_layout *L, const float *scores, con
   A3_REQUIRE(scores && sel_start, A3_ERR_INVALID_ARG, "a3_topk_select: scores/sel_start is NULL");
   if (total_k == 0) return A3_OK;
   A3_REQUIRE(sel_idx, A3_ERR_INVALID_ARG, "a3_topk_select: sel_idx is NULL");
-  if (L->max_ctx_len <= kMaxLdsKeys) {
-    const size_t lds = ((size_t)L->max_ctx_len + L->max_ctx_len / 32 + 1) * sizeof(uint32_t);
-    static bool attr_done = false;
-    if (!attr_done) {
-      const int cap = (int)((kMaxLdsKeys + kMaxLdsKeys / 32 + 1) * sizeof(uint32_t));
-      hipError_t e1 = hipFuncSetAttribute((const void *)topk_select_reg_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, cap);
-      hipError_t e2 = hipFuncSetAttribute((const void *)topk_select_reg_kernel<16>, hipFuncAttributeMaxDynamicSharedMemorySize, cap);
-      hipError_t e3 = hipFuncSetAttribute((const void *)topk_select_reg_kernel<36>, hipFuncAttributeMaxDynamicSharedMemorySize, cap);
-      if (e1 != hipSuccess || e2 != hipSuccess || e3 != hipSuccess)
-        return a3_fail(A3_ERR_HIP, "a3_topk_select: cannot raise the dynamic LDS limit");
-      attr_done = true;
-    }
-    const int per = (L->max_ctx_len + kBlock - 1) / kBlock;  // keys per lane of the longest request
-    if (per <= 4)
-      hipLaunchKernelGGL(topk_select_reg_kernel<4>, dim3(L->n_req), dim3(kBlock), lds, (hipStream_t)stream, scores,
-                         L->seg_start, L->ctx_len, sel_start, sel_idx);
-    else if (per <= 16)
-      hipLaunchKernelGGL(topk_select_reg_kernel<16>, dim3(L->n_req), dim3(kBlock), lds, (hipStream_t)stream, scores,
-                         L->seg_start, L->ctx_len, sel_start, sel_idx);
-    else
-      hipLaunchKernelGGL(topk_select_reg_kernel<36>, dim3(L->n_req), dim3(kBlock), lds, (hipStream_t)stream, scores,
-                         L->seg_start, L->ctx_len, sel_start, sel_idx);
-  } else {
-    hipLaunchKernelGGL(topk_select_kernel, dim3(L->n_req), dim3(kBlock), 0, (hipStream_t)stream, scores,
-                       L->seg_start, L->ctx_len, sel_start, sel_idx);
+  const topk_problem prob{L->seg_start, L->ctx_len, sel_start, nullptr, nullptr, 0, 0};
+  return topk_launch(L, scores, prob, 1, sel_idx, (hipStream_t)stream, "a3_topk_select");
+}
+
+extern "C" size_t a3_evict_ws_bytes(const a3_layout *L) {
+  if (L == nullptr || L->n_kv_heads <= 0 || L->total_tokens < 0) return 0;
+  return a3_align_up((size_t)L->n_kv_heads * L->total_tokens * sizeof(float), 256) + 256;
+}
+
+extern "C" a3_status a3_evict_select(const a3_layout *L, const float *votes, const int *sys_len, const int *keep_start,
+                                     int total_keep, int pool_width, int pool_mode, int *keep_idx, void *ws,
+                                     size_t ws_bytes, void *stream) {
+  a3_status s = a3_check_layout(L, "a3_evict_select", true);
+  if (s != A3_OK) return s;
+  A3_REQUIRE(total_keep >= 0 && total_keep <= L->total_tokens, A3_ERR_INVALID_ARG,
+             "a3_evict_select: total_keep %d outside [0, %d]", total_keep, L->total_tokens);
+  A3_REQUIRE(votes && sys_len && keep_start, A3_ERR_INVALID_ARG, "a3_evict_select: votes/sys_len/keep_start is NULL");
+  A3_REQUIRE(pool_width >= 1 && pool_width % 2 == 1 && pool_width <= 63, A3_ERR_INVALID_ARG,
+             "a3_evict_select: pool_width %d is not an odd number in [1, 63]", pool_width);
+  A3_REQUIRE(pool_mode == A3_POOL_MAX || pool_mode == A3_POOL_AVG, A3_ERR_INVALID_ARG,
+             "a3_evict_select: pool_mode %d", pool_mode);
+  if (total_keep == 0 || L->n_req == 0) return A3_OK;
+  A3_REQUIRE(keep_idx, A3_ERR_INVALID_ARG, "a3_evict_select: keep_idx is NULL");
+  hipStream_t st = (hipStream_t)stream;
+  const float *ranked = votes;
+  if (pool_width > 1) {
+    A3_REQUIRE(ws != nullptr && ws_bytes >= a3_evict_ws_bytes(L), A3_ERR_WORKSPACE,
+               "a3_evict_select: workspace %zu bytes, need %zu", ws_bytes, a3_evict_ws_bytes(L));
+    float *pooled = (float *)ws;
+    hipLaunchKernelGGL(pool_votes_kernel, dim3((L->total_tokens + 255) / 256, L->n_kv_heads), dim3(256), 0, st, votes,
+                       pooled, L->tok_req, L->tok_chunk, L->seg_start, L->ctx_len, L->total_tokens, pool_width,
+                       pool_mode);
+    ranked = pooled;
   }
-  A3_CHECK_LAUNCH("a3_topk_select");
+  const topk_problem prob{L->seg_start, L->ctx_len, keep_start, sys_len, L->q_len, (long)L->total_tokens,
+                          (long)total_keep};
+  hipLaunchKernelGGL(evict_fixed_rows_kernel, dim3(L->n_req, L->n_kv_heads), dim3(256), 0, st, prob, keep_idx);
+  return topk_launch(L, ranked, prob, L->n_kv_heads, keep_idx, st, "a3_evict_select");
+}
+
+extern "C" a3_status a3_evict_compact(const a3_layout *L, const void *k_fused, const void *v_fused, const int *keep_idx,
+                                      int total_keep, void *k_out, void *v_out, void *stream) {
+  a3_status s = a3_check_layout(L, "a3_evict_compact", false);
+  if (s != A3_OK) return s;
+  A3_REQUIRE(total_keep >= 0 && total_keep <= L->total_tokens, A3_ERR_INVALID_ARG,
+             "a3_evict_compact: total_keep %d outside [0, %d]", total_keep, L->total_tokens);
+  if (total_keep == 0) return A3_OK;
+  A3_REQUIRE(k_fused && v_fused && keep_idx && k_out && v_out, A3_ERR_INVALID_ARG, "a3_evict_compact: NULL tensor");
+  A3_REQUIRE(a3_aligned16(k_fused) && a3_aligned16(v_fused) && a3_aligned16(k_out) && a3_aligned16(v_out),
+             A3_ERR_INVALID_ARG, "a3_evict_compact: tensors must be 16-byte aligned");
+  const int head_bytes = L->head_dim * (L->dtype == A3_BF16 ? 2 : 4);
+  A3_REQUIRE(head_bytes % 16 == 0, A3_ERR_UNSUPPORTED, "a3_evict_compact: a head row of %d bytes", head_bytes);
+  const long n = (long)total_keep * L->n_kv_heads * (head_bytes / 16);
+  hipLaunchKernelGGL(evict_compact_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
+                     (const uint4 *)k_fused, (const uint4 *)v_fused, keep_idx, total_keep, L->n_kv_heads, head_bytes / 16,
+                     (uint4 *)k_out, (uint4 *)v_out);
+  A3_CHECK_LAUNCH("a3_evict_compact");
   return A3_OK;
 }

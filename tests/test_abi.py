@@ -130,6 +130,25 @@ def test_bad_arguments_are_rejected_before_launch():
     assert L.a3_rms_norm(p, None, None, 5, 0x1000, 1e-5, 0x1000, None) == api.A3_ERR_INVALID_ARG
     assert L.a3_rms_norm(p, 0x1000, None, 5, 0x1000, -1.0, 0x1000, None) == api.A3_ERR_INVALID_ARG
     assert L.a3_rms_norm(p, 0x1004, None, 5, 0x1000, 1e-5, 0x1000, None) == api.A3_ERR_INVALID_ARG
+    # selection-score variant and eviction extension
+    assert L.a3_question_scores_causal(p, 0x1000, 0x1000, None, 0x1000, 1 << 40, None) == api.A3_ERR_INVALID_ARG
+    assert L.a3_question_scores_causal(p, 0x1000, 0x1000, 0x1000, None, 0, None) == api.A3_ERR_WORKSPACE
+    assert L.a3_window_votes(p, 0x1000, 0x1000, None, 0x1000, 1 << 40, None) == api.A3_ERR_INVALID_ARG
+    assert L.a3_window_votes(p, 0x1000, 0x1000, 0x1000, 0x1000, 16, None) == api.A3_ERR_WORKSPACE
+    assert L.a3_evict_ws_bytes(p) >= 8 * 16448 * 4 and L.a3_evict_ws_bytes(None) == 0
+    ev = lambda *a: L.a3_evict_select(p, *a)
+    assert ev(0x1000, 0x1000, 0x1000, 0, 1, 0, None, None, 0, None) == api.A3_OK                      # nothing kept
+    assert ev(None, 0x1000, 0x1000, 1024, 1, 0, 0x1000, None, 0, None) == api.A3_ERR_INVALID_ARG
+    assert ev(0x1000, 0x1000, 0x1000, -1, 1, 0, 0x1000, None, 0, None) == api.A3_ERR_INVALID_ARG
+    assert ev(0x1000, 0x1000, 0x1000, 10 ** 6, 1, 0, 0x1000, None, 0, None) == api.A3_ERR_INVALID_ARG
+    assert ev(0x1000, 0x1000, 0x1000, 1024, 4, 0, 0x1000, None, 0, None) == api.A3_ERR_INVALID_ARG     # even width
+    assert ev(0x1000, 0x1000, 0x1000, 1024, 65, 0, 0x1000, None, 0, None) == api.A3_ERR_INVALID_ARG
+    assert ev(0x1000, 0x1000, 0x1000, 1024, 7, 5, 0x1000, None, 0, None) == api.A3_ERR_INVALID_ARG     # pooling mode
+    assert ev(0x1000, 0x1000, 0x1000, 1024, 7, 0, 0x1000, None, 0, None) == api.A3_ERR_WORKSPACE       # pooling needs ws
+    assert ev(0x1000, 0x1000, 0x1000, 1024, 1, 0, None, None, 0, None) == api.A3_ERR_INVALID_ARG
+    assert L.a3_evict_compact(p, 0x1000, 0x1000, 0x1000, 0, 0x1000, 0x1000, None) == api.A3_OK
+    assert L.a3_evict_compact(p, 0x1000, None, 0x1000, 8, 0x1000, 0x1000, None) == api.A3_ERR_INVALID_ARG
+    assert L.a3_evict_compact(p, 0x1000, 0x1008, 0x1000, 8, 0x1000, 0x1000, None) == api.A3_ERR_INVALID_ARG
     f32_d64 = _host_layout(dtype=api.A3_F32, head_dim=64)
     assert L.a3_rope_realign(C.byref(f32_d64), None, None, None) == api.A3_ERR_INVALID_ARG
     bf16_d64 = _host_layout(head_dim=64)
