@@ -181,6 +181,37 @@ def stack_main(args):
     torch.cuda.synchronize()
     tail_us = e0.elapsed_time(e1) * 1e3 / 20
     tail_flops = 2.0 * n_act * (qd * h + 3 * h * f)
+    # eviction extension on one layer's cache: votes of the question window, retention at C = 1024 per KV head
+    # (system prompt of 32 rows and the question always kept), compaction of K and V
+    C, S = 1024, 32
+    budget = [min(max(C - S - int(q), 0), int(n) - S) for n, q in zip(w.ctx_len, w.q_lens)]
+    keep_start = np.concatenate([[0], np.cumsum([S + b + int(q) for b, q in zip(budget, w.q_lens)])]).astype(np.int32)
+    total_keep = int(keep_start[-1])
+    dev_i32 = lambda a: torch.as_tensor(np.ascontiguousarray(a, dtype=np.int32), device="cuda")
+    sys_len_d, keep_start_d = dev_i32([S] * w.n_req), dev_i32(keep_start)
+    q_question = mk(w.total_q, s.n_q_heads, s.head_dim, std=1.0)
+    kc = k_cat[2] if args.stack > 2 else mk(T, s.n_kv_heads, s.head_dim, std=sigma)
+    vc = v_cat[2] if args.stack > 2 else mk(T, s.n_kv_heads, s.head_dim, std=sigma)
+    votes = torch.empty((s.n_kv_heads, T), dtype=torch.float32, device="cuda")
+    keep = torch.empty((s.n_kv_heads, total_keep), dtype=torch.int32, device="cuda")
+    k_ev = torch.empty((total_keep, s.n_kv_heads, s.head_dim), dtype=dt, device="cuda")
+    v_ev = torch.empty_like(k_ev)
+    ws_e = lay.workspace(0)
+
+    def evict():
+        api.a3_window_votes(lay, q_question, kc, votes, ws_e)
+        api.a3_evict_select(lay, votes, sys_len_d, keep_start_d, total_keep, keep)
+        api.a3_evict_compact(lay, kc, vc, keep, total_keep, k_ev, v_ev)
+
+    for _ in range(3):
+        evict()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(20):
+        evict()
+    e1.record()
+    torch.cuda.synchronize()
+    evict_us = e0.elapsed_time(e1) * 1e3 / 20
     print(json.dumps({
         "metric": f"time of the A^3 schedule over {args.stack} decoder blocks (embedding output to final hidden "
                   "states of the rows [Re, Q])",
@@ -193,6 +224,8 @@ def stack_main(args):
         "block_tail": {"us_per_call": round(tail_us, 1), "rows": n_act, "flops_per_call": tail_flops,
                        "achieved_TFLOPs": round(tail_flops / tail_us / 1e6, 1),
                        "frac_of_mfma_peak": tail_flops / tail_us / 1e6 / PEAK_BF16_TFLOPS},
+        "eviction": {"capacity": C, "system_prompt_rows": S, "us_per_layer": round(evict_us, 1),
+                     "ms_all_layers": round(evict_us * args.stack / 1e3, 3), "rows_kept_per_head": total_keep},
     }))
 
 
