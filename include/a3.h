@@ -250,6 +250,22 @@ a3_status a3_evict_select(const a3_layout *layout, const float *votes, const int
 a3_status a3_evict_compact(const a3_layout *layout, const void *k_fused, const void *v_fused, const int *keep_idx,
                            int total_keep, void *k_out, void *v_out, void *stream);
 
+/* ---- alternative producers of the recompute list Re (Experiments, "Baselines"): they replace steps 2-3, the
+ * lists feed steps 4-5 unchanged ---------------------------------------------------------------------------
+ *
+ * Largest value deviation: scores[t] = sum over KV heads and coordinates of (v_true[t] - v_cat[t])^2 for
+ * context rows, -inf for question rows; a3_topk_select then takes the top p.  v_true, v_cat:
+ * [total_tokens, n_kv_heads, head_dim] (v_true from a V-only a3_selected_qkv_proj over all rows). */
+a3_status a3_value_deviation_scores(const a3_layout *layout, const void *v_true, const void *v_cat, float *scores,
+                                    void *stream);
+
+/* Chunk edges: for request r, sel_idx[sel_start[r] .. sel_start[r+1]) receives, ascending, the first n_head
+ * and the last n_tail rows of each of its chunks (a chunk of at most n_head + n_tail rows: all its rows).
+ * The caller sizes sel_start: request r holds sum over its chunks of min(chunk_len, n_head + n_tail) rows;
+ * total_k = sel_start[n_req] (host value). */
+a3_status a3_select_chunk_edges(const a3_layout *layout, int n_head, int n_tail, const int *sel_start, int total_k,
+                                int *sel_idx, void *stream);
+
 const char *a3_strerror(a3_status status);
 /* Text of the last error raised on the calling thread ("" if none). */
 const char *a3_last_error(void);

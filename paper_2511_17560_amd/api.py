@@ -23,7 +23,8 @@ A3_POOL_MAX, A3_POOL_AVG = 0, 1
 EXPORTS = ["a3_workspace_bytes", "a3_layout_prepare", "a3_rope_realign", "a3_question_scores", "a3_realign_scores", "a3_topk_select",
            "a3_selected_qkv_proj", "a3_selected_qkv_proj_scatter", "a3_kv_scatter", "a3_fused_attention", "a3_active_rows",
            "a3_block_tail_ws_bytes", "a3_block_tail", "a3_rms_norm", "a3_question_scores_causal", "a3_window_votes",
-           "a3_evict_ws_bytes", "a3_evict_select", "a3_evict_compact", "a3_strerror", "a3_last_error", "a3_version"]
+           "a3_evict_ws_bytes", "a3_evict_select", "a3_evict_compact", "a3_value_deviation_scores",
+           "a3_select_chunk_edges", "a3_strerror", "a3_last_error", "a3_version"]
 
 
 class A3Error(RuntimeError):
@@ -86,6 +87,10 @@ def lib() -> C.CDLL:
     L.a3_evict_ws_bytes.argtypes = [P]
     L.a3_evict_select.argtypes = [P, V, V, V, I, I, I, V, V, C.c_size_t, V]
     L.a3_evict_compact.argtypes = [P, V, V, V, I, V, V, V]
+    L.a3_value_deviation_scores.argtypes = [P, V, V, V, V]
+    L.a3_select_chunk_edges.argtypes = [P, I, I, V, I, V, V]
+    L.a3_value_deviation_scores.restype = I
+    L.a3_select_chunk_edges.restype = I
     for name in ("a3_question_scores_causal", "a3_window_votes", "a3_evict_select", "a3_evict_compact"):
         getattr(L, name).restype = I
     L.a3_rms_norm.restype = I
@@ -301,3 +306,24 @@ def a3_evict_compact(layout: Layout, k_fused: torch.Tensor, v_fused: torch.Tenso
                      total_keep: int, k_out: torch.Tensor, v_out: torch.Tensor, stream=None) -> None:
     _check(lib().a3_evict_compact(layout.ref, _ptr(k_fused), _ptr(v_fused), _ptr(keep_idx), int(total_keep),
                                   _ptr(k_out), _ptr(v_out), _stream(stream)), "a3_evict_compact")
+
+
+def a3_value_deviation_scores(layout: Layout, v_true: torch.Tensor, v_cat: torch.Tensor, scores: torch.Tensor,
+                              stream=None) -> None:
+    _check(lib().a3_value_deviation_scores(layout.ref, _ptr(v_true), _ptr(v_cat), _ptr(scores), _stream(stream)),
+           "a3_value_deviation_scores")
+
+
+def chunk_edge_sel_start(seg_start, ctx_len, chunk_start, chunk_len, n_head: int, n_tail: int) -> np.ndarray:
+    """sel_start [R+1] for a3_select_chunk_edges: request r holds, per chunk, min(chunk_len, n_head + n_tail) rows."""
+    counts = []
+    for r in range(len(ctx_len)):
+        lo, hi = int(seg_start[r]), int(seg_start[r]) + int(ctx_len[r])
+        counts.append(sum(min(int(n), n_head + n_tail) for s, n in zip(chunk_start, chunk_len) if lo <= int(s) < hi))
+    return np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+
+
+def a3_select_chunk_edges(layout: Layout, n_head: int, n_tail: int, sel_start: torch.Tensor, total_k: int,
+                          sel_idx: torch.Tensor, stream=None) -> None:
+    _check(lib().a3_select_chunk_edges(layout.ref, int(n_head), int(n_tail), _ptr(sel_start), int(total_k),
+                                       _ptr(sel_idx), _stream(stream)), "a3_select_chunk_edges")

@@ -203,6 +203,62 @@ active_rows_kernel(const int *__restrict__ sel_idx, const int *__restrict__ sel_
   act_idx[i] = j < k ? sel_idx[sel_start[r] + j] : seg_start[r] + ctx_len[r] + (j - k);
 }
 
+// ---------------------------------------------------------------------------------------
+// alternative producers of the recompute list
+// ---------------------------------------------------------------------------------------
+// scores[t] = |v_true[t] - v_cat[t]|^2 over all KV heads for context rows, -inf for question rows.
+// One wave per row, 16 bytes per lane and step, lanes added in a fixed tree.
+template <typename T>
+__global__ void __launch_bounds__(kBlock)
+value_deviation_kernel(const T *__restrict__ a, const T *__restrict__ b, const int *__restrict__ tok_chunk,
+                       float *__restrict__ scores, int n_rows, int row_elems) {
+  constexpr int V = a3_elem<T>::kVec;
+  typedef T vec_t __attribute__((ext_vector_type(V)));
+  const int lane = threadIdx.x & 63, t = blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6);
+  if (t >= n_rows) return;
+  if (tok_chunk[t] < 0) {
+    if (lane == 0) scores[t] = -INFINITY;
+    return;
+  }
+  const T *pa = a + (size_t)t * row_elems, *pb = b + (size_t)t * row_elems;
+  float acc = 0.f;
+  for (int v = lane; v < row_elems / V; v += 64) {
+    const vec_t x = *reinterpret_cast<const vec_t *>(pa + v * V), y = *reinterpret_cast<const vec_t *>(pb + v * V);
+#pragma unroll
+    for (int e = 0; e < V; ++e) { const float d = (float)x[e] - (float)y[e]; acc = fmaf(d, d, acc); }
+  }
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) acc += __shfl_xor(acc, o);
+  if (lane == 0) scores[t] = acc;
+}
+
+// The first n_head and the last n_tail rows of every chunk (a chunk no longer than n_head + n_tail: all of
+// its rows once), per request in ascending order.  One thread per chunk; its output offset is the request's
+// start plus the counts of the request's earlier chunks.
+__global__ void __launch_bounds__(kBlock)
+chunk_edges_kernel(const int *__restrict__ chunk_start, const int *__restrict__ chunk_len,
+                   const int *__restrict__ tok_req, const int *__restrict__ sel_start, int n_chunks, int n_head,
+                   int n_tail, int *__restrict__ sel_idx) {
+  const int c = blockIdx.x * kBlock + threadIdx.x;
+  if (c >= n_chunks) return;
+  const int len = chunk_len[c];
+  if (len <= 0) return;
+  const int s = chunk_start[c], r = tok_req[s];
+  int off = sel_start[r];
+  for (int p = c - 1; p >= 0; --p) {
+    const int pl = chunk_len[p];
+    if (pl <= 0) continue;
+    if (tok_req[chunk_start[p]] != r) break;
+    off += min(pl, n_head + n_tail);
+  }
+  if (len <= n_head + n_tail) {
+    for (int i = 0; i < len; ++i) sel_idx[off + i] = s + i;
+  } else {
+    for (int i = 0; i < n_head; ++i) sel_idx[off + i] = s + i;
+    for (int i = 0; i < n_tail; ++i) sel_idx[off + n_head + i] = s + len - n_tail + i;
+  }
+}
+
 template <typename T>
 a3_status launch_realign(const a3_layout *L, const void *k_cat, void *k_fused, hipStream_t st) {
   constexpr int VEC = a3_elem<T>::kVec;
@@ -288,5 +344,43 @@ extern "C" a3_status a3_active_rows(const a3_layout *L, const int *sel_idx, cons
   hipLaunchKernelGGL(active_rows_kernel, dim3((n_act + kBlock - 1) / kBlock), dim3(kBlock), 0, (hipStream_t)stream,
                      sel_idx, sel_start, L->q_start, L->seg_start, L->ctx_len, L->n_req, n_act, act_idx);
   A3_CHECK_LAUNCH("a3_active_rows");
+  return A3_OK;
+}
+
+extern "C" a3_status a3_value_deviation_scores(const a3_layout *L, const void *v_true, const void *v_cat,
+                                               float *scores, void *stream) {
+  a3_status s = a3_check_layout(L, "a3_value_deviation_scores", true);
+  if (s != A3_OK) return s;
+  if (L->total_tokens == 0) return A3_OK;
+  A3_REQUIRE(v_true && v_cat && scores, A3_ERR_INVALID_ARG, "a3_value_deviation_scores: NULL tensor");
+  A3_REQUIRE(a3_aligned16(v_true) && a3_aligned16(v_cat), A3_ERR_INVALID_ARG,
+             "a3_value_deviation_scores: tensors must be 16-byte aligned");
+  const int row_elems = L->n_kv_heads * L->head_dim;
+  const dim3 grid((L->total_tokens + kBlock / 64 - 1) / (kBlock / 64));
+  if (L->dtype == A3_BF16) {
+    A3_REQUIRE(row_elems % 8 == 0, A3_ERR_UNSUPPORTED, "a3_value_deviation_scores: row of %d elements", row_elems);
+    hipLaunchKernelGGL(value_deviation_kernel<bf16_t>, grid, dim3(kBlock), 0, (hipStream_t)stream, (const bf16_t *)v_true,
+                       (const bf16_t *)v_cat, L->tok_chunk, scores, L->total_tokens, row_elems);
+  } else {
+    A3_REQUIRE(row_elems % 4 == 0, A3_ERR_UNSUPPORTED, "a3_value_deviation_scores: row of %d elements", row_elems);
+    hipLaunchKernelGGL(value_deviation_kernel<float>, grid, dim3(kBlock), 0, (hipStream_t)stream, (const float *)v_true,
+                       (const float *)v_cat, L->tok_chunk, scores, L->total_tokens, row_elems);
+  }
+  A3_CHECK_LAUNCH("a3_value_deviation_scores");
+  return A3_OK;
+}
+
+extern "C" a3_status a3_select_chunk_edges(const a3_layout *L, int n_head, int n_tail, const int *sel_start,
+                                           int total_k, int *sel_idx, void *stream) {
+  a3_status s = a3_check_layout(L, "a3_select_chunk_edges", true);
+  if (s != A3_OK) return s;
+  A3_REQUIRE(n_head >= 0 && n_tail >= 0, A3_ERR_INVALID_ARG, "a3_select_chunk_edges: n_head %d, n_tail %d", n_head, n_tail);
+  A3_REQUIRE(total_k >= 0 && total_k <= L->total_tokens, A3_ERR_INVALID_ARG,
+             "a3_select_chunk_edges: total_k %d outside [0, %d]", total_k, L->total_tokens);
+  if (total_k == 0 || L->n_chunks == 0) return A3_OK;
+  A3_REQUIRE(sel_start && sel_idx, A3_ERR_INVALID_ARG, "a3_select_chunk_edges: NULL argument");
+  hipLaunchKernelGGL(chunk_edges_kernel, dim3((L->n_chunks + kBlock - 1) / kBlock), dim3(kBlock), 0, (hipStream_t)stream,
+                     L->chunk_start, L->chunk_len, L->tok_req, sel_start, L->n_chunks, n_head, n_tail, sel_idx);
+  A3_CHECK_LAUNCH("a3_select_chunk_edges");
   return A3_OK;
 }

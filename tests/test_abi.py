@@ -149,6 +149,13 @@ def test_bad_arguments_are_rejected_before_launch():
     assert L.a3_evict_compact(p, 0x1000, 0x1000, 0x1000, 0, 0x1000, 0x1000, None) == api.A3_OK
     assert L.a3_evict_compact(p, 0x1000, None, 0x1000, 8, 0x1000, 0x1000, None) == api.A3_ERR_INVALID_ARG
     assert L.a3_evict_compact(p, 0x1000, 0x1008, 0x1000, 8, 0x1000, 0x1000, None) == api.A3_ERR_INVALID_ARG
+    # alternative producers of the recompute list
+    assert L.a3_value_deviation_scores(p, None, 0x1000, 0x1000, None) == api.A3_ERR_INVALID_ARG
+    assert L.a3_value_deviation_scores(p, 0x1000, 0x1004, 0x1000, None) == api.A3_ERR_INVALID_ARG
+    assert L.a3_select_chunk_edges(p, -1, 20, 0x1000, 100, 0x1000, None) == api.A3_ERR_INVALID_ARG
+    assert L.a3_select_chunk_edges(p, 20, 20, 0x1000, 10 ** 6, 0x1000, None) == api.A3_ERR_INVALID_ARG
+    assert L.a3_select_chunk_edges(p, 20, 20, None, 100, 0x1000, None) == api.A3_ERR_INVALID_ARG
+    assert L.a3_select_chunk_edges(p, 20, 20, 0x1000, 0, None, None) == api.A3_OK
     f32_d64 = _host_layout(dtype=api.A3_F32, head_dim=64)
     assert L.a3_rope_realign(C.byref(f32_d64), None, None, None) == api.A3_ERR_INVALID_ARG
     bf16_d64 = _host_layout(head_dim=64)

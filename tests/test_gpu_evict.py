@@ -120,3 +120,56 @@ def test_evict_on_the_gpus_own_votes_16k():
     # and the votes themselves against the oracle, all 8 x 16384 of them
     want = ev.kv_head_votes(ev.window_votes(res["q_question"], res["k_fused"], sm_scale=scale, **kw), s.n_kv_heads)
     assert max_abs_rel(vt[:, :N], want[:, :N]) <= 1e-4
+
+
+# ---------------------------------------------------------------------------------------
+# alternative producers of the recompute list
+# ---------------------------------------------------------------------------------------
+from oracle import selectors_oracle as sel_ora   # noqa: E402
+
+
+@pytest.mark.parametrize("name", NAMES)
+def test_value_deviation_scores_and_selection(name):
+    """|V_true - V_cat|^2 per context row (1e-5), then the unchanged top-p on the GPU's own scores: checked by
+    the property that defines it (no unselected row scores higher than a selected one, count and order)."""
+    c, w, res, lay, kw, scale = _inputs(name)
+    s, t, b = w.shape, c["b"]["t"], c["b"]
+    dt = s.dtype
+    rows = np.arange(w.total_tokens)
+    _, _, v_true = ora.selected_qkv_proj(t.x_cur, rows, w.token_positions(), t.wq, t.wk, t.wv, s.n_q_heads, s.n_kv_heads,
+                                         s.head_dim, s.rope_base, s.rope_layout, dt)
+    want = sel_ora.value_deviation_scores(v_true, b["v_cat"], w.seg_start, w.ctx_len)
+    scores = torch.zeros(w.total_tokens, dtype=torch.float32, device="cuda")
+    api.a3_value_deviation_scores(lay, to_dev(v_true, dt), to_dev(b["v_cat"], dt), scores)
+    sel = torch.full((max(w.total_k, 1),), -1, dtype=torch.int32, device="cuda")
+    api.a3_topk_select(lay, scores, idev(w.sel_start), w.total_k, sel)
+    torch.cuda.synchronize()
+    got = to_host(scores)
+    ctx = np.concatenate([w.ctx_rows(r) for r in range(w.n_req)])
+    assert max_abs_rel(got[ctx], want[ctx]) <= 1e-5
+    assert np.all(np.isneginf(got[w.question_rows()]))
+    picked = sel.cpu().numpy()[:w.total_k]
+    for r in range(w.n_req):
+        mine = picked[w.sel_start[r]:w.sel_start[r + 1]]
+        assert np.all(np.diff(mine) > 0) and np.all(np.isin(mine, w.ctx_rows(r)))
+        rest = np.setdiff1d(w.ctx_rows(r), mine)
+        if len(mine) and len(rest):
+            assert got[mine].min() >= got[rest].max()
+    # and it is the oracle's list wherever the oracle's ranking is not a near-tie
+    want_sel = ora.topk_select(want, w.seg_start, w.ctx_len, w.sel_start)
+    flips = set(picked.tolist()) ^ set(want_sel.tolist())
+    assert len(flips) <= max(2, w.total_k // 50)
+
+
+@pytest.mark.parametrize("name", NAMES)
+@pytest.mark.parametrize("n_head,n_tail", [(20, 20), (3, 0), (0, 5), (600, 600), (0, 0)])
+def test_select_chunk_edges(name, n_head, n_tail):
+    c, w, res, lay, kw, scale = _inputs(name)
+    want_idx, want_start = sel_ora.chunk_edge_rows(w.seg_start, w.ctx_len, w.chunk_start, w.chunk_len, n_head, n_tail)
+    start = api.chunk_edge_sel_start(w.seg_start, w.ctx_len, w.chunk_start, w.chunk_len, n_head, n_tail)
+    assert np.array_equal(start, want_start)
+    total = int(start[-1])
+    out = torch.full((max(total, 1),), -1, dtype=torch.int32, device="cuda")
+    api.a3_select_chunk_edges(lay, n_head, n_tail, idev(start), total, out)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy()[:total], want_idx)
