@@ -163,6 +163,16 @@ def stack_main(args):
     assert out["n_act"] == w.total_k + w.total_q and np.all(np.diff(act) > 0)
     assert bool(torch.isfinite(out["hidden"][out["act_idx"].long()].float()).all())
     full_ms, _ = timed(lambda: stack.prefill_stack(lay, s, layers, g_final, resid), max(1, steps // 4), 1)
+    streamed_ms = None
+    if args.stream_caches:
+        from paper_2511_17560_amd import loader
+        host_k = [None if c is None else [c[s0:s0 + n].cpu().pin_memory() for s0, n in zip(w.chunk_start, w.chunk_len)]
+                  for c in k_cat]
+        host_v = [None if c is None else [c[s0:s0 + n].cpu().pin_memory() for s0, n in zip(w.chunk_start, w.chunk_len)]
+                  for c in v_cat]
+        cs = loader.ChunkCacheStream(lay, s, w.chunk_start, w.chunk_len, host_k, host_v, depth=2)
+        streamed_ms, _ = timed(lambda: stack.fuse_stack(lay, s, layers, g_final, resid, None, None, w.sel_start, q_rows,
+                                                        cache_stream=cs), steps, warmup)
     n_act = out["n_act"]
     # H(.) alone at the active rows: the call that dominates a layer once the rows are few
     attn_out = mk(n_act, s.n_q_heads, s.head_dim, std=1.0)
@@ -221,6 +231,9 @@ def stack_main(args):
                    "selected_tokens": w.total_k, "requests": w.n_req,
                    "shape": f"h{s.hidden}/Hq{s.n_q_heads}/Hkv{s.n_kv_heads}/d{s.head_dim}/ffn{s.ffn}"},
         "full_prefill_ms": full_ms, "speedup_over_full_prefill": full_ms / fuse_ms,
+        "streamed_caches_ms": streamed_ms,
+        "streamed_cache_bytes": None if streamed_ms is None else
+        2 * (args.stack - 2) * int(w.total_ctx) * kd * (2 if s.dtype == "bf16" else 4),
         "block_tail": {"us_per_call": round(tail_us, 1), "rows": n_act, "flops_per_call": tail_flops,
                        "achieved_TFLOPs": round(tail_flops / tail_us / 1e6, 1),
                        "frac_of_mfma_peak": tail_flops / tail_us / 1e6 / PEAK_BF16_TFLOPS},
@@ -237,6 +250,9 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="workload configuration 1..5 (3 = the 16K-context metric)")
     ap.add_argument("--layers", type=int, default=0, help="independent layer buffer sets to cycle (0 = 32 for config 3)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--stream-caches", action="store_true",
+                    help="with --stack: also time the schedule with the chunk caches streamed from pinned host memory "
+                         "layer by layer (a3_chunk_cache_load on a copy stream) instead of resident in HBM")
     ap.add_argument("--stack", type=int, default=0,
                     help="L >= 2: time the A^3 schedule over L decoder blocks against the plain prefill of the same "
                          "stack instead of the per-layer hot path (not the headline metric)")

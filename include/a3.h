@@ -266,6 +266,21 @@ a3_status a3_value_deviation_scores(const a3_layout *layout, const void *v_true,
 a3_status a3_select_chunk_edges(const a3_layout *layout, int n_head, int n_tail, const int *sel_start, int total_k,
                                 int *sel_idx, void *stream);
 
+/* ---- chunk-cache staging (Eq. 1's per-chunk K/V store lives outside the GPU; the paper names loading it as
+ * the method's limitation) ---------------------------------------------------------------------------------
+ *
+ * Copies one layer's chunk blocks from HOST memory into their packed slots of the concatenated caches:
+ * rows [chunk_start_host[c], + chunk_len_host[c]) of k_cat / v_cat receive host_k[c] / host_v[c], each a
+ * contiguous [chunk_len, n_kv_heads, head_dim] block in the layout's dtype.  chunk_start_host and
+ * chunk_len_host are HOST arrays (the layout's own are device pointers); host_k / host_v are host arrays of
+ * n_chunks HOST pointers; k_cat, v_cat are device pointers.  The copies are enqueued on `stream` and are
+ * asynchronous when the host blocks are pinned (hipHostMalloc); the caller keeps the blocks alive until the
+ * stream has passed them.  Nothing is allocated.  Errors: A3_ERR_INVALID_ARG (before any copy is enqueued),
+ * A3_ERR_HIP. */
+a3_status a3_chunk_cache_load(const a3_layout *layout, const int *chunk_start_host, const int *chunk_len_host,
+                              int n_chunks, const void *const *host_k, const void *const *host_v,
+                              void *k_cat, void *v_cat, void *stream);
+
 const char *a3_strerror(a3_status status);
 /* Text of the last error raised on the calling thread ("" if none). */
 const char *a3_last_error(void);

@@ -24,7 +24,7 @@ EXPORTS = ["a3_workspace_bytes", "a3_layout_prepare", "a3_rope_realign", "a3_que
            "a3_selected_qkv_proj", "a3_selected_qkv_proj_scatter", "a3_kv_scatter", "a3_fused_attention", "a3_active_rows",
            "a3_block_tail_ws_bytes", "a3_block_tail", "a3_rms_norm", "a3_question_scores_causal", "a3_window_votes",
            "a3_evict_ws_bytes", "a3_evict_select", "a3_evict_compact", "a3_value_deviation_scores",
-           "a3_select_chunk_edges", "a3_strerror", "a3_last_error", "a3_version"]
+           "a3_select_chunk_edges", "a3_chunk_cache_load", "a3_strerror", "a3_last_error", "a3_version"]
 
 
 class A3Error(RuntimeError):
@@ -90,6 +90,9 @@ def lib() -> C.CDLL:
     L.a3_value_deviation_scores.argtypes = [P, V, V, V, V]
     L.a3_select_chunk_edges.argtypes = [P, I, I, V, I, V, V]
     L.a3_value_deviation_scores.restype = I
+    L.a3_chunk_cache_load.argtypes = [P, C.POINTER(C.c_int), C.POINTER(C.c_int), I, C.POINTER(C.c_void_p),
+                                      C.POINTER(C.c_void_p), V, V, V]
+    L.a3_chunk_cache_load.restype = I
     L.a3_select_chunk_edges.restype = I
     for name in ("a3_question_scores_causal", "a3_window_votes", "a3_evict_select", "a3_evict_compact"):
         getattr(L, name).restype = I
@@ -327,3 +330,18 @@ def a3_select_chunk_edges(layout: Layout, n_head: int, n_tail: int, sel_start: t
                           sel_idx: torch.Tensor, stream=None) -> None:
     _check(lib().a3_select_chunk_edges(layout.ref, int(n_head), int(n_tail), _ptr(sel_start), int(total_k),
                                        _ptr(sel_idx), _stream(stream)), "a3_select_chunk_edges")
+
+
+def a3_chunk_cache_load(layout: Layout, chunk_start, chunk_len, host_k, host_v, k_cat: torch.Tensor,
+                        v_cat: torch.Tensor, stream=None) -> None:
+    """host_k / host_v: one CPU tensor per chunk ([chunk_len, Hkv, d], pinned for asynchronous copies); the
+    caller keeps them alive until the stream has passed the copies."""
+    n = len(chunk_start)
+    starts = (C.c_int * n)(*[int(x) for x in chunk_start])
+    lens = (C.c_int * n)(*[int(x) for x in chunk_len])
+    for t in list(host_k) + list(host_v):
+        assert t is None or (t.device.type == "cpu" and t.is_contiguous())
+    pk = (C.c_void_p * n)(*[t.data_ptr() if t is not None else None for t in host_k])
+    pv = (C.c_void_p * n)(*[t.data_ptr() if t is not None else None for t in host_v])
+    _check(lib().a3_chunk_cache_load(layout.ref, starts, lens, n, pk, pv, _ptr(k_cat), _ptr(v_cat), _stream(stream)),
+           "a3_chunk_cache_load")

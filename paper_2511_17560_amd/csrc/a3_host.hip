@@ -1,5 +1,5 @@
 // Host-side plumbing of liba3: status strings, per-thread error text, layout validation,
-// workspace sizing.  No kernels here.
+// workspace sizing, and the staging of chunk caches from host memory.  No kernels here.
 #include <stdarg.h>
 #include <stdio.h>
 #include <string.h>
@@ -69,4 +69,36 @@ extern "C" size_t a3_workspace_bytes(const a3_layout *L, int max_active_rows) {
   size_t a = a3_scores_ws_bytes(L);
   size_t b = a3_attn_ws_bytes(L, max_active_rows);
   return (a > b ? a : b) + 256;
+}
+
+// The per-chunk K/V store of Eq. 1 lives outside the GPU (the paper keeps it on persistent storage and names
+// its loading cost as the method's limitation).  One layer's chunks go from host memory into their packed
+// slots of the concatenated cache as asynchronous copies on the caller's stream: with pinned host blocks and
+// a stream of its own they run beside the kernels of the previous layer.
+extern "C" a3_status a3_chunk_cache_load(const a3_layout *L, const int *chunk_start_host, const int *chunk_len_host,
+                                         int n_chunks, const void *const *host_k, const void *const *host_v,
+                                         void *k_cat, void *v_cat, void *stream) {
+  a3_status s = a3_check_layout(L, "a3_chunk_cache_load", false);
+  if (s != A3_OK) return s;
+  A3_REQUIRE(n_chunks >= 0, A3_ERR_INVALID_ARG, "a3_chunk_cache_load: n_chunks %d is negative", n_chunks);
+  if (n_chunks == 0) return A3_OK;
+  A3_REQUIRE(chunk_start_host && chunk_len_host && host_k && host_v && k_cat && v_cat, A3_ERR_INVALID_ARG,
+             "a3_chunk_cache_load: NULL argument");
+  const size_t row_bytes = (size_t)L->n_kv_heads * L->head_dim * (L->dtype == A3_BF16 ? 2 : 4);
+  for (int c = 0; c < n_chunks; ++c) {
+    const int start = chunk_start_host[c], len = chunk_len_host[c];
+    A3_REQUIRE(len >= 0 && start >= 0 && (long long)start + len <= L->total_tokens, A3_ERR_INVALID_ARG,
+               "a3_chunk_cache_load: chunk %d covers rows [%d, %d) outside [0, %d)", c, start, start + len,
+               L->total_tokens);
+    A3_REQUIRE(len == 0 || (host_k[c] && host_v[c]), A3_ERR_INVALID_ARG, "a3_chunk_cache_load: chunk %d has no host block", c);
+  }
+  hipStream_t st = (hipStream_t)stream;
+  for (int c = 0; c < n_chunks; ++c) {
+    const size_t bytes = (size_t)chunk_len_host[c] * row_bytes, off = (size_t)chunk_start_host[c] * row_bytes;
+    if (bytes == 0) continue;
+    hipError_t e = hipMemcpyAsync((char *)k_cat + off, host_k[c], bytes, hipMemcpyHostToDevice, st);
+    if (e == hipSuccess) e = hipMemcpyAsync((char *)v_cat + off, host_v[c], bytes, hipMemcpyHostToDevice, st);
+    if (e != hipSuccess) return a3_fail(A3_ERR_HIP, "a3_chunk_cache_load: chunk %d: %s", c, hipGetErrorString(e));
+  }
+  return A3_OK;
 }

@@ -1,0 +1,59 @@
+"""Streams the per-layer chunk caches from pinned host memory into HBM beside the computation.
+
+The chunk K/V store of Eq. 1 is far larger than one prompt needs and lives outside the GPU; a prompt only
+needs, layer by layer, the blocks of its own chunks in their packed slots.  ``ChunkCacheStream`` keeps a small
+ring of device buffers, fills buffer ``l % depth`` with layer ``l`` on a copy stream (a3_chunk_cache_load)
+while earlier layers compute, and hands the buffers over with events.  Sequencing only.
+"""
+from __future__ import annotations
+
+from typing import List, Sequence
+
+import torch
+
+from . import api
+
+
+class ChunkCacheStream:
+    """host_k[l][c], host_v[l][c]: pinned CPU tensors [chunk_len[c], Hkv, d] of layer l, chunk c
+    (None for layers that use no cache).  ``depth`` device buffer pairs are cycled."""
+
+    def __init__(self, layout: api.Layout, shape, chunk_start, chunk_len, host_k: Sequence, host_v: Sequence,
+                 depth: int = 2):
+        assert depth >= 2
+        self.layout, self.depth = layout, depth
+        self.chunk_start, self.chunk_len = list(map(int, chunk_start)), list(map(int, chunk_len))
+        self.host_k, self.host_v = host_k, host_v
+        dt = api.torch_dtype(layout.dtype)
+        T = layout.total_tokens
+        mk = lambda: torch.zeros((T, shape.n_kv_heads, shape.head_dim), dtype=dt, device=layout.device)
+        self.k = [mk() for _ in range(depth)]
+        self.v = [mk() for _ in range(depth)]
+        self.copy_stream = torch.cuda.Stream(device=layout.device)          # default priority
+        self.loaded: List = [None] * depth       # event: buffer i holds its layer
+        self.free: List = [None] * depth         # event: the consumer of buffer i is done with it
+
+    def prefetch(self, l: int) -> None:
+        """Enqueue layer l's copies on the copy stream (after the buffer's previous consumer has finished)."""
+        if l >= len(self.host_k) or self.host_k[l] is None:
+            return
+        i = l % self.depth
+        if self.free[i] is not None:
+            self.copy_stream.wait_event(self.free[i])
+        api.a3_chunk_cache_load(self.layout, self.chunk_start, self.chunk_len, self.host_k[l], self.host_v[l],
+                                self.k[i], self.v[i], stream=self.copy_stream)
+        ev = torch.cuda.Event()
+        ev.record(self.copy_stream)
+        self.loaded[i] = ev
+
+    def acquire(self, l: int, stream=None):
+        """(k_cat, v_cat) of layer l; the compute stream waits until the copies have landed."""
+        i = l % self.depth
+        (stream or torch.cuda.current_stream()).wait_event(self.loaded[i])
+        return self.k[i], self.v[i]
+
+    def release(self, l: int, stream=None) -> None:
+        """The compute stream is done with layer l's buffers (recorded as an event)."""
+        ev = torch.cuda.Event()
+        ev.record(stream or torch.cuda.current_stream())
+        self.free[l % self.depth] = ev

@@ -19,11 +19,14 @@ from . import api
 
 def fuse_stack(layout: api.Layout, shape, layers: Sequence[Dict[str, torch.Tensor]], g_final: torch.Tensor,
                resid: torch.Tensor, k_cat: List[torch.Tensor], v_cat: List[torch.Tensor], sel_start: np.ndarray,
-               q_rows: np.ndarray, stream=None, keep: bool = False) -> dict:
+               q_rows: np.ndarray, stream=None, keep: bool = False, cache_stream=None) -> dict:
     """``resid`` [T, h] holds the embedding output and is overwritten by the residual stream (all rows after
     block 0, the active rows afterwards).  ``k_cat[l]`` / ``v_cat[l]`` are the chunk caches of layer l >= 2
     (entries 0 and 1 are ignored); ``v_cat[l]`` is updated in place.  Every layer dict holds wq, wk, wv, wo,
     g_in, g_post, w_gate, w_up, w_down and optionally bq, bk, bv.
+    With ``cache_stream`` (a loader.ChunkCacheStream) the caches are not resident: layer l's blocks are copied
+    from host memory into a ring of device buffers while the layers before it compute, and ``k_cat`` / ``v_cat``
+    are ignored.
     Returns dict(sel_idx, act_idx, n_act, scores, resid, hidden): ``hidden`` [T, h] holds the final-normed
     output at the active rows.  With ``keep`` the per-layer attention outputs and caches are kept too."""
     dev, dt = layout.device, api.torch_dtype(layout.dtype)
@@ -50,6 +53,10 @@ def fuse_stack(layout: api.Layout, shape, layers: Sequence[Dict[str, torch.Tenso
 
     def bias(lw):
         return dict(bq=lw.get("bq"), bk=lw.get("bk"), bv=lw.get("bv"))
+
+    if cache_stream is not None:
+        for l in range(2, min(2 + cache_stream.depth, n_layers)):
+            cache_stream.prefetch(l)
 
     # ---- block 0 on every row ---------------------------------------------------------------------------
     lw = layers[0]
@@ -94,13 +101,17 @@ def fuse_stack(layout: api.Layout, shape, layers: Sequence[Dict[str, torch.Tenso
     # ---- layers 2 ..: Eq. 2, Eq. 5 --------------------------------------------------------------------------
     for l in range(2, n_layers):
         lw = layers[l]
-        api.a3_rope_realign(layout, k_cat[l], k_l, stream=stream)
+        k_c, v_c = (k_cat[l], v_cat[l]) if cache_stream is None else cache_stream.acquire(l, stream)
+        api.a3_rope_realign(layout, k_c, k_l, stream=stream)
         api.a3_selected_qkv_proj_scatter(layout, x, act_idx, n_act, lw["wq"], lw["wk"], lw["wv"], q_out=q_act,
-                                         k_fused=k_l, v_fused=v_cat[l], stream=stream, **bias(lw))
-        api.a3_fused_attention(layout, q_act, act_idx, n_act, k_l, v_cat[l], out, ws_attn, stream=stream)
-        tail(l, out, act_idx, n_act)
+                                         k_fused=k_l, v_fused=v_c, stream=stream, **bias(lw))
+        api.a3_fused_attention(layout, q_act, act_idx, n_act, k_l, v_c, out, ws_attn, stream=stream)
         if keep:
-            kept.append(dict(k=k_l.clone(), v=v_cat[l].clone(), out=out[:n_act].clone()))
+            kept.append(dict(k=k_l.clone(), v=v_c.clone(), out=out[:n_act].clone()))
+        if cache_stream is not None:
+            cache_stream.release(l, stream)
+            cache_stream.prefetch(l + cache_stream.depth)
+        tail(l, out, act_idx, n_act)
     return dict(sel_idx=sel_idx[:total_k], act_idx=act_idx[:n_act], n_act=n_act, scores=scores, resid=resid, hidden=x,
                 per_layer=kept)
 

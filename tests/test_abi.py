@@ -156,6 +156,18 @@ def test_bad_arguments_are_rejected_before_launch():
     assert L.a3_select_chunk_edges(p, 20, 20, 0x1000, 10 ** 6, 0x1000, None) == api.A3_ERR_INVALID_ARG
     assert L.a3_select_chunk_edges(p, 20, 20, None, 100, 0x1000, None) == api.A3_ERR_INVALID_ARG
     assert L.a3_select_chunk_edges(p, 20, 20, 0x1000, 0, None, None) == api.A3_OK
+    # chunk-cache staging: every argument is checked before a copy is enqueued
+    starts, lens = (C.c_int * 2)(0, 512), (C.c_int * 2)(512, 512)
+    blocks = (C.c_void_p * 2)(0x1000, 0x1000)
+    load = lambda *a: L.a3_chunk_cache_load(p, *a)
+    assert load(starts, lens, 0, blocks, blocks, 0x1000, 0x1000, None) == api.A3_OK
+    assert load(starts, lens, -1, blocks, blocks, 0x1000, 0x1000, None) == api.A3_ERR_INVALID_ARG
+    assert load(starts, lens, 2, blocks, blocks, None, 0x1000, None) == api.A3_ERR_INVALID_ARG
+    assert load(None, lens, 2, blocks, blocks, 0x1000, 0x1000, None) == api.A3_ERR_INVALID_ARG
+    past = (C.c_int * 2)(0, 16448 - 100)
+    assert load(past, lens, 2, blocks, blocks, 0x1000, 0x1000, None) == api.A3_ERR_INVALID_ARG       # runs past the last row
+    holes = (C.c_void_p * 2)(0x1000, None)
+    assert load(starts, lens, 2, holes, blocks, 0x1000, 0x1000, None) == api.A3_ERR_INVALID_ARG
     f32_d64 = _host_layout(dtype=api.A3_F32, head_dim=64)
     assert L.a3_rope_realign(C.byref(f32_d64), None, None, None) == api.A3_ERR_INVALID_ARG
     bf16_d64 = _host_layout(head_dim=64)

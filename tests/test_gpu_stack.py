@@ -254,3 +254,57 @@ def test_prefill_stack(case):
     for l in range(n_layers):
         assert max_abs_rel(to_host(alone["k"][l]), k_cat[l][s0:s0 + n]) <= tol, l
         assert max_abs_rel(to_host(alone["v"][l]), v_cat[l][s0:s0 + n]) <= tol, l
+
+
+def test_chunk_cache_load_and_streamed_stack():
+    """a3_chunk_cache_load puts every chunk block at its packed rows (bit-exact, other rows untouched), and
+    the schedule run on caches streamed from pinned host memory layer by layer gives bit for bit what it
+    gives on resident caches."""
+    from paper_2511_17560_amd import loader
+    shape, chunk_lens, q_lens, ratio, n_layers = STACK_CASES["batched-bf16"]
+    n_layers = 6
+    dt = shape.dtype
+    w = synth.custom(shape, chunk_lens, q_lens, ratio=ratio, seed=79)
+    sw = synth.draw_stack_weights(w, n_layers)
+    for lw in sw["layers"]:
+        for k in ("wq", "wk"):
+            lw[k] = synth.round_to_storage(lw[k] * np.float32(5.0), dt)
+    lay = api.Layout.from_workload(w)
+    rng = np.random.default_rng(3)
+    T = w.total_tokens
+    tdt = api.torch_dtype(dt)
+    caches_k = [None, None] + [synth.round_to_storage(rng.standard_normal((T, shape.n_kv_heads, shape.head_dim), dtype=np.float32), dt)
+                               for _ in range(n_layers - 2)]
+    caches_v = [None, None] + [synth.round_to_storage(rng.standard_normal((T, shape.n_kv_heads, shape.head_dim), dtype=np.float32), dt)
+                               for _ in range(n_layers - 2)]
+    pin = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(tdt).pin_memory()
+    host_k = [None if ck is None else [pin(ck[s:s + n]) for s, n in zip(w.chunk_start, w.chunk_len)] for ck in caches_k]
+    host_v = [None if cv is None else [pin(cv[s:s + n]) for s, n in zip(w.chunk_start, w.chunk_len)] for cv in caches_v]
+    # the copy itself
+    k_dev = torch.full((T, shape.n_kv_heads, shape.head_dim), 9.0, dtype=tdt, device="cuda")
+    v_dev = torch.full_like(k_dev, 9.0)
+    api.a3_chunk_cache_load(lay, w.chunk_start, w.chunk_len, host_k[2], host_v[2], k_dev, v_dev)
+    torch.cuda.synchronize()
+    ctx = np.concatenate([w.ctx_rows(r) for r in range(w.n_req)])
+    assert np.array_equal(to_host(k_dev)[ctx], caches_k[2][ctx].astype(F64)) and np.array_equal(to_host(v_dev)[ctx], caches_v[2][ctx].astype(F64))
+    assert np.all(to_host(k_dev)[w.question_rows()] == 9.0)
+    with pytest.raises(api.A3Error):
+        api.a3_chunk_cache_load(lay, [T - 3], [10], [host_k[2][0]], [host_v[2][0]], k_dev, v_dev)   # runs past the last row
+    # the schedule, resident against streamed
+    dev_layers = [{k: to_dev(v, dt) for k, v in lw.items()} for lw in sw["layers"]]
+    g_final = to_dev(sw["g_final"], dt)
+
+    def resident():
+        kc = [None if c is None else to_dev(np.where(np.isin(np.arange(T), ctx)[:, None, None], c, 0), dt) for c in caches_k]
+        vc = [None if c is None else to_dev(np.where(np.isin(np.arange(T), ctx)[:, None, None], c, 0), dt) for c in caches_v]
+        return stack.fuse_stack(lay, shape, dev_layers, g_final, to_dev(sw["resid0"], dt), kc, vc, w.sel_start,
+                                w.question_rows())
+
+    a = resident()
+    cs = loader.ChunkCacheStream(lay, shape, w.chunk_start, w.chunk_len, host_k, host_v, depth=2)
+    b = stack.fuse_stack(lay, shape, dev_layers, g_final, to_dev(sw["resid0"], dt), None, None, w.sel_start,
+                         w.question_rows(), cache_stream=cs)
+    torch.cuda.synchronize()
+    assert torch.equal(a["act_idx"], b["act_idx"])
+    rows = a["act_idx"].long()
+    assert torch.equal(a["hidden"][rows], b["hidden"][rows]) and torch.equal(a["resid"][rows], b["resid"][rows])
