@@ -96,7 +96,7 @@ __device__ __forceinline__ int plan_scan(int v, int *wave_tot, int *total) {
 
 __global__ void __launch_bounds__(kPlanThreads)
 attn_plan_kernel(attn_plan p, const int *__restrict__ act_idx, int n_act, const int *__restrict__ seg_start,
-                 int n_req, int G, int wgs_per_head) {
+                 int n_req, int G, int wgs_per_head, int item_cost) {
   __shared__ int wave_tot[kPlanThreads / 64];
   const int tid = threadIdx.x;
   // active rows are ascending, so the rows of request r are a contiguous range found by bisection
@@ -114,7 +114,9 @@ attn_plan_kernel(attn_plan p, const int *__restrict__ act_idx, int n_act, const 
   __syncthreads();
   const int n_tiles = min(p.tile_start[n_req], p.max_tiles);
 
-  // ---- tiles and the running number of key steps -----------------------------------------
+  // ---- tiles and their running cost -------------------------------------------------------
+  // A tile is laid out as `item_cost` units of start-up (fetching its queries and first keys, storing its
+  // result: measured at six to seven key steps) followed by one unit per key step.
   int carry = 0;
   for (int base = 0; base < n_tiles; base += kPlanThreads) {
     const int t = base + tid;
@@ -130,16 +132,16 @@ attn_plan_kernel(attn_plan p, const int *__restrict__ act_idx, int n_act, const 
       p.tile_a[t] = make_int4(r, j * kTM, kv, nr * G);
     }
     int total;
-    const int before = plan_scan(steps, wave_tot, &total);
+    const int before = plan_scan(t < n_tiles ? steps + item_cost : 0, wave_tot, &total);
     if (t < n_tiles) p.tile_pre[t] = carry + before;
     carry += total;
   }
-  const int W = carry;                                       // key steps of one head, >= n_tiles
+  const int W = carry;                                       // cost of one head, >= n_tiles
   if (tid == 0) p.tile_pre[n_tiles] = W;
   __syncthreads();
 
   // ---- equal shares ------------------------------------------------------------------------
-  int P = (W + 7) / 8;
+  int P = (W - n_tiles * item_cost + 7) / 8;                  // at least 8 key steps per share
   if (P > wgs_per_head) P = wgs_per_head;
   if (P > p.max_wgs) P = p.max_wgs;
   if (P < 1) P = 1;
@@ -149,9 +151,10 @@ attn_plan_kernel(attn_plan p, const int *__restrict__ act_idx, int n_act, const 
     s_beg = (long long)tid * W / P;
     s_end = (long long)(tid + 1) * W / P;
     if (s_end > s_beg) {
-      t0 = upper_bound_i32(p.tile_pre, n_tiles + 1, (int)s_beg) - 1;
-      const int t1 = lower_bound_i32(p.tile_pre, n_tiles + 1, (int)s_end) - 1;
-      cnt = t1 - t0 + 1;
+      t0 = upper_bound_i32(p.tile_pre, n_tiles + 1, (int)s_beg) - 1;    // tile that holds position s_beg
+      const int t1 = lower_bound_i32(p.tile_pre, n_tiles + 1, (int)s_end) - 1;   // ... and position s_end - 1
+      // the last tile only counts if the share reaches past its start-up units
+      cnt = t1 - t0 + 1 - (s_end <= (long long)p.tile_pre[t1] + item_cost ? 1 : 0);
     }
   }
   int n_items;
@@ -161,7 +164,7 @@ attn_plan_kernel(attn_plan p, const int *__restrict__ act_idx, int n_act, const 
   for (int i = 0; i < cnt; ++i) {
     const int t = t0 + i, idx = first + i;
     if (idx >= p.max_items) break;
-    const int pre = p.tile_pre[t], nxt = p.tile_pre[t + 1];
+    const int pre = p.tile_pre[t] + item_cost, nxt = p.tile_pre[t + 1];  // key step s of the tile sits at pre + s
     const int it_b = (int)(s_beg > pre ? s_beg - pre : 0), it_e = (int)((s_end < nxt ? s_end : nxt) - pre);
     const int kv = p.tile_a[t].z;
     p.items[idx] = make_int4(t, it_b * kTK, min(kv, it_e * kTK), 0);
@@ -169,7 +172,7 @@ attn_plan_kernel(attn_plan p, const int *__restrict__ act_idx, int n_act, const 
   }
   // items of a tile = share boundaries strictly inside it + 1; boundary q lies at floor(q W / P)
   for (int t = tid; t < n_tiles; t += kPlanThreads) {
-    const long long x = p.tile_pre[t], y = p.tile_pre[t + 1];
+    const long long x = (long long)p.tile_pre[t] + item_cost, y = p.tile_pre[t + 1];
     const long long ub = ((x + 1) * P + W - 1) / W;          // first q with floor(q W / P) > x
     const long long lb = (y * P + W - 1) / W;                // first q with floor(q W / P) >= y
     p.tile_b[t].y = (int)(lb > ub ? lb - ub : 0) + 1;
@@ -613,6 +616,17 @@ int attn_wgs_per_head(const a3_layout *L) {
   return w;
 }
 
+// Start-up cost of an item in key steps (what the share boundaries are balanced with), or the tuning
+// override A3_ATTN_ITEM_COST.
+int attn_item_cost() {
+  int c = 7;
+  if (const char *e = getenv("A3_ATTN_ITEM_COST")) {
+    int v = atoi(e);
+    if (v >= 0 && v <= 64) c = v;
+  }
+  return c;
+}
+
 // every tile starts an item, every share boundary inside a tile starts another
 int attn_max_items(const a3_layout *L, int n_act) { return attn_max_tiles(L, n_act) + attn_wgs_per_head(L); }
 
@@ -674,7 +688,7 @@ extern "C" a3_status a3_fused_attention(const a3_layout *L, const void *q_act, c
     a.plan.part_ml = (float2 *)cur.take((size_t)max_items * Hkv * kTM * sizeof(float2));
     a.plan.max_tiles = max_tiles; a.plan.max_items = max_items; a.plan.max_wgs = wgs_per_head;
     hipLaunchKernelGGL(attn_plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, a.plan, act_idx, n_act, L->seg_start,
-                       L->n_req, L->n_q_heads / L->n_kv_heads, wgs_per_head);
+                       L->n_req, L->n_q_heads / L->n_kv_heads, wgs_per_head, attn_item_cost());
     // blockIdx % Hkv = KV head, so with 8 KV heads each XCD's L2 serves the K/V of one head
     hipLaunchKernelGGL(attn_bf16_kernel, dim3((unsigned)wgs_per_head * Hkv), dim3(kAttnThreads), kAttnLds, st, a);
     hipLaunchKernelGGL(attn_combine_kernel, dim3((unsigned)max_tiles, Hkv, kTM / 32), dim3(256), 0, st, a);

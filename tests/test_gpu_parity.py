@@ -273,14 +273,18 @@ def test_fused_attention(name):
     assert max_abs_rel(to_host(out), res["out"]) <= tol(w)
 
 
-@pytest.mark.parametrize("wgs", ["1", "3", "37", "300"])
+@pytest.mark.parametrize("wgs,item_cost", [("1", None), ("3", None), ("37", None), ("300", None), ("37", "0"),
+                                           ("5", "64"), ("300", "1"), ("32", "30")])
 @pytest.mark.parametrize("name", ["ragged-bf16", "batched-bf16-half", "g7-bf16", "cfg2", "long-bf16"])
-def test_fused_attention_with_other_share_counts(name, wgs, monkeypatch):
-    """The key steps of all tiles are cut into one equal share per workgroup of a KV head.  Other
-    numbers of workgroups move the cuts: none at all (1), a few long shares, many short ones (tiles
-    cut into several items, items that start or end exactly on a tile boundary, rows that see nothing
-    of a later item, ordered merge of the partial results)."""
+def test_fused_attention_with_other_share_counts(name, wgs, item_cost, monkeypatch):
+    """The work of all tiles (key steps plus a start-up cost per tile) is cut into one equal share per
+    workgroup of a KV head.  Other numbers of workgroups and other start-up costs move the cuts: none at
+    all (1), a few long shares, many short ones (tiles cut into several items, items that start or end
+    exactly on a tile boundary, cuts that fall into a tile's start-up units, rows that see nothing of a
+    later item, ordered merge of the partial results)."""
     monkeypatch.setenv("A3_ATTN_WGS", wgs)
+    if item_cost is not None:
+        monkeypatch.setenv("A3_ATTN_ITEM_COST", item_cost)
     c = ctx_of(name)
     w, res, lay = c["w"], c["res"], c["lay"]
     s = w.shape
