@@ -361,6 +361,22 @@ def main():
         return out
 
     per_call_us = breakdown(True)
+
+    # what a plain device copy of the realign's size reaches on this machine (read + write): the practical
+    # ceiling the HBM-bound kernels are up against, next to the nominal peak
+    src = layers[0]["k_cat"]
+    dsts = [torch.empty_like(src) for _ in range(4)]
+    for d in dsts:
+        d.copy_(src)
+    torch.cuda.synchronize()
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0.record()
+    for i in range(32):
+        dsts[i % 4].copy_(layers[i % n_layers]["k_cat"])
+    c1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 2 * src.numel() * src.element_size() / (c0.elapsed_time(c1) * 1e-3 / 32) / 1e9
+    del dsts
     per_call_plain = breakdown(False)
 
     # ---- sanity: the pass produced a full, finite result --------------------------------------------
@@ -384,6 +400,7 @@ def main():
         "attn_TFLOPs": work["attn_flops"] / (per_call_us["a3_fused_attention"]["us_per_step"] * 1e-6) / 1e12,
         # both passes form every logit once
         "scores_TFLOPs": 2 * work["scores_flops"] / (per_call_plain["a3_question_scores"]["us_per_step"] * 1e-6) / 1e12,
+        "plain_copy_same_size_GBs": copy_gbs,
     }
     result = {
         "metric": "fused-context tokens/sec per layer at 16K ctx" if args.config == 3
