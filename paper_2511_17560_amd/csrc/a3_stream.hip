@@ -238,7 +238,7 @@ value_deviation_kernel(const T *__restrict__ a, const T *__restrict__ b, const i
 __global__ void __launch_bounds__(kBlock)
 chunk_edges_kernel(const int *__restrict__ chunk_start, const int *__restrict__ chunk_len,
                    const int *__restrict__ tok_req, const int *__restrict__ sel_start, int n_chunks, int n_head,
-                   int n_tail, int *__restrict__ sel_idx) {
+                   int n_tail, int total_k, int *__restrict__ sel_idx) {
   const int c = blockIdx.x * kBlock + threadIdx.x;
   if (c >= n_chunks) return;
   const int len = chunk_len[c];
@@ -251,11 +251,15 @@ chunk_edges_kernel(const int *__restrict__ chunk_start, const int *__restrict__ 
     if (tok_req[chunk_start[p]] != r) break;
     off += min(pl, n_head + n_tail);
   }
+  // (a sel_start that does not match the rule must not send a store outside the list)
   if (len <= n_head + n_tail) {
-    for (int i = 0; i < len; ++i) sel_idx[off + i] = s + i;
+    for (int i = 0; i < len; ++i)
+      if (off + i >= 0 && off + i < total_k) sel_idx[off + i] = s + i;
   } else {
-    for (int i = 0; i < n_head; ++i) sel_idx[off + i] = s + i;
-    for (int i = 0; i < n_tail; ++i) sel_idx[off + n_head + i] = s + len - n_tail + i;
+    for (int i = 0; i < n_head; ++i)
+      if (off + i >= 0 && off + i < total_k) sel_idx[off + i] = s + i;
+    for (int i = 0; i < n_tail; ++i)
+      if (off + n_head + i >= 0 && off + n_head + i < total_k) sel_idx[off + n_head + i] = s + len - n_tail + i;
   }
 }
 
@@ -380,7 +384,7 @@ extern "C" a3_status a3_select_chunk_edges(const a3_layout *L, int n_head, int n
   if (total_k == 0 || L->n_chunks == 0) return A3_OK;
   A3_REQUIRE(sel_start && sel_idx, A3_ERR_INVALID_ARG, "a3_select_chunk_edges: NULL argument");
   hipLaunchKernelGGL(chunk_edges_kernel, dim3((L->n_chunks + kBlock - 1) / kBlock), dim3(kBlock), 0, (hipStream_t)stream,
-                     L->chunk_start, L->chunk_len, L->tok_req, sel_start, L->n_chunks, n_head, n_tail, sel_idx);
+                     L->chunk_start, L->chunk_len, L->tok_req, sel_start, L->n_chunks, n_head, n_tail, total_k, sel_idx);
   A3_CHECK_LAUNCH("a3_select_chunk_edges");
   return A3_OK;
 }

@@ -340,13 +340,16 @@ pool_votes_kernel(const float *__restrict__ in, float *__restrict__ out, const i
 // keep_idx[g][keep_start[r] + i] for the system-prompt rows (i < skip[r]) and the question rows (the last
 // q_len[r] slots of the request)
 __global__ void __launch_bounds__(256)
-evict_fixed_rows_kernel(topk_problem p, int *__restrict__ keep_idx) {
+evict_fixed_rows_kernel(topk_problem p, int total_keep, int *__restrict__ keep_idx) {
   const int r = blockIdx.x;
   int *out = keep_idx + (size_t)blockIdx.y * p.out_stride;
   const int s = p.seg_start[r], N = p.ctx_len[r], nq = p.q_len[r], sk = p.skip[r];
   const int o0 = p.sel_start[r], o1 = p.sel_start[r + 1];
-  for (int i = threadIdx.x; i < sk; i += 256) out[o0 + i] = s + i;
-  for (int j = threadIdx.x; j < nq; j += 256) out[o1 - nq + j] = s + N + j;
+  // (a keep_start that does not match the rule must not send a store outside the list)
+  for (int i = threadIdx.x; i < sk; i += 256)
+    if (o0 + i >= 0 && o0 + i < total_keep) out[o0 + i] = s + i;
+  for (int j = threadIdx.x; j < nq; j += 256)
+    if (o1 - nq + j >= 0 && o1 - nq + j < total_keep) out[o1 - nq + j] = s + N + j;
 }
 
 // out[slot, g, :] = in[keep_idx[g][slot], g, :] for K and V; 16 bytes per lane
@@ -412,7 +415,7 @@ extern "C" a3_status a3_evict_select(const a3_layout *L, const float *votes, con
   }
   const topk_problem prob{L->seg_start, L->ctx_len, keep_start, sys_len, L->q_len, (long)L->total_tokens,
                           (long)total_keep};
-  hipLaunchKernelGGL(evict_fixed_rows_kernel, dim3(L->n_req, L->n_kv_heads), dim3(256), 0, st, prob, keep_idx);
+  hipLaunchKernelGGL(evict_fixed_rows_kernel, dim3(L->n_req, L->n_kv_heads), dim3(256), 0, st, prob, total_keep, keep_idx);
   return topk_launch(L, ranked, prob, L->n_kv_heads, keep_idx, st, "a3_evict_select");
 }
 
