@@ -168,6 +168,17 @@ a3_status a3_fused_attention(const a3_layout *layout, const void *q_act, const i
                              const void *k_fused, const void *v_fused, void *out,
                              void *ws, size_t ws_bytes, void *stream);
 
+/* The same step in two calls.  How a3_fused_attention divides its work among the compute units depends only
+ * on the list of active rows, so it can be laid out as soon as that list exists: a3_attention_plan writes the
+ * layout into ws (one small kernel), a3_fused_attention_planned then attends with it.  Between the two calls
+ * nothing else may write ws; the arguments they share must be the same; stream order (or an event) must put the
+ * plan first.  Together they give what a3_fused_attention gives, bit for bit. */
+a3_status a3_attention_plan(const a3_layout *layout, const int *act_idx, int n_act, void *ws, size_t ws_bytes,
+                            void *stream);
+a3_status a3_fused_attention_planned(const a3_layout *layout, const void *q_act, const int *act_idx, int n_act,
+                                     const void *k_fused, const void *v_fused, void *out,
+                                     void *ws, size_t ws_bytes, void *stream);
+
 /* Helper between steps 3 and 4: the active rows [Re, Q] of Eq. 4 / Eq. 5 in ascending packed order.
  * For request r, act_idx receives its k_r selected rows followed by its q_len[r] question rows, at
  * offset sel_start[r] + q_start[r].  sel_idx: device int32 [total_k] as written by a3_topk_select;

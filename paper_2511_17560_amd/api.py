@@ -21,7 +21,7 @@ A3_ROPE_INTERLEAVED, A3_ROPE_HALF = 0, 1
 A3_POOL_MAX, A3_POOL_AVG = 0, 1
 
 EXPORTS = ["a3_workspace_bytes", "a3_layout_prepare", "a3_rope_realign", "a3_question_scores", "a3_realign_scores", "a3_topk_select",
-           "a3_selected_qkv_proj", "a3_selected_qkv_proj_scatter", "a3_kv_scatter", "a3_fused_attention", "a3_active_rows",
+           "a3_selected_qkv_proj", "a3_selected_qkv_proj_scatter", "a3_kv_scatter", "a3_fused_attention", "a3_attention_plan", "a3_fused_attention_planned", "a3_active_rows",
            "a3_block_tail_ws_bytes", "a3_block_tail", "a3_rms_norm", "a3_question_scores_causal", "a3_window_votes",
            "a3_evict_ws_bytes", "a3_evict_select", "a3_evict_compact", "a3_value_deviation_scores",
            "a3_select_chunk_edges", "a3_chunk_cache_load", "a3_strerror", "a3_last_error", "a3_version"]
@@ -76,6 +76,10 @@ def lib() -> C.CDLL:
     L.a3_kv_scatter.argtypes = [P, V, V, V, I, V, V, V]
     L.a3_fused_attention.argtypes = [P, V, V, I, V, V, V, V, C.c_size_t, V]
     L.a3_active_rows.argtypes = [P, V, V, I, V, V]
+    L.a3_attention_plan.argtypes = [P, V, I, V, C.c_size_t, V]
+    L.a3_fused_attention_planned.argtypes = [P, V, V, I, V, V, V, V, C.c_size_t, V]
+    L.a3_attention_plan.restype = I
+    L.a3_fused_attention_planned.restype = I
     L.a3_block_tail_ws_bytes.restype = C.c_size_t
     L.a3_block_tail_ws_bytes.argtypes = [P, I, I]
     L.a3_block_tail.argtypes = [P, V, V, I, C.POINTER(a3_block_weights), V, V, V, C.c_size_t, V]
@@ -345,3 +349,16 @@ def a3_chunk_cache_load(layout: Layout, chunk_start, chunk_len, host_k, host_v, 
     pv = (C.c_void_p * n)(*[t.data_ptr() if t is not None else None for t in host_v])
     _check(lib().a3_chunk_cache_load(layout.ref, starts, lens, n, pk, pv, _ptr(k_cat), _ptr(v_cat), _stream(stream)),
            "a3_chunk_cache_load")
+
+
+def a3_attention_plan(layout: Layout, act_idx: torch.Tensor, n_act: int, ws: torch.Tensor, stream=None) -> None:
+    _check(lib().a3_attention_plan(layout.ref, _ptr(act_idx), int(n_act), _ptr(ws), ws.numel() if ws is not None else 0,
+                                   _stream(stream)), "a3_attention_plan")
+
+
+def a3_fused_attention_planned(layout: Layout, q_act: torch.Tensor, act_idx: torch.Tensor, n_act: int,
+                               k_fused: torch.Tensor, v_fused: torch.Tensor, out: torch.Tensor, ws: torch.Tensor,
+                               stream=None) -> None:
+    _check(lib().a3_fused_attention_planned(layout.ref, _ptr(q_act), _ptr(act_idx), int(n_act), _ptr(k_fused),
+                                            _ptr(v_fused), _ptr(out), _ptr(ws), ws.numel() if ws is not None else 0,
+                                            _stream(stream)), "a3_fused_attention_planned")

@@ -643,17 +643,22 @@ size_t a3_attn_ws_bytes(const a3_layout *L, int max_active_rows) {
          a3_align_up(items * L->n_kv_heads * kTM * sizeof(float2), 256) + 2048;
 }
 
-extern "C" a3_status a3_fused_attention(const a3_layout *L, const void *q_act, const int *act_idx, int n_act,
-                                        const void *k_fused, const void *v_fused, void *out, void *ws,
-                                        size_t ws_bytes, void *stream) {
+// parts & 1: lay out the work (plan kernel); parts & 2: attend and merge.  The plan only depends on the list of
+// active rows, so a caller may have it made beside whatever else precedes the attention.
+static a3_status attn_launch(const a3_layout *L, const void *q_act, const int *act_idx, int n_act,
+                             const void *k_fused, const void *v_fused, void *out, void *ws, size_t ws_bytes,
+                             void *stream, int parts) {
   a3_status s = a3_check_layout(L, "a3_fused_attention", true);
   if (s != A3_OK) return s;
   A3_REQUIRE(n_act >= 0 && n_act <= L->total_tokens, A3_ERR_INVALID_ARG,
              "a3_fused_attention: n_act %d outside [0, %d]", n_act, L->total_tokens);
   if (n_act == 0) return A3_OK;
-  A3_REQUIRE(q_act && act_idx && k_fused && v_fused && out, A3_ERR_INVALID_ARG, "a3_fused_attention: NULL argument");
-  A3_REQUIRE(a3_aligned16(q_act) && a3_aligned16(k_fused) && a3_aligned16(v_fused) && a3_aligned16(out),
-             A3_ERR_INVALID_ARG, "a3_fused_attention: tensors must be 16-byte aligned");
+  A3_REQUIRE(act_idx != nullptr, A3_ERR_INVALID_ARG, "a3_fused_attention: act_idx is NULL");
+  if (parts & 2) {
+    A3_REQUIRE(q_act && k_fused && v_fused && out, A3_ERR_INVALID_ARG, "a3_fused_attention: NULL argument");
+    A3_REQUIRE(a3_aligned16(q_act) && a3_aligned16(k_fused) && a3_aligned16(v_fused) && a3_aligned16(out),
+               A3_ERR_INVALID_ARG, "a3_fused_attention: tensors must be 16-byte aligned");
+  }
   hipStream_t st = (hipStream_t)stream;
   attn_args a;
   a.q = q_act; a.k = k_fused; a.v = v_fused; a.out = out;
@@ -687,14 +692,34 @@ extern "C" a3_status a3_fused_attention(const a3_layout *L, const void *q_act, c
     a.plan.part_o = (float *)cur.take((size_t)max_items * Hkv * kTM * kD * sizeof(float));
     a.plan.part_ml = (float2 *)cur.take((size_t)max_items * Hkv * kTM * sizeof(float2));
     a.plan.max_tiles = max_tiles; a.plan.max_items = max_items; a.plan.max_wgs = wgs_per_head;
-    hipLaunchKernelGGL(attn_plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, a.plan, act_idx, n_act, L->seg_start,
-                       L->n_req, L->n_q_heads / L->n_kv_heads, wgs_per_head, attn_item_cost());
-    // blockIdx % Hkv = KV head, so with 8 KV heads each XCD's L2 serves the K/V of one head
-    hipLaunchKernelGGL(attn_bf16_kernel, dim3((unsigned)wgs_per_head * Hkv), dim3(kAttnThreads), kAttnLds, st, a);
-    hipLaunchKernelGGL(attn_combine_kernel, dim3((unsigned)max_tiles, Hkv, kTM / 32), dim3(256), 0, st, a);
-  } else {
+    if (parts & 1)
+      hipLaunchKernelGGL(attn_plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, a.plan, act_idx, n_act, L->seg_start,
+                         L->n_req, L->n_q_heads / L->n_kv_heads, wgs_per_head, attn_item_cost());
+    if (parts & 2) {
+      // blockIdx % Hkv = KV head, so with 8 KV heads each XCD's L2 serves the K/V of one head
+      hipLaunchKernelGGL(attn_bf16_kernel, dim3((unsigned)wgs_per_head * Hkv), dim3(kAttnThreads), kAttnLds, st, a);
+      hipLaunchKernelGGL(attn_combine_kernel, dim3((unsigned)max_tiles, Hkv, kTM / 32), dim3(256), 0, st, a);
+    }
+  } else if (parts & 2) {
     hipLaunchKernelGGL(attn_f32_kernel, dim3(n_act, L->n_q_heads), dim3(256), 0, st, a);
   }
   A3_CHECK_LAUNCH("a3_fused_attention");
   return A3_OK;
+}
+
+extern "C" a3_status a3_fused_attention(const a3_layout *L, const void *q_act, const int *act_idx, int n_act,
+                                        const void *k_fused, const void *v_fused, void *out, void *ws,
+                                        size_t ws_bytes, void *stream) {
+  return attn_launch(L, q_act, act_idx, n_act, k_fused, v_fused, out, ws, ws_bytes, stream, 3);
+}
+
+extern "C" a3_status a3_attention_plan(const a3_layout *L, const int *act_idx, int n_act, void *ws, size_t ws_bytes,
+                                       void *stream) {
+  return attn_launch(L, nullptr, act_idx, n_act, nullptr, nullptr, nullptr, ws, ws_bytes, stream, 1);
+}
+
+extern "C" a3_status a3_fused_attention_planned(const a3_layout *L, const void *q_act, const int *act_idx, int n_act,
+                                                const void *k_fused, const void *v_fused, void *out, void *ws,
+                                                size_t ws_bytes, void *stream) {
+  return attn_launch(L, q_act, act_idx, n_act, k_fused, v_fused, out, ws, ws_bytes, stream, 2);
 }

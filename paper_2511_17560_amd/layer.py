@@ -32,6 +32,9 @@ class LayerBuffers:
     total_k: int
     n_act: int
     single: bool
+    side: object = None        # second stream (default priority) on which the attention plan is made
+    ev_rows: object = None     # event: the list of active rows is final
+    ev_plan: object = None     # event: the plan is in the workspace
 
 
 def make_buffers(layout: api.Layout, sel_start: np.ndarray, q_rows: np.ndarray, shape) -> LayerBuffers:
@@ -63,12 +66,13 @@ def make_buffers(layout: api.Layout, sel_start: np.ndarray, q_rows: np.ndarray, 
         k_act=torch.empty((max(n_act, 1), Hkv, d), dtype=dt, device=dev),
         v_act=torch.empty((max(n_act, 1), Hkv, d), dtype=dt, device=dev),
         out=torch.empty((max(n_act, 1), Hq, d), dtype=dt, device=dev),
-        ws=layout.workspace(n_act), total_k=total_k, n_act=n_act, single=single)
+        ws=layout.workspace(n_act), total_k=total_k, n_act=n_act, single=single,
+        side=torch.cuda.Stream(device=dev), ev_rows=torch.cuda.Event(), ev_plan=torch.cuda.Event())
 
 
 def fuse_layer(layout: api.Layout, b: LayerBuffers, x_cur: torch.Tensor, k_cat: torch.Tensor, v_cache: torch.Tensor,
                wq: torch.Tensor, wk: torch.Tensor, wv: torch.Tensor, stream=None, fused_scatter: bool = True,
-               fused_realign: bool = True) -> None:
+               fused_realign: bool = True, overlap_plan: bool = False) -> None:
     """Runs steps 1-5 for one layer.  ``k_cat`` is read, ``b.k_fused`` and ``v_cache`` (in place)
     hold the fused cache afterwards, ``b.out`` the attention output of the active rows.
 
@@ -76,7 +80,11 @@ def fuse_layer(layout: api.Layout, b: LayerBuffers, x_cur: torch.Tensor, k_cat: 
     (a3_selected_qkv_proj_scatter); otherwise the plain sequence a3_selected_qkv_proj ->
     a3_kv_scatter is used.  Both give the same cache: the question rows are written before the
     realign, which only writes context rows, and the selected rows after the scores were read.
-    ``fused_realign`` (default) runs steps 1 and 2 as one call (a3_realign_scores)."""
+    ``fused_realign`` (default) runs steps 1 and 2 as one call (a3_realign_scores).
+    ``overlap_plan`` has the attention's work laid out (a3_attention_plan, one small workgroup) on a second
+    stream as soon as the active rows are known, beside the projection of the selected rows, and then calls
+    a3_fused_attention_planned.  Off by default: on this hardware the two cross-stream waits cost more (about
+    20 us) than the 9 us plan kernel they hide."""
     nq = b.n_act - b.total_k
     k = b.total_k
     if b.single:
@@ -97,6 +105,13 @@ def fuse_layer(layout: api.Layout, b: LayerBuffers, x_cur: torch.Tensor, k_cat: 
     rows, n_rows = (b.sel_idx, k) if b.single else (b.act_idx, b.n_act)
     if not b.single:
         api.a3_active_rows(layout, b.sel_idx, b.sel_start, b.n_act, b.act_idx, stream=stream)
+    overlap_plan = overlap_plan and b.side is not None
+    if overlap_plan:
+        main = stream if stream is not None else torch.cuda.current_stream()
+        b.ev_rows.record(main)
+        b.side.wait_event(b.ev_rows)
+        api.a3_attention_plan(layout, b.act_idx, b.n_act, b.ws, stream=b.side)
+        b.ev_plan.record(b.side)
     if fused_scatter:
         api.a3_selected_qkv_proj_scatter(layout, x_cur, rows, n_rows, wq, wk, wv, q_out=b.q_act, k_fused=b.k_fused,
                                          v_fused=v_cache, stream=stream)
@@ -104,4 +119,9 @@ def fuse_layer(layout: api.Layout, b: LayerBuffers, x_cur: torch.Tensor, k_cat: 
         api.a3_selected_qkv_proj(layout, x_cur, rows, n_rows, wq, wk, wv, q_out=b.q_act, k_out=b.k_act,
                                  v_out=b.v_act, stream=stream)
         api.a3_kv_scatter(layout, b.k_act, b.v_act, b.act_idx, b.n_act, b.k_fused, v_cache, stream=stream)
-    api.a3_fused_attention(layout, b.q_act, b.act_idx, b.n_act, b.k_fused, v_cache, b.out, b.ws, stream=stream)
+    if overlap_plan:
+        main.wait_event(b.ev_plan)
+        api.a3_fused_attention_planned(layout, b.q_act, b.act_idx, b.n_act, b.k_fused, v_cache, b.out, b.ws,
+                                       stream=stream)
+    else:
+        api.a3_fused_attention(layout, b.q_act, b.act_idx, b.n_act, b.k_fused, v_cache, b.out, b.ws, stream=stream)

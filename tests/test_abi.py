@@ -93,6 +93,13 @@ def test_bad_arguments_are_rejected_before_launch():
         == api.A3_ERR_INVALID_ARG
     assert L.a3_fused_attention(p, None, None, 0, None, None, None, None, 0, None) == api.A3_OK
     assert L.a3_active_rows(p, None, None, 5, None, None) == api.A3_ERR_INVALID_ARG
+    assert L.a3_attention_plan(p, None, 10, 0x1000, 1 << 40, None) == api.A3_ERR_INVALID_ARG
+    assert L.a3_attention_plan(p, 0x1000, 10, None, 0, None) == api.A3_ERR_WORKSPACE
+    assert L.a3_attention_plan(p, 0x1000, 0, None, 0, None) == api.A3_OK
+    assert L.a3_fused_attention_planned(p, None, 0x1000, 10, 0x1000, 0x1000, 0x1000, 0x1000, 1 << 40, None) \
+        == api.A3_ERR_INVALID_ARG
+    assert L.a3_fused_attention_planned(p, 0x1000, 0x1000, 10, 0x1000, 0x1000, 0x1000, None, 0, None) \
+        == api.A3_ERR_WORKSPACE
     # the single-launch variants check what their plain counterparts check
     assert L.a3_realign_scores(p, 0x1000, None, 0x1000, 0x1000, 0x1000, 1 << 40, None) == api.A3_ERR_INVALID_ARG
     assert L.a3_realign_scores(p, 0x1000, 0x1008, 0x1000, 0x1000, 0x1000, 1 << 40, None) == api.A3_ERR_INVALID_ARG

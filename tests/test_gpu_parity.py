@@ -399,3 +399,43 @@ def test_full_size_config(name):
     test_fused_attention(name)
     test_chained_layer(name)
     _cache.pop(name, None)
+
+
+@pytest.mark.parametrize("name", ["ragged-bf16", "batched-bf16-half", "cfg2", "cfg1"])
+def test_attention_in_two_calls(name):
+    """a3_attention_plan (on a second stream, ordered by events) + a3_fused_attention_planned give what
+    a3_fused_attention gives, bit for bit; and the layer pass with and without that overlap agrees (the overlap
+    is off by default: the cross-stream waits cost more than the plan kernel they hide)."""
+    c = ctx_of(name)
+    w, res, lay = c["w"], c["res"], c["lay"]
+    s = w.shape
+    dt = s.dtype
+    act = res["act_idx"]
+    q, k, v, idx = to_dev(res["q_act"], dt), to_dev(res["k_fused"], dt), to_dev(res["v_fused"], dt), idev(act)
+    one = torch.zeros((len(act), s.n_q_heads, s.head_dim), dtype=api.torch_dtype(dt), device="cuda")
+    two = torch.zeros_like(one)
+    ws = lay.workspace(len(act))
+    api.a3_fused_attention(lay, q, idx, len(act), k, v, one, ws)
+    torch.cuda.synchronize()
+    ws.zero_()
+    side = torch.cuda.Stream()
+    ready, planned = torch.cuda.Event(), torch.cuda.Event()
+    ready.record()
+    side.wait_event(ready)
+    api.a3_attention_plan(lay, idx, len(act), ws, stream=side)
+    planned.record(side)
+    torch.cuda.current_stream().wait_event(planned)
+    api.a3_fused_attention_planned(lay, q, idx, len(act), k, v, two, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(one, two)
+    b, t = c["b"], c["b"]["t"]
+    outs = []
+    for overlap in (False, True, True):
+        bufs = layer.make_buffers(lay, w.sel_start, w.question_rows(), s)
+        v_cache = to_dev(b["v_cat"], dt)
+        layer.fuse_layer(lay, bufs, to_dev(t.x_cur, dt), to_dev(b["k_cat"], dt), v_cache, to_dev(t.wq, dt),
+                         to_dev(t.wk, dt), to_dev(t.wv, dt), overlap_plan=overlap)
+        torch.cuda.synchronize()
+        outs.append((bufs.out[:bufs.n_act].clone(), bufs.act_idx[:bufs.n_act].clone()))
+    for o, a in outs[1:]:
+        assert torch.equal(a, outs[0][1]) and torch.equal(o, outs[0][0])
