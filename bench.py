@@ -163,7 +163,7 @@ def stack_main(args):
     assert out["n_act"] == w.total_k + w.total_q and np.all(np.diff(act) > 0)
     assert bool(torch.isfinite(out["hidden"][out["act_idx"].long()].float()).all())
     full_ms, _ = timed(lambda: stack.prefill_stack(lay, s, layers, g_final, resid), max(1, steps // 4), 1)
-    streamed_ms = None
+    streamed_ms = streamed_q8_ms = None
     if args.stream_caches:
         from paper_2511_17560_amd import loader
         host_k = [None if c is None else [c[s0:s0 + n].cpu().pin_memory() for s0, n in zip(w.chunk_start, w.chunk_len)]
@@ -173,6 +173,21 @@ def stack_main(args):
         cs = loader.ChunkCacheStream(lay, s, w.chunk_start, w.chunk_len, host_k, host_v, depth=2)
         streamed_ms, _ = timed(lambda: stack.fuse_stack(lay, s, layers, g_final, resid, None, None, w.sel_start, q_rows,
                                                         cache_stream=cs), steps, warmup)
+        del cs, host_k, host_v
+        # the same with 8-bit blocks (quantised once by a3_quantize_q8, as a chunk store would hold them)
+        row = api.a3_q8_row_bytes(lay)
+        host_q8 = []
+        for kc, vc in zip(k_cat, v_cat):
+            if kc is None:
+                host_q8.append(None)
+                continue
+            rec = torch.empty((T, row), dtype=torch.uint8, device="cuda")
+            api.a3_quantize_q8(lay, kc, vc, rec)
+            rec = rec.cpu()
+            host_q8.append([rec[s0:s0 + n].contiguous().pin_memory() for s0, n in zip(w.chunk_start, w.chunk_len)])
+        cs8 = loader.ChunkCacheStream(lay, s, w.chunk_start, w.chunk_len, host_q8, None, depth=2)
+        streamed_q8_ms, _ = timed(lambda: stack.fuse_stack(lay, s, layers, g_final, resid, None, None, w.sel_start,
+                                                           q_rows, cache_stream=cs8), steps, warmup)
     n_act = out["n_act"]
     # H(.) alone at the active rows: the call that dominates a layer once the rows are few
     attn_out = mk(n_act, s.n_q_heads, s.head_dim, std=1.0)
@@ -234,6 +249,9 @@ def stack_main(args):
         "streamed_caches_ms": streamed_ms,
         "streamed_cache_bytes": None if streamed_ms is None else
         2 * (args.stack - 2) * int(w.total_ctx) * kd * (2 if s.dtype == "bf16" else 4),
+        "streamed_q8_caches_ms": streamed_q8_ms,
+        "streamed_q8_cache_bytes": None if streamed_q8_ms is None else
+        (args.stack - 2) * int(w.total_ctx) * row,
         "block_tail": {"us_per_call": round(tail_us, 1), "rows": n_act, "flops_per_call": tail_flops,
                        "achieved_TFLOPs": round(tail_flops / tail_us / 1e6, 1),
                        "frac_of_mfma_peak": tail_flops / tail_us / 1e6 / PEAK_BF16_TFLOPS},

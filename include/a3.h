@@ -292,6 +292,30 @@ a3_status a3_chunk_cache_load(const a3_layout *layout, const int *chunk_start_ho
                               int n_chunks, const void *const *host_k, const void *const *host_v,
                               void *k_cat, void *v_cat, void *stream);
 
+/* ---- 8-bit form of the chunk caches (the paper fixes no format and calls cache quantisation orthogonal; it
+ * halves what the staging above has to move) -----------------------------------------------------------------
+ *
+ * One packed row of one layer is one record of a3_q8_row_bytes(layout) = n_kv_heads * (2 * head_dim + 8) bytes:
+ *     [ K codes: n_kv_heads * head_dim int8 | V codes: the same | K scales: n_kv_heads float32 | V scales ],
+ * x = code * scale per row and KV head (symmetric).  A chunk's rows of both caches are one contiguous block.
+ * cache_q8 is [total_tokens] records, device, 16-byte aligned.
+ *
+ * a3_quantize_q8: the quantiser, run once when a chunk's caches are produced: k, v [total_tokens, n_kv_heads,
+ * head_dim] in the layout's dtype (finite values) -> records; the scale is the float32 rounding of max|x| / 127,
+ * the code the quotient x / scale rounded half to even, both taken in float64; a row of zeros gets scale 0 and
+ * codes 0.
+ * a3_rope_realign_q8: step 1 (Eq. 2) on the dequantised keys, and the values, in one kernel: k_fused receives,
+ * for context rows, the dequantised key turned by its chunk's offset, for question rows the dequantised key;
+ * v_fused receives the dequantised value; one rounding to the layout's dtype each.  Either output may be NULL.
+ * a3_chunk_cache_load_q8: as a3_chunk_cache_load, one host block of chunk_len[c] records and one copy per
+ * chunk. */
+size_t a3_q8_row_bytes(const a3_layout *layout);
+a3_status a3_quantize_q8(const a3_layout *layout, const void *k, const void *v, void *cache_q8, void *stream);
+a3_status a3_rope_realign_q8(const a3_layout *layout, const void *cache_q8, void *k_fused, void *v_fused,
+                             void *stream);
+a3_status a3_chunk_cache_load_q8(const a3_layout *layout, const int *chunk_start_host, const int *chunk_len_host,
+                                 int n_chunks, const void *const *host_q8, void *cache_q8, void *stream);
+
 const char *a3_strerror(a3_status status);
 /* Text of the last error raised on the calling thread ("" if none). */
 const char *a3_last_error(void);

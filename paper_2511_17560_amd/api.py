@@ -24,7 +24,8 @@ EXPORTS = ["a3_workspace_bytes", "a3_layout_prepare", "a3_rope_realign", "a3_que
            "a3_selected_qkv_proj", "a3_selected_qkv_proj_scatter", "a3_kv_scatter", "a3_fused_attention", "a3_attention_plan", "a3_fused_attention_planned", "a3_active_rows",
            "a3_block_tail_ws_bytes", "a3_block_tail", "a3_rms_norm", "a3_question_scores_causal", "a3_window_votes",
            "a3_evict_ws_bytes", "a3_evict_select", "a3_evict_compact", "a3_value_deviation_scores",
-           "a3_select_chunk_edges", "a3_chunk_cache_load", "a3_strerror", "a3_last_error", "a3_version"]
+           "a3_select_chunk_edges", "a3_chunk_cache_load", "a3_rope_realign_q8", "a3_q8_row_bytes", "a3_quantize_q8",
+           "a3_chunk_cache_load_q8", "a3_strerror", "a3_last_error", "a3_version"]
 
 
 class A3Error(RuntimeError):
@@ -97,6 +98,13 @@ def lib() -> C.CDLL:
     L.a3_chunk_cache_load.argtypes = [P, C.POINTER(C.c_int), C.POINTER(C.c_int), I, C.POINTER(C.c_void_p),
                                       C.POINTER(C.c_void_p), V, V, V]
     L.a3_chunk_cache_load.restype = I
+    L.a3_q8_row_bytes.argtypes = [P]
+    L.a3_q8_row_bytes.restype = C.c_size_t
+    L.a3_quantize_q8.argtypes = [P, V, V, V, V]
+    L.a3_rope_realign_q8.argtypes = [P, V, V, V, V]
+    L.a3_chunk_cache_load_q8.argtypes = [P, C.POINTER(C.c_int), C.POINTER(C.c_int), I, C.POINTER(C.c_void_p), V, V]
+    for name in ("a3_quantize_q8", "a3_rope_realign_q8", "a3_chunk_cache_load_q8"):
+        getattr(L, name).restype = I
     L.a3_select_chunk_edges.restype = I
     for name in ("a3_question_scores_causal", "a3_window_votes", "a3_evict_select", "a3_evict_compact"):
         getattr(L, name).restype = I
@@ -362,3 +370,28 @@ def a3_fused_attention_planned(layout: Layout, q_act: torch.Tensor, act_idx: tor
     _check(lib().a3_fused_attention_planned(layout.ref, _ptr(q_act), _ptr(act_idx), int(n_act), _ptr(k_fused),
                                             _ptr(v_fused), _ptr(out), _ptr(ws), ws.numel() if ws is not None else 0,
                                             _stream(stream)), "a3_fused_attention_planned")
+
+
+def a3_q8_row_bytes(layout: Layout) -> int:
+    return int(lib().a3_q8_row_bytes(layout.ref))
+
+
+def a3_quantize_q8(layout: Layout, k: torch.Tensor, v: torch.Tensor, cache_q8: torch.Tensor, stream=None) -> None:
+    _check(lib().a3_quantize_q8(layout.ref, _ptr(k), _ptr(v), _ptr(cache_q8), _stream(stream)), "a3_quantize_q8")
+
+
+def a3_rope_realign_q8(layout: Layout, cache_q8: torch.Tensor, k_fused: Optional[torch.Tensor],
+                       v_fused: Optional[torch.Tensor], stream=None) -> None:
+    _check(lib().a3_rope_realign_q8(layout.ref, _ptr(cache_q8), _ptr(k_fused), _ptr(v_fused), _stream(stream)),
+           "a3_rope_realign_q8")
+
+
+def a3_chunk_cache_load_q8(layout: Layout, chunk_start, chunk_len, host_q8, cache_q8: torch.Tensor, stream=None) -> None:
+    n = len(chunk_start)
+    starts = (C.c_int * n)(*[int(x) for x in chunk_start])
+    lens = (C.c_int * n)(*[int(x) for x in chunk_len])
+    for t in host_q8:
+        assert t is None or (t.device.type == "cpu" and t.is_contiguous())
+    blocks = (C.c_void_p * n)(*[t.data_ptr() if t is not None else None for t in host_q8])
+    _check(lib().a3_chunk_cache_load_q8(layout.ref, starts, lens, n, blocks, _ptr(cache_q8), _stream(stream)),
+           "a3_chunk_cache_load_q8")

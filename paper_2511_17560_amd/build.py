@@ -16,7 +16,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liba3.so")
 
-SOURCES = ["a3_host.hip", "a3_stream.hip", "a3_topk.hip", "a3_scores.hip", "a3_proj.hip", "a3_attn.hip", "a3_block.hip"]
+SOURCES = ["a3_host.hip", "a3_stream.hip", "a3_topk.hip", "a3_scores.hip", "a3_proj.hip", "a3_attn.hip", "a3_block.hip", "a3_q8.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",

@@ -16,19 +16,28 @@ from . import api
 
 class ChunkCacheStream:
     """host_k[l][c], host_v[l][c]: pinned CPU tensors [chunk_len[c], Hkv, d] of layer l, chunk c
-    (None for layers that use no cache).  ``depth`` device buffer pairs are cycled."""
+    (None for layers that use no cache).  ``depth`` device buffer pairs are cycled.
+    With ``host_v`` None the blocks are 8-bit: host_k[l][c] is a pinned uint8 tensor of chunk_len[c] records of
+    a3_q8_row_bytes (keys and values of the chunk's rows in one block); acquire() then hands out the device
+    records for a3_rope_realign_q8."""
 
-    def __init__(self, layout: api.Layout, shape, chunk_start, chunk_len, host_k: Sequence, host_v: Sequence,
+    def __init__(self, layout: api.Layout, shape, chunk_start, chunk_len, host_k: Sequence, host_v: Sequence = None,
                  depth: int = 2):
         assert depth >= 2
         self.layout, self.depth = layout, depth
         self.chunk_start, self.chunk_len = list(map(int, chunk_start)), list(map(int, chunk_len))
         self.host_k, self.host_v = host_k, host_v
-        dt = api.torch_dtype(layout.dtype)
+        self.q8 = host_v is None
         T = layout.total_tokens
-        mk = lambda: torch.zeros((T, shape.n_kv_heads, shape.head_dim), dtype=dt, device=layout.device)
-        self.k = [mk() for _ in range(depth)]
-        self.v = [mk() for _ in range(depth)]
+        if self.q8:
+            row = api.a3_q8_row_bytes(layout)
+            self.k = [torch.zeros((T, row), dtype=torch.uint8, device=layout.device) for _ in range(depth)]
+            self.v = [None] * depth
+        else:
+            dt = api.torch_dtype(layout.dtype)
+            mk = lambda: torch.zeros((T, shape.n_kv_heads, shape.head_dim), dtype=dt, device=layout.device)
+            self.k = [mk() for _ in range(depth)]
+            self.v = [mk() for _ in range(depth)]
         self.copy_stream = torch.cuda.Stream(device=layout.device)          # default priority
         self.loaded: List = [None] * depth       # event: buffer i holds its layer
         self.free: List = [None] * depth         # event: the consumer of buffer i is done with it
@@ -40,17 +49,22 @@ class ChunkCacheStream:
         i = l % self.depth
         if self.free[i] is not None:
             self.copy_stream.wait_event(self.free[i])
-        api.a3_chunk_cache_load(self.layout, self.chunk_start, self.chunk_len, self.host_k[l], self.host_v[l],
-                                self.k[i], self.v[i], stream=self.copy_stream)
+        if self.q8:
+            api.a3_chunk_cache_load_q8(self.layout, self.chunk_start, self.chunk_len, self.host_k[l], self.k[i],
+                                       stream=self.copy_stream)
+        else:
+            api.a3_chunk_cache_load(self.layout, self.chunk_start, self.chunk_len, self.host_k[l], self.host_v[l],
+                                    self.k[i], self.v[i], stream=self.copy_stream)
         ev = torch.cuda.Event()
         ev.record(self.copy_stream)
         self.loaded[i] = ev
 
     def acquire(self, l: int, stream=None):
-        """(k_cat, v_cat) of layer l; the compute stream waits until the copies have landed."""
+        """(k_cat, v_cat) of layer l, or the layer's 8-bit records; the compute stream waits until the copies
+        have landed."""
         i = l % self.depth
         (stream or torch.cuda.current_stream()).wait_event(self.loaded[i])
-        return self.k[i], self.v[i]
+        return self.k[i] if self.q8 else (self.k[i], self.v[i])
 
     def release(self, l: int, stream=None) -> None:
         """The compute stream is done with layer l's buffers (recorded as an event)."""

@@ -26,7 +26,7 @@ def fuse_stack(layout: api.Layout, shape, layers: Sequence[Dict[str, torch.Tenso
     g_in, g_post, w_gate, w_up, w_down and optionally bq, bk, bv.
     With ``cache_stream`` (a loader.ChunkCacheStream) the caches are not resident: layer l's blocks are copied
     from host memory into a ring of device buffers while the layers before it compute, and ``k_cat`` / ``v_cat``
-    are ignored.
+    are ignored; its blocks may be 8-bit (position recovery and dequantisation then run in one kernel).
     Returns dict(sel_idx, act_idx, n_act, scores, resid, hidden): ``hidden`` [T, h] holds the final-normed
     output at the active rows.  With ``keep`` the per-layer attention outputs and caches are kept too."""
     dev, dt = layout.device, api.torch_dtype(layout.dtype)
@@ -101,14 +101,21 @@ def fuse_stack(layout: api.Layout, shape, layers: Sequence[Dict[str, torch.Tenso
     # ---- layers 2 ..: Eq. 2, Eq. 5 --------------------------------------------------------------------------
     for l in range(2, n_layers):
         lw = layers[l]
-        k_c, v_c = (k_cat[l], v_cat[l]) if cache_stream is None else cache_stream.acquire(l, stream)
-        api.a3_rope_realign(layout, k_c, k_l, stream=stream)
+        if cache_stream is not None and cache_stream.q8:
+            # 8-bit blocks: both caches are expanded into the layer's own buffers and the ring slot is free again
+            api.a3_rope_realign_q8(layout, cache_stream.acquire(l, stream), k_l, v_l, stream=stream)
+            v_c = v_l
+            cache_stream.release(l, stream)
+            cache_stream.prefetch(l + cache_stream.depth)
+        else:
+            k_c, v_c = (k_cat[l], v_cat[l]) if cache_stream is None else cache_stream.acquire(l, stream)
+            api.a3_rope_realign(layout, k_c, k_l, stream=stream)
         api.a3_selected_qkv_proj_scatter(layout, x, act_idx, n_act, lw["wq"], lw["wk"], lw["wv"], q_out=q_act,
                                          k_fused=k_l, v_fused=v_c, stream=stream, **bias(lw))
         api.a3_fused_attention(layout, q_act, act_idx, n_act, k_l, v_c, out, ws_attn, stream=stream)
         if keep:
             kept.append(dict(k=k_l.clone(), v=v_c.clone(), out=out[:n_act].clone()))
-        if cache_stream is not None:
+        if cache_stream is not None and not cache_stream.q8:
             cache_stream.release(l, stream)
             cache_stream.prefetch(l + cache_stream.depth)
         tail(l, out, act_idx, n_act)

@@ -15,7 +15,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def _declared_symbols():
     text = open(os.path.join(ROOT, "include", "a3.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(a3_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(a3_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_library_exports_every_declared_symbol():
@@ -175,6 +175,20 @@ def test_bad_arguments_are_rejected_before_launch():
     assert load(past, lens, 2, blocks, blocks, 0x1000, 0x1000, None) == api.A3_ERR_INVALID_ARG       # runs past the last row
     holes = (C.c_void_p * 2)(0x1000, None)
     assert load(starts, lens, 2, holes, blocks, 0x1000, 0x1000, None) == api.A3_ERR_INVALID_ARG
+    # 8-bit caches
+    assert L.a3_q8_row_bytes(p) == 8 * (2 * 128 + 8) and L.a3_q8_row_bytes(None) == 0
+    assert L.a3_rope_realign_q8(p, None, 0x1000, 0x1000, None) == api.A3_ERR_INVALID_ARG
+    assert L.a3_rope_realign_q8(p, 0x1000, None, None, None) == api.A3_ERR_INVALID_ARG              # nothing to write
+    assert L.a3_rope_realign_q8(p, 0x1008, 0x1000, 0x1000, None) == api.A3_ERR_INVALID_ARG
+    assert L.a3_rope_realign_q8(None, 0x1000, 0x1000, 0x1000, None) == api.A3_ERR_INVALID_ARG
+    assert L.a3_quantize_q8(p, 0x1000, 0x1000, None, None) == api.A3_ERR_INVALID_ARG
+    assert L.a3_quantize_q8(p, 0x1000, 0x1004, 0x1000, None) == api.A3_ERR_INVALID_ARG
+    load8 = lambda *a: L.a3_chunk_cache_load_q8(p, *a)
+    assert load8(starts, lens, 0, blocks, 0x1000, None) == api.A3_OK
+    assert load8(starts, lens, 2, None, 0x1000, None) == api.A3_ERR_INVALID_ARG
+    assert load8(starts, lens, 2, blocks, None, None) == api.A3_ERR_INVALID_ARG
+    assert load8(past, lens, 2, blocks, 0x1000, None) == api.A3_ERR_INVALID_ARG
+    assert load8(starts, lens, 2, holes, 0x1000, None) == api.A3_ERR_INVALID_ARG
     f32_d64 = _host_layout(dtype=api.A3_F32, head_dim=64)
     assert L.a3_rope_realign(C.byref(f32_d64), None, None, None) == api.A3_ERR_INVALID_ARG
     bf16_d64 = _host_layout(head_dim=64)
