@@ -188,14 +188,96 @@ scores_bf16_kernel(scores_args a) {
     _Pragma("unroll") for (int ks = 0; ks < kD / 16; ++ks) qf[b][ks] = *reinterpret_cast<const bf16x8 *>(qp_ + ks * 16); \
   }
   if (Mg > 0) { A3_LOAD_Q(min(wave * 64, Mg - 1)) }
+  const bool have_rows = wave * 64 < Mg;                       // this wave has a first group of rows
+  if (PASS == 1) {
+    // max + log2(sum) of this wave's 64 rows, read back as broadcasts below; rows past Mg contribute 0
+    const int m = wave * 64 + lane;
+    float st = INFINITY;                                       // exp2(x - inf) = 0
+    if (m < Mg) st = a.stats[(qrow0 + m / G) * a.Hq + g * G + m % G].x;
+    St[wave * 64 + lane] = st;                                 // same-wave write/read: no barrier needed
+  }
+
+  // The K tile arrives in four quarters of 64 keys.  Every load of the tile is issued up front; the logits
+  // of the wave's first 64 rows against quarter q are formed as soon as that quarter is in LDS, while the
+  // later quarters are still on their way, so the arithmetic runs under the memory time instead of after it.
+  constexpr int kQuarters = 4;
+  constexpr int kKB = kTileKeysMfma / 32;                      // 32-key blocks per tile
+  const int n_kb = min(kKB, (N - i0 + 31) / 32);               // key blocks with at least one real key
+  // fragment read: key 32 kb + l32, piece 2 ks + lhi -> slot (2 ks + lhi) ^ (l32 % 16)
+  const unsigned char *kt = lds_raw + l32 * kKRowBytes;
+  const int kswz = (lhi ^ (l32 & 15)) * 16;
+  float colsum[kKB];
+#pragma unroll
+  for (int kb = 0; kb < kKB; ++kb) colsum[kb] = 0.f;
+  float run_max[2] = {-INFINITY, -INFINITY}, run_sum[2] = {0.f, 0.f};
+
+  // logits of the current 64 rows (fragments in qf) against key block KB, folded into the running row
+  // statistics (pass A) or into the column sums (pass B)
+#define A3_KEY_BLOCK(KB)                                                                                       \
+  {                                                                                                            \
+    f32x16 acc[2];                                                                                             \
+    _Pragma("unroll") for (int b = 0; b < 2; ++b)                                                              \
+      _Pragma("unroll") for (int x = 0; x < 16; ++x) acc[b][x] = 0.f;                                          \
+    _Pragma("unroll") for (int ks = 0; ks < kD / 16; ++ks) {                                                   \
+      const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(kt + (KB) * 32 * kKRowBytes + ((32 * ks) ^ kswz));   \
+      _Pragma("unroll") for (int b = 0; b < 2; ++b) {                                                          \
+        if (PASS == 0) acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[b][ks], acc[b], 0, 0, 0); /* C[key][row] */ \
+        else           acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[b][ks], kf, acc[b], 0, 0, 0); /* C[row][key] */ \
+      }                                                                                                        \
+    }                                                                                                          \
+    if (PASS == 0) {                                                                                           \
+      /* lane: row (column l32 of block b); registers: keys i0 + 32 kb + 8(x/4) + 4 lhi + x%4 */               \
+      const bool tail = i0 + 32 * (KB) + 31 >= N;                                                              \
+      _Pragma("unroll") for (int b = 0; b < 2; ++b) {                                                          \
+        if (tail) {                                                                                            \
+          /* (the empty statement keeps the 16 comparisons of each of the unrolled blocks here: gathered at */ \
+          /* the top of the kernel their lane masks do not fit the scalar registers)                        */ \
+          int n_real = N - i0 - 32 * (KB) - 4 * lhi;                                                           \
+          asm volatile("" : "+v"(n_real));                                                                     \
+          _Pragma("unroll") for (int x = 0; x < 16; ++x)                                                       \
+            if (8 * (x >> 2) + (x & 3) >= n_real) acc[b][x] = -INFINITY;                                       \
+        }                                                                                                      \
+        float mx = acc[b][0];                                                                                  \
+        _Pragma("unroll") for (int x = 1; x < 16; ++x) mx = fmaxf(mx, acc[b][x]);                              \
+        mx = halves_max(mx) * a.scale2;                        /* block 0 of a tile always has a real key */   \
+        const float new_max = fmaxf(run_max[b], mx);                                                           \
+        float sum = 0.f;                                                                                       \
+        _Pragma("unroll") for (int x = 0; x < 16; ++x) sum += fast_exp2(fmaf(acc[b][x], a.scale2, -new_max));  \
+        run_sum[b] = run_sum[b] * fast_exp2(run_max[b] - new_max) + sum;   /* per lane half */                 \
+        run_max[b] = new_max;                                                                                  \
+      }                                                                                                        \
+    } else {                                                                                                   \
+      /* lane: key l32 of block kb; registers: rows 8(x/4) + 4 lhi + x%4 of row block b */                     \
+      float part = 0.f;                                                                                        \
+      _Pragma("unroll") for (int b = 0; b < 2; ++b)                                                            \
+        _Pragma("unroll") for (int x = 0; x < 16; ++x) {                                                       \
+          const float st = St[wave * 64 + b * 32 + 8 * (x >> 2) + 4 * lhi + (x & 3)];                          \
+          part += fast_exp2(fmaf(acc[b][x], a.scale2, -st));                                                   \
+        }                                                                                                      \
+      colsum[KB] += part;                                                                                      \
+    }                                                                                                          \
+  }
+  // the 64 rows are done: pass A leaves their (max, sum) over this tile
+#define A3_ROWS_DONE(RB0)                                                                                      \
+  if (PASS == 0) {                                                                                             \
+    _Pragma("unroll") for (int b = 0; b < 2; ++b) {                                                            \
+      const float z = halves_sum(run_sum[b]);                                                                  \
+      if (lhi == 0 && (RB0) + b * 32 + l32 < Mg)                                                               \
+        a.part[(size_t)blockIdx.x * a.total_rows + row_id[b]] = make_float2(run_max[b], z);                    \
+    }                                                                                                          \
+  }
 
   // ---- K tile: 256 keys x 128 dims of head g, global memory -> LDS directly (16 bytes per lane, lane i
   // lands at base + 16 i).  One wave instruction brings 4 keys x 256 B; instruction j of wave w covers
-  // keys 4 (4 j + w) .. +3.  The lane fetches piece (slot ^ key % 16) of its key, so LDS slot s of key
-  // r holds piece s ^ (r % 16) and the 16 keys a quarter wave reads at one piece index touch all 64
-  // banks once.  Inline assembly: the compiler then does not track these as LDS writes (it would
-  // wait for all of them before every LDS read); the explicit wait below covers them.
+  // keys 4 (4 j + w) .. +3, so the instructions 4 q .. 4 q + 3 of the four waves bring quarter q.  The lane
+  // fetches piece (slot ^ key % 16) of its key, so LDS slot s of key r holds piece s ^ (r % 16) and the 16
+  // keys a quarter wave reads at one piece index touch all 64 banks once.  Inline assembly: the compiler
+  // then does not track these as LDS writes (it would wait for all of them before every LDS read); the
+  // explicit waits below cover them.
   if (!REALIGN) {
+    // The compiler's own wait for the Q fragments and the row statistics would, counted by the hardware, also
+    // wait for everything issued before them; they are therefore awaited first, then the tile is requested.
+    __builtin_amdgcn_s_waitcnt(0);
     const int drow = 4 * wave + (lane >> 4);                   // key of the lane in instruction 0
     const int dpiece = (lane & 15) ^ (drow & 15);              // (4 (4 j + w) + lane/16) % 16 does not depend on j
     const uint32_t lds_k = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds_raw;
@@ -206,6 +288,20 @@ scores_bf16_kernel(scores_args a) {
       asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
                    :: "s"(__builtin_amdgcn_readfirstlane(lds_k + 4 * (4 * j + wave) * kKRowBytes)), "v"(gp) : "memory");
     }
+    // at most the 4 (3 - QT) younger instructions of this wave are still in flight: its part of quarter QT
+    // has landed; after the barrier everybody's has.  (vmcnt in bits 3:0 and 15:14, the other counters open.)
+#define A3_QUARTER(QT)                                                                                         \
+    __builtin_amdgcn_s_waitcnt((4 * (kQuarters - 1 - (QT))) | (7 << 4) | (15 << 8));                           \
+    __builtin_amdgcn_s_barrier();                                                                              \
+    if (have_rows) {                                                                                           \
+      if (2 * (QT) < n_kb) A3_KEY_BLOCK(2 * (QT))                                                              \
+      if (2 * (QT) + 1 < n_kb) A3_KEY_BLOCK(2 * (QT) + 1)                                                      \
+    }
+    A3_QUARTER(0)
+    A3_QUARTER(1)
+    A3_QUARTER(2)
+    A3_QUARTER(3)
+#undef A3_QUARTER
   } else {
     // Position recovery (Eq. 2) on the way in: the tile comes from the stale cache through registers,
     // every pair is turned by its chunk's offset, and the rounded result goes both to the realigned cache
@@ -213,7 +309,7 @@ scores_bf16_kernel(scores_args a) {
     // a key: in either pairing (adjacent coordinates, or i with i + 64) it then holds whole pairs.
     const bf16_t *Kc = (const bf16_t *)a.k_cat;               // may be the same buffer as k_out
     bf16_t *Ko = (bf16_t *)a.k_out;
-    const int c = tid & 7, kr0 = tid >> 3;                     // 32 keys per round, 8 rounds
+    const int c = tid & 7, kr0 = tid >> 3;                     // 32 keys per round, 8 rounds: 2 per quarter
     constexpr int kRounds = kTileKeysMfma / 32;
     // all loads of the stale keys and of their chunk numbers are issued before the first rotation
     bf16x8 lo[kRounds], hi[kRounds];
@@ -272,88 +368,36 @@ scores_bf16_kernel(scores_args a) {
       unsigned char *ld = lds_raw + key * kKRowBytes;
       *reinterpret_cast<bf16x8 *>(ld + ((c ^ (key & 15)) * 16)) = rlo;
       *reinterpret_cast<bf16x8 *>(ld + (((c + 8) ^ (key & 15)) * 16)) = rhi;
+      if (j & 1) {
+        // quarter j / 2 is in LDS once everybody's two rounds are written (this wave's writes first: the
+        // LDS counter only; a full fence would also wait for the keys still on their way)
+        __builtin_amdgcn_s_waitcnt(15 | (3 << 14) | (7 << 4) | (0 << 8));
+        __builtin_amdgcn_s_barrier();
+        if (have_rows) {
+          if (j - 1 < n_kb) A3_KEY_BLOCK(j - 1)
+          if (j < n_kb) A3_KEY_BLOCK(j)
+        }
+      }
     }
   }
-  __builtin_amdgcn_s_waitcnt(0);                               // Q fragments and this wave's part of the tile
-  __syncthreads();
-  constexpr int kKB = kTileKeysMfma / 32;                      // 32-key blocks per tile
-  const int n_kb = min(kKB, (N - i0 + 31) / 32);                 // key blocks with at least one real key
-  // fragment read: key 32 kb + l32, piece 2 ks + lhi -> slot (2 ks + lhi) ^ (l32 % 16)
-  const unsigned char *kt = lds_raw + l32 * kKRowBytes;
-  const int kswz = (lhi ^ (l32 & 15)) * 16;
+  if (have_rows) { A3_ROWS_DONE(wave * 64) }
 
-  float colsum[kKB];
-#pragma unroll
-  for (int kb = 0; kb < kKB; ++kb) colsum[kb] = 0.f;
-
-  for (int rb0 = wave * 64; rb0 < Mg; rb0 += 256) {            // this wave's rows rb0 .. rb0+63
-    if (rb0 != wave * 64) { A3_LOAD_Q(rb0) }
+  // ---- the wave's further rows (more than 256 rows per KV head): the whole tile is in LDS by now --------------
+  for (int rb0 = wave * 64 + 256; rb0 < Mg; rb0 += 256) {      // this wave's rows rb0 .. rb0+63
+    A3_LOAD_Q(rb0)
     if (PASS == 1) {
-      // max + log2(sum) of this wave's 64 rows, read back as broadcasts below; rows past Mg contribute 0
       const int m = rb0 + lane;
-      float st = INFINITY;                                     // exp2(x - inf) = 0
+      float st = INFINITY;
       if (m < Mg) st = a.stats[(qrow0 + m / G) * a.Hq + g * G + m % G].x;
-      St[wave * 64 + lane] = st;                               // same-wave write/read: no barrier needed
+      St[wave * 64 + lane] = st;
     }
-    float run_max[2] = {-INFINITY, -INFINITY}, run_sum[2] = {0.f, 0.f};
-    for (int kb = 0; kb < n_kb; ++kb) {
-      f32x16 acc[2];
-#pragma unroll
-      for (int b = 0; b < 2; ++b)
-#pragma unroll
-        for (int x = 0; x < 16; ++x) acc[b][x] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < kD / 16; ++ks) {
-        const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(kt + kb * 32 * kKRowBytes + ((32 * ks) ^ kswz));
-#pragma unroll
-        for (int b = 0; b < 2; ++b) {
-          if (PASS == 0) acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[b][ks], acc[b], 0, 0, 0);   // C[key][row]
-          else           acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[b][ks], kf, acc[b], 0, 0, 0);   // C[row][key]
-        }
-      }
-      if (PASS == 0) {
-        // lane: row (column l32 of block b); registers: keys i0 + 32 kb + 8(x/4) + 4 lhi + x%4
-        const bool tail = i0 + 32 * kb + 31 >= N;
-#pragma unroll
-        for (int b = 0; b < 2; ++b) {
-          if (tail) {
-#pragma unroll
-            for (int x = 0; x < 16; ++x)
-              if (i0 + 32 * kb + 8 * (x >> 2) + 4 * lhi + (x & 3) >= N) acc[b][x] = -INFINITY;
-          }
-          float mx = acc[b][0];
-#pragma unroll
-          for (int x = 1; x < 16; ++x) mx = fmaxf(mx, acc[b][x]);
-          mx = halves_max(mx) * a.scale2;                      // block 0 of a tile always has a real key
-          const float new_max = fmaxf(run_max[b], mx);
-          float sum = 0.f;
-#pragma unroll
-          for (int x = 0; x < 16; ++x) sum += fast_exp2(fmaf(acc[b][x], a.scale2, -new_max));
-          run_sum[b] = run_sum[b] * fast_exp2(run_max[b] - new_max) + sum;   // per lane half
-          run_max[b] = new_max;
-        }
-      } else {
-        // lane: key l32 of block kb; registers: rows 8(x/4) + 4 lhi + x%4 of row block b
-        float part = 0.f;
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-          for (int x = 0; x < 16; ++x) {
-            const float st = St[wave * 64 + b * 32 + 8 * (x >> 2) + 4 * lhi + (x & 3)];
-            part += fast_exp2(fmaf(acc[b][x], a.scale2, -st));
-          }
-        colsum[kb] += part;
-      }
-    }
-    if (PASS == 0) {
-#pragma unroll
-      for (int b = 0; b < 2; ++b) {
-        const float z = halves_sum(run_sum[b]);
-        if (lhi == 0 && rb0 + b * 32 + l32 < Mg)
-          a.part[(size_t)blockIdx.x * a.total_rows + row_id[b]] = make_float2(run_max[b], z);
-      }
-    }
+    run_max[0] = run_max[1] = -INFINITY;
+    run_sum[0] = run_sum[1] = 0.f;
+    for (int kb = 0; kb < n_kb; ++kb) A3_KEY_BLOCK(kb)
+    A3_ROWS_DONE(rb0)
   }
+#undef A3_KEY_BLOCK
+#undef A3_ROWS_DONE
 #undef A3_LOAD_Q
   if (PASS == 1) {
 #pragma unroll
