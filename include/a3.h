@@ -172,7 +172,9 @@ a3_status a3_fused_attention(const a3_layout *layout, const void *q_act, const i
  * on the list of active rows, so it can be laid out as soon as that list exists: a3_attention_plan writes the
  * layout into ws (one small kernel), a3_fused_attention_planned then attends with it.  Between the two calls
  * nothing else may write ws; the arguments they share must be the same; stream order (or an event) must put the
- * plan first.  Together they give what a3_fused_attention gives, bit for bit. */
+ * plan first.  Together they give what a3_fused_attention gives, bit for bit.  a3_fused_attention_planned leaves
+ * the plan as it is: further calls with the same act_idx and ws (the layers of a stack whose active rows stay the
+ * same) may reuse it. */
 a3_status a3_attention_plan(const a3_layout *layout, const int *act_idx, int n_act, void *ws, size_t ws_bytes,
                             void *stream);
 a3_status a3_fused_attention_planned(const a3_layout *layout, const void *q_act, const int *act_idx, int n_act,

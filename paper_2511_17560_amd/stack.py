@@ -93,7 +93,9 @@ def fuse_stack(layout: api.Layout, shape, layers: Sequence[Dict[str, torch.Tenso
     api.a3_active_rows(layout, sel_idx, sel_start_d, n_act, act_idx, stream=stream)
     api.a3_selected_qkv_proj(layout, x, act_idx, n_act, lw["wq"], None, None, bq=lw.get("bq"), q_out=q_act,
                              stream=stream)
-    api.a3_fused_attention(layout, q_act, act_idx, n_act, k_l, v_l, out, ws_attn, stream=stream)
+    # the rows [Re, Q] stay the same from here on: their attention work is laid out once and reused by every layer
+    api.a3_attention_plan(layout, act_idx, n_act, ws_attn, stream=stream)
+    api.a3_fused_attention_planned(layout, q_act, act_idx, n_act, k_l, v_l, out, ws_attn, stream=stream)
     tail(1, out, act_idx, n_act)
     if keep:
         kept.append(dict(k=k_l.clone(), v=v_l.clone(), out=out[:n_act].clone()))
@@ -112,7 +114,7 @@ def fuse_stack(layout: api.Layout, shape, layers: Sequence[Dict[str, torch.Tenso
             api.a3_rope_realign(layout, k_c, k_l, stream=stream)
         api.a3_selected_qkv_proj_scatter(layout, x, act_idx, n_act, lw["wq"], lw["wk"], lw["wv"], q_out=q_act,
                                          k_fused=k_l, v_fused=v_c, stream=stream, **bias(lw))
-        api.a3_fused_attention(layout, q_act, act_idx, n_act, k_l, v_c, out, ws_attn, stream=stream)
+        api.a3_fused_attention_planned(layout, q_act, act_idx, n_act, k_l, v_c, out, ws_attn, stream=stream)
         if keep:
             kept.append(dict(k=k_l.clone(), v=v_c.clone(), out=out[:n_act].clone()))
         if cache_stream is not None and not cache_stream.q8:
