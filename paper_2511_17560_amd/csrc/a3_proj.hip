@@ -35,6 +35,8 @@ constexpr int kRowBytes = kBK * 2;   // an LDS row is one 64-byte k-slab of a we
 // that two workgroups share a CU and cover each other's barriers; the larger tiles run alone with 4.
 constexpr int proj_stages(int tb) { return tb == 2 ? 3 : 4; }
 constexpr size_t proj_lds_bytes(int tb) { return (size_t)proj_stages(tb) * (2 * kHeadDim + 64 * tb) * kRowBytes; }
+// the variant with 128-byte row pieces: 3 weight stages and 2 stages of hidden rows
+constexpr size_t proj_lds_bytes_k64(int tb) { return (size_t)3 * 256 * 128 + (size_t)2 * 64 * tb * 128; }
 
 struct proj_args {
   const bf16_t *hidden;
@@ -64,7 +66,7 @@ __device__ __forceinline__ head_sel select_head(int h, int Hq, int Hkv) {
 // nothing else (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8)
 constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
 
-template <int TB>
+template <int TB, bool K64>
 __global__ void __launch_bounds__(256, TB == 2 ? 2 : 1)
 proj_bf16_kernel(proj_args a) {
   constexpr int kTokTile = 64 * TB;
@@ -90,6 +92,31 @@ proj_bf16_kernel(proj_args a) {
   const int l32 = lane & 31, lhi = lane >> 5;
   const int fh = wave & 1, th = wave >> 1;
 
+  // ---- this wave's head and rows ---------------------------------------------------------------------
+  const int my_head = 2 * hp + fh;
+  const head_sel hs = select_head(min(my_head, n_heads - 1), a.Hq, a.Hkv);
+  bf16_t *__restrict__ out = my_head < n_heads ? a.out[hs.which] : nullptr;
+  const bool compute = out != nullptr;
+  const int tok0 = tt * kTokTile + th * 32 * TB;
+
+  f32x16 acc[4][TB];
+#pragma unroll
+  for (int fb = 0; fb < 4; ++fb)
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[fb][tb][r] = 0.f;
+
+  // global_load_lds: lane i's 16 bytes land at (M0 = wave-uniform LDS byte address) + 16 i.  Issued as
+  // inline assembly on purpose: the compiler then neither tracks these as LDS writes (it would put
+  // a full vmcnt(0) in front of every LDS read and undo the lookahead) nor reorders memory accesses
+  // across them; the waits for them are the explicit s_waitcnt below.  M0 is not used by anything
+  // else in this kernel (LDS instructions need no M0 on gfx9 and later).
+  const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds;
+#define A3_DMA(GPTR, LDS_OFF)                                                                                 \
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"                                          \
+               :: "s"(__builtin_amdgcn_readfirstlane(lds_base + (uint32_t)(LDS_OFF))), "v"(GPTR) : "memory")
+  if constexpr (!K64) {
   // ---- loading roles.  One wave instruction brings 16 rows x 64 B: lane -> (row lane/4, slot lane%4),
   // and the lane fetches the 16-byte piece (slot ^ swz(row)) of its row, so that LDS slot s of row r
   // holds piece s ^ swz(r), swz(r) = (r/4) % 4: the 16 consecutive rows that one quarter of a wave
@@ -115,15 +142,6 @@ proj_bf16_kernel(proj_args a) {
     const int src_row = a.row_idx ? a.row_idx[m] : m;
     xsrc[j] = reinterpret_cast<const char *>(a.hidden + (size_t)src_row * a.K + piece * 8);
   }
-  // global_load_lds: lane i's 16 bytes land at (M0 = wave-uniform LDS byte address) + 16 i.  Issued as
-  // inline assembly on purpose: the compiler then neither tracks these as LDS writes (it would put
-  // a full vmcnt(0) in front of every LDS read and undo the lookahead) nor reorders memory accesses
-  // across them; the waits for them are the explicit s_waitcnt below.  M0 is not used by anything
-  // else in this kernel (LDS instructions need no M0 on gfx9 and later).
-  const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds;
-#define A3_DMA(GPTR, LDS_OFF)                                                                                 \
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"                                          \
-               :: "s"(__builtin_amdgcn_readfirstlane(lds_base + (uint32_t)(LDS_OFF))), "v"(GPTR) : "memory")
 #define A3_ISSUE(STAGE, K0)                                                                                   \
   {                                                                                                           \
     const uint32_t st_ = (STAGE) * kStageBytes;                                                               \
@@ -133,25 +151,10 @@ proj_bf16_kernel(proj_args a) {
       A3_DMA(xsrc[j] + kb_, st_ + kWBytes + 16 * (4 * j + wave) * kRowBytes);                                 \
   }
 
-  // ---- this wave's head and rows ---------------------------------------------------------------------
-  const int my_head = 2 * hp + fh;
-  const head_sel hs = select_head(min(my_head, n_heads - 1), a.Hq, a.Hkv);
-  bf16_t *__restrict__ out = my_head < n_heads ? a.out[hs.which] : nullptr;
-  const bool compute = out != nullptr;
-  const int tok0 = tt * kTokTile + th * 32 * TB;
   // fragment addresses: row base + swizzled slot of piece 2 ks + lhi
   const int swz = (l32 >> 2) & 3;
   const int frag_w = (fh * kHeadDim + l32) * kRowBytes, frag_x = kWBytes + (th * 32 * TB + l32) * kRowBytes;
   const int slot_k0 = ((lhi) ^ swz) * 16, slot_k1 = ((2 + lhi) ^ swz) * 16;
-
-  f32x16 acc[4][TB];
-#pragma unroll
-  for (int fb = 0; fb < 4; ++fb)
-#pragma unroll
-    for (int tb = 0; tb < TB; ++tb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[fb][tb][r] = 0.f;
-
 #define A3_FRAGS(WF, XF, ST, SLOT)                                                                           \
   {                                                                                                          \
     _Pragma("unroll") for (int tb = 0; tb < TB; ++tb)                                                        \
@@ -230,10 +233,105 @@ proj_bf16_kernel(proj_args a) {
 #undef A3_FENCE
 #undef A3_FRAG1
   __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));                   // drain the tail loads before LDS is released
-#undef A3_DMA
 #undef A3_ISSUE
 #undef A3_FRAGS
 #undef A3_MFMAS
+  } else {
+    // ---- 128-byte row pieces: a slab is 64 elements of the reduction dimension ------------------------------
+    // The L1 path moves a wave instruction of 8 rows x 128 B (whole cache lines) a third faster than one of
+    // 16 rows x 64 B (half lines), and at these tile sizes that path, not the matrix pipe, sets the pace of
+    // the loop.  LDS: a ring of 3 weight stages [256 rows][128 B] and a ring of 2 stages of hidden rows
+    // [64 TB rows][128 B]; the weights, which come from HBM the first time an XCD asks for them, are
+    // requested two slabs ahead, the hidden rows (shared by all head pairs, L2 hits) one slab ahead.
+    // LDS slot s of row r holds piece s ^ ((r >> 1) & 7): the 16 consecutive rows a quarter wave reads at one
+    // piece index then touch all 64 banks once.
+    constexpr int kRowB = 128, kWStage = 256 * kRowB, kXStage = kTokTile * kRowB, kXBase = 3 * kWStage;
+    constexpr int kLW = 8, kLX = 2 * TB;                       // direct-to-LDS loads per wave and slab
+    const int row8 = lane >> 3, slot8 = lane & 7;
+    const int piece8 = slot8 ^ ((4 * (wave & 1) + (row8 >> 1)) & 7);   // rows 8 (4 j + wave) + row8: (row >> 1) & 7
+    const char *wsrc[kLW];
+#pragma unroll
+    for (int j = 0; j < kLW; ++j) {
+      const int row = 8 * (4 * j + wave) + row8;               // 0..255
+      const head_sel hsl = select_head(min(2 * hp + (row >> 7), n_heads - 1), a.Hq, a.Hkv);
+      const bf16_t *wb = a.w[hsl.which];
+      int hh = hsl.head;
+      if (wb == nullptr) { wb = a.w[0] ? a.w[0] : (a.w[1] ? a.w[1] : a.w[2]); hh = 0; }   // unused head: any valid tile
+      wsrc[j] = reinterpret_cast<const char *>(wb + ((size_t)hh * kHeadDim + (row & 127)) * a.K + piece8 * 8);
+    }
+    const char *xsrc[kLX];
+#pragma unroll
+    for (int j = 0; j < kLX; ++j) {
+      const int row = 8 * (4 * j + wave) + row8;               // 0..64 TB - 1
+      const int m = min(tt * kTokTile + row, a.n_rows - 1);    // clamp: computed but never stored
+      const int src_row = a.row_idx ? a.row_idx[m] : m;
+      xsrc[j] = reinterpret_cast<const char *>(a.hidden + (size_t)src_row * a.K + piece8 * 8);
+    }
+    const int n_slabs = a.K / 64;
+#define A3_KB(SLAB) ((size_t)min((SLAB), n_slabs - 1) * 128)     /* byte offset of a slab in a row; past the end: the last one, unused */
+#define A3_W_LOAD(J, WOFF, SLAB) A3_DMA(wsrc[J] + A3_KB(SLAB), (WOFF) + (4 * (J) + wave) * 1024);
+#define A3_X_LOAD(J, XOFF, SLAB) A3_DMA(xsrc[J] + A3_KB(SLAB), (XOFF) + (4 * (J) + wave) * 1024);
+    // fragment addresses: row base + swizzled slot of piece 2 ks + lhi
+    const int swz8 = (l32 >> 1) & 7;
+    const int frag_w = (fh * kHeadDim + l32) * kRowB, frag_x = (th * 32 * TB + l32) * kRowB;
+    int slot[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) slot[ks] = ((2 * ks + lhi) ^ swz8) * 16;
+#define A3_FENCE __builtin_amdgcn_sched_barrier(0);
+    // the I-th fragment read of a k-step: hidden rows first, then the weights
+#define A3_FRAG8(I, WF, XF, WOFF, XOFF, SLOT)                                                                   \
+    if ((I) < TB) XF[(I) < TB ? (I) : 0] = *reinterpret_cast<const bf16x8 *>(lds + (XOFF) + frag_x + ((I) < TB ? (I) : 0) * 32 * kRowB + (SLOT)); \
+    else if ((I) < TB + 4) WF[(I) >= TB && (I) - TB < 4 ? (I) - TB : 0] = *reinterpret_cast<const bf16x8 *>(lds + (WOFF) + frag_w + ((I) >= TB && (I) - TB < 4 ? (I) - TB : 0) * 32 * kRowB + (SLOT));
+    // one k-step: its MFMAs, and behind each of them at most one fragment read and one load
+#define A3_KSTEP(WA, XA, WB, XB, WOFF, XOFF, SLOT, LOADS)                                                       \
+    A3_FENCE                                                                                                    \
+    _Pragma("unroll") for (int i = 0; i < 4 * TB; ++i) {                                                        \
+      const int fb = i / TB, tb = i % TB;                                                                       \
+      acc[fb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(WA[fb], XA[tb], acc[fb][tb], 0, 0, 0);              \
+      A3_FENCE                                                                                                  \
+      A3_FRAG8(i, WB, XB, WOFF, XOFF, SLOT)                                                                     \
+      LOADS                                                                                                     \
+      A3_FENCE                                                                                                  \
+    }
+    // request order: W(0) X(0) W(1) X(1), then per slab sl: W(sl+2) under its first k-step and X(sl+2) under
+    // its last one, so that at the barrier of slab sl only the 8 loads of W(sl+2) may still be on their way
+    int w_cur = 0, w_nxt = kWStage, w_nn = 2 * kWStage;        // weight stages of slabs sl, sl + 1, sl + 2
+    int x_cur = kXBase, x_nxt = kXBase + kXStage;
+#pragma unroll
+    for (int j = 0; j < kLW; ++j) A3_W_LOAD(j, w_cur, 0)
+#pragma unroll
+    for (int j = 0; j < kLX; ++j) A3_X_LOAD(j, x_cur, 0)
+#pragma unroll
+    for (int j = 0; j < kLW; ++j) A3_W_LOAD(j, w_nxt, 1)
+#pragma unroll
+    for (int j = 0; j < kLX; ++j) A3_X_LOAD(j, x_nxt, 1)
+    bf16x8 wf0[4], xf0[TB], wf1[4], xf1[TB];
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(kLW + kLX));          // this wave's loads of slab 0 have landed
+    __builtin_amdgcn_s_barrier();                              // ... and everybody's
+#pragma unroll
+    for (int i = 0; i < TB + 4; ++i) { A3_FRAG8(i, wf0, xf0, w_cur, x_cur, slot[0]) }
+    for (int sl = 0; sl < n_slabs; ++sl) {
+      A3_KSTEP(wf0, xf0, wf1, xf1, w_cur, x_cur, slot[1], if (i < kLW) A3_W_LOAD(i, w_nn, sl + 2))
+      A3_KSTEP(wf1, xf1, wf0, xf0, w_cur, x_cur, slot[2], )
+      A3_KSTEP(wf0, xf0, wf1, xf1, w_cur, x_cur, slot[3], )
+      // Slab sl + 1 is complete once only the 8 youngest loads (W(sl+2)) are outstanding; the barrier also says
+      // that every wave has fetched its last fragments of slab sl (LDS counter at zero first), whose stage of
+      // hidden rows the loads issued next overwrite (and whose weight stage W(sl+3) will).
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm(kLW) & ~(15 << 8));
+      __builtin_amdgcn_s_barrier();
+      A3_KSTEP(wf1, xf1, wf0, xf0, w_nxt, x_nxt, slot[0], if (i < kLX) A3_X_LOAD(i, x_cur, sl + 2))
+      { const int t = w_cur; w_cur = w_nxt; w_nxt = w_nn; w_nn = t; }
+      { const int t = x_cur; x_cur = x_nxt; x_nxt = t; }
+    }
+#undef A3_KSTEP
+#undef A3_FRAG8
+#undef A3_FENCE
+#undef A3_W_LOAD
+#undef A3_X_LOAD
+#undef A3_KB
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));                  // drain the tail loads before LDS is released
+  }
+#undef A3_DMA
   // ---- epilogue: bias, RoPE, one rounding, store -------------------------------------------------------
   // In the accumulators a lane holds one row and, per register quad, 4 consecutive features: stored
   // from there, every instruction would touch 64 different cache lines, and the (cos, sin) reads
@@ -745,18 +843,25 @@ static a3_status proj_launch(const a3_layout *L, const void *hidden, const int *
     if (ntw < 2 || ntw > 4) ntw = 2;
     a.n_tok_tiles = (n_rows + 64 * ntw - 1) / (64 * ntw);
     const unsigned grid = 8u * (unsigned)((a.n_pairs + 7) / 8) * (unsigned)a.n_tok_tiles;
+    // 128-byte row pieces for the 192- and 256-row tiles when the hidden size allows (tuning override A3_PROJ_K64)
+    bool k64 = ntw >= 3 && L->hidden % 64 == 0;
+    if (const char *e = getenv("A3_PROJ_K64")) k64 = k64 && atoi(e) != 0;
     static bool attr_done = false;
     if (!attr_done) {
-      hipError_t e1 = hipFuncSetAttribute((const void *)proj_bf16_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)proj_lds_bytes(2));
-      hipError_t e2 = hipFuncSetAttribute((const void *)proj_bf16_kernel<3>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)proj_lds_bytes(3));
-      hipError_t e3 = hipFuncSetAttribute((const void *)proj_bf16_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)proj_lds_bytes(4));
-      if (e1 != hipSuccess || e2 != hipSuccess || e3 != hipSuccess)
+      hipError_t e1 = hipFuncSetAttribute((const void *)proj_bf16_kernel<2, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)proj_lds_bytes(2));
+      hipError_t e2 = hipFuncSetAttribute((const void *)proj_bf16_kernel<3, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)proj_lds_bytes(3));
+      hipError_t e3 = hipFuncSetAttribute((const void *)proj_bf16_kernel<4, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)proj_lds_bytes(4));
+      hipError_t e4 = hipFuncSetAttribute((const void *)proj_bf16_kernel<3, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)proj_lds_bytes_k64(3));
+      hipError_t e5 = hipFuncSetAttribute((const void *)proj_bf16_kernel<4, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)proj_lds_bytes_k64(4));
+      if (e1 != hipSuccess || e2 != hipSuccess || e3 != hipSuccess || e4 != hipSuccess || e5 != hipSuccess)
         return a3_fail(A3_ERR_HIP, "a3_selected_qkv_proj: cannot raise the dynamic LDS limit");
       attr_done = true;
     }
-    if (ntw == 2) hipLaunchKernelGGL(proj_bf16_kernel<2>, dim3(grid), dim3(256), proj_lds_bytes(2), st, a);
-    else if (ntw == 3) hipLaunchKernelGGL(proj_bf16_kernel<3>, dim3(grid), dim3(256), proj_lds_bytes(3), st, a);
-    else hipLaunchKernelGGL(proj_bf16_kernel<4>, dim3(grid), dim3(256), proj_lds_bytes(4), st, a);
+    if (ntw == 2) hipLaunchKernelGGL((proj_bf16_kernel<2, false>), dim3(grid), dim3(256), proj_lds_bytes(2), st, a);
+    else if (ntw == 3 && k64) hipLaunchKernelGGL((proj_bf16_kernel<3, true>), dim3(grid), dim3(256), proj_lds_bytes_k64(3), st, a);
+    else if (ntw == 3) hipLaunchKernelGGL((proj_bf16_kernel<3, false>), dim3(grid), dim3(256), proj_lds_bytes(3), st, a);
+    else if (k64) hipLaunchKernelGGL((proj_bf16_kernel<4, true>), dim3(grid), dim3(256), proj_lds_bytes_k64(4), st, a);
+    else hipLaunchKernelGGL((proj_bf16_kernel<4, false>), dim3(grid), dim3(256), proj_lds_bytes(4), st, a);
   } else {
     proj_args_f32 a;
     a.hidden = (const float *)hidden; a.row_idx = row_idx; a.n_rows = n_rows;
