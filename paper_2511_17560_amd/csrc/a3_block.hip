@@ -79,7 +79,7 @@ struct gemm_args {
 constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
 
 template <int TB, int EPI, bool K64>
-__global__ void __launch_bounds__(256, TB == 2 ? 2 : 1)
+__global__ void __launch_bounds__(256, (TB == 2 && !K64) ? 2 : 1)
 gemm_bf16_kernel(gemm_args a) {
   constexpr int kTokTile = 64 * TB;
   constexpr int kStages = gemm_stages(TB);
@@ -460,10 +460,11 @@ template <int EPI>
 a3_status gemm_bf16_launch(const gemm_args &a0, hipStream_t st, const char *who) {
   gemm_args a = a0;
   a.n_ftiles = EPI == EPI_RESID ? (a.N + 255) / 256 : (a.N + 127) / 128;
-  const int tb = pick_tb(a.n_rows, a.n_ftiles);
+  int tb = pick_tb(a.n_rows, a.n_ftiles);
+  if (const char *e = getenv("A3_GEMM_TB")) { const int t = atoi(e); if (t >= 2 && t <= 4) tb = t; }   // tuning override
   a.n_tok_tiles = (a.n_rows + 64 * tb - 1) / (64 * tb);
-  // 128-byte row pieces for the 192- and 256-row tiles when K allows (tuning override A3_GEMM_K64)
-  bool k64 = tb >= 3 && a.K % 64 == 0;
+  // 128-byte row pieces whenever K allows (tuning override A3_GEMM_K64=0: the 64-byte loop)
+  bool k64 = a.K % 64 == 0;
   if (const char *e = getenv("A3_GEMM_K64")) k64 = k64 && atoi(e) != 0;
   static bool attr_done = false;
   if (!attr_done) {
@@ -472,12 +473,14 @@ a3_status gemm_bf16_launch(const gemm_args &a0, hipStream_t st, const char *who)
     hipError_t e3 = hipFuncSetAttribute((const void *)gemm_bf16_kernel<4, EPI, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes(4));
     hipError_t e4 = hipFuncSetAttribute((const void *)gemm_bf16_kernel<3, EPI, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes_k64(3));
     hipError_t e5 = hipFuncSetAttribute((const void *)gemm_bf16_kernel<4, EPI, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes_k64(4));
-    if (e1 != hipSuccess || e2 != hipSuccess || e3 != hipSuccess || e4 != hipSuccess || e5 != hipSuccess)
+    hipError_t e6 = hipFuncSetAttribute((const void *)gemm_bf16_kernel<2, EPI, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes_k64(2));
+    if (e1 != hipSuccess || e2 != hipSuccess || e3 != hipSuccess || e4 != hipSuccess || e5 != hipSuccess || e6 != hipSuccess)
       return a3_fail(A3_ERR_HIP, "%s: cannot raise the dynamic LDS limit", who);
     attr_done = true;
   }
   const unsigned grid = 8u * (unsigned)((a.n_ftiles + 7) / 8) * (unsigned)a.n_tok_tiles;
-  if (tb == 2) hipLaunchKernelGGL((gemm_bf16_kernel<2, EPI, false>), dim3(grid), dim3(256), gemm_lds_bytes(2), st, a);
+  if (tb == 2 && k64) hipLaunchKernelGGL((gemm_bf16_kernel<2, EPI, true>), dim3(grid), dim3(256), gemm_lds_bytes_k64(2), st, a);
+  else if (tb == 2) hipLaunchKernelGGL((gemm_bf16_kernel<2, EPI, false>), dim3(grid), dim3(256), gemm_lds_bytes(2), st, a);
   else if (tb == 3 && k64) hipLaunchKernelGGL((gemm_bf16_kernel<3, EPI, true>), dim3(grid), dim3(256), gemm_lds_bytes_k64(3), st, a);
   else if (tb == 3) hipLaunchKernelGGL((gemm_bf16_kernel<3, EPI, false>), dim3(grid), dim3(256), gemm_lds_bytes(3), st, a);
   else if (k64) hipLaunchKernelGGL((gemm_bf16_kernel<4, EPI, true>), dim3(grid), dim3(256), gemm_lds_bytes_k64(4), st, a);
