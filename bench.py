@@ -100,18 +100,24 @@ def cpu_baseline(cfg, max_seconds=60.0):
     from oracle import workload as wl
     from paper_2511_17560_amd import synth
 
-    w = synth.config(cfg, layer=0)
-    t = synth.draw_tensors(w)
-    k_cat, v_cat = synth.draw_cache(w, "k"), synth.draw_cache(w, "v")
-    t0 = time.perf_counter()
-    res = ora.fuse_layer(t.x_cur, k_cat, v_cat, t.wq, t.wk, t.wv, **wl.layout_kwargs(w))
-    dt = time.perf_counter() - t0
+    dt, n_layers, n_sel = 0.0, 0, 0
+    for layer_i in range(3):                     # three of the 32 layers: about 10 s of CPU work
+        w = synth.config(cfg, layer=layer_i)
+        t = synth.draw_tensors(w)
+        k_cat, v_cat = synth.draw_cache(w, "k"), synth.draw_cache(w, "v")
+        t0 = time.perf_counter()
+        res = ora.fuse_layer(t.x_cur, k_cat, v_cat, t.wq, t.wk, t.wv, **wl.layout_kwargs(w))
+        dt += time.perf_counter() - t0
+        n_layers += 1
+        n_sel = int(len(res["sel_idx"]))
+        if dt > max_seconds:
+            break
     threads = max([p.get("num_threads", 1) for p in threadpool_info() if p.get("user_api") == "blas"] + [1])
     return {
-        "value": w.total_ctx / dt, "unit": "fused-context tokens/s/layer", "cores": int(threads), "kind": "oracle",
-        "sample": f"1 of the 32 layers of {w.name} (float64 NumPy oracle, all steps, stale cache drawn directly), "
+        "value": n_layers * w.total_ctx / dt, "unit": "fused-context tokens/s/layer", "cores": int(threads), "kind": "oracle",
+        "sample": f"{n_layers} of the 32 layers of {w.name} (float64 NumPy oracle, all steps, stale cache drawn directly), "
                   f"{dt:.1f} s wall",
-        "seconds": dt, "n_selected": int(len(res["sel_idx"])),
+        "seconds": dt, "n_selected": n_sel,
     }
 
 
