@@ -49,6 +49,11 @@ def _workload(name):
         return synth.config(5)
     if name == "long-bf16":      # visible keys beyond 1.5 x 4096: tiles are cut into key segments and merged
         return synth.custom(SMALL_BF16, [[3000, 2500, 2100]], [40], ratio=(10, 100), n_planted=4, seed=45)
+    if name == "k64-bf16":       # reduction dimension of one 64-element slab, and of two
+        return synth.custom(synth.ModelShape("k64", "bf16", 64, 2, 1, 128, 10000.0), [[300, 211]], [13], ratio=(40, 100), seed=46)
+    if name == "k128-bf16":
+        return synth.custom(synth.ModelShape("k128", "bf16", 128, 4, 2, 128, 10000.0, synth.ROPE_HALF), [[150, 260]], [7],
+                            ratio=(50, 100), seed=47)
     if name == "batched-f32-d128":
         return synth.custom(SMALL_F32_D128, [[40, 77], [129]], [7, 3], ratio=(30, 100), seed=44)
     raise KeyError(name)
@@ -156,7 +161,7 @@ def test_selected_qkv_proj(name):
 
 
 @pytest.mark.parametrize("ntw", ["2", "3", "4"])
-@pytest.mark.parametrize("name", ["g7-bf16", "batched-bf16-half", "cfg2"])
+@pytest.mark.parametrize("name", ["g7-bf16", "batched-bf16-half", "cfg2", "k64-bf16", "k128-bf16"])
 def test_selected_qkv_proj_every_tile_width(name, ntw, monkeypatch):
     """The large-tile GEMM kernel in each of its three workgroup shapes (the library normally
     picks one by row count; few rows go to the weight-streaming kernel instead)."""

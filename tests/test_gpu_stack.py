@@ -65,6 +65,7 @@ TAIL_CASES = {
     "bf16-one-row": ("bf16", 256, 2, 128, 512, 10, 1),
     "bf16-llama": ("bf16", 4096, 32, 128, 14336, 2000, 450),
     "bf16-all-rows": ("bf16", 512, 4, 128, 1024, 640, 640),          # act_idx NULL
+    "bf16-short-k": ("bf16", 128, 1, 128, 64, 400, 390),             # reductions of one and two 64-element slabs
 }
 
 
