@@ -245,8 +245,32 @@ topk_select_reg_kernel(const float *__restrict__ scores, topk_problem prob, int 
     lo += sh_bin << shift;
     hi = min(hi, lo + ((1u << shift) - 1u));
     need = sh_need;
+    const uint32_t in_bin = hist[sh_bin];                    // candidates left, need of them wanted
     __syncthreads();
     if (shift == 0) break;                                   // the bin was a single key
+    if (in_bin <= 64) {
+      // Few candidates left (the usual case after two rounds): they are gathered (in any order: what follows
+      // does not depend on it) and one wave ranks them instead of two more rounds over all lanes.  The key v
+      // with fewer than `need` candidates above it and at least `need` at or above it is the wanted one.
+      uint32_t *cand = hist;                                 // free since the barrier above
+      if (tid == 0) sh_bin = 0;
+      __syncthreads();
+#pragma unroll
+      for (int j = 0; j < KPT; ++j)
+        if (j < nv && key[j] - lo <= hi - lo) cand[atomicAdd(&sh_bin, 1u)] = key[j];
+      __syncthreads();
+      if (tid < 64) {
+        const uint32_t mine = tid < (int)in_bin ? cand[tid] : 0u;
+        uint32_t gt = 0, ge = 0;
+        for (uint32_t i = 0; i < in_bin; ++i) { const uint32_t c = cand[i]; gt += c > mine; ge += c >= mine; }
+        // (several lanes hold the wanted key when it occurs more than once: they store the same two numbers)
+        if (tid < (int)in_bin && gt < need && need <= ge) { wave_min[0] = mine; sh_need = need - gt; }
+      }
+      __syncthreads();
+      lo = hi = wave_min[0];
+      need = sh_need;
+      break;
+    }
   }
   const uint32_t tau = lo;               // key of the k-th largest; `need` rows equal to it are taken
 
