@@ -169,7 +169,7 @@ def stack_main(args):
     assert out["n_act"] == w.total_k + w.total_q and np.all(np.diff(act) > 0)
     assert bool(torch.isfinite(out["hidden"][out["act_idx"].long()].float()).all())
     full_ms, _ = timed(lambda: stack.prefill_stack(lay, s, layers, g_final, resid), max(1, steps // 4), 1)
-    streamed_ms = streamed_q8_ms = None
+    streamed_ms = streamed_q8_ms = file_q8_ms = None
     if args.stream_caches:
         from paper_2511_17560_amd import loader
         host_k = [None if c is None else [c[s0:s0 + n].cpu().pin_memory() for s0, n in zip(w.chunk_start, w.chunk_len)]
@@ -194,6 +194,25 @@ def stack_main(args):
         cs8 = loader.ChunkCacheStream(lay, s, w.chunk_start, w.chunk_len, host_q8, None, depth=2)
         streamed_q8_ms, _ = timed(lambda: stack.fuse_stack(lay, s, layers, g_final, resid, None, None, w.sel_start,
                                                            q_rows, cache_stream=cs8), steps, warmup)
+        del cs8
+        # and with the records in files (one per chunk, layer after layer; written just now, so the reads are served
+        # from the page cache: what is timed is the path, not a disk)
+        import os
+        import tempfile
+        with tempfile.TemporaryDirectory() as tmp:
+            paths = []
+            for ci in range(len(w.chunk_start)):
+                paths.append(os.path.join(tmp, f"chunk{ci}.q8"))
+                with open(paths[-1], "wb") as fh:
+                    for blocks_l in host_q8:
+                        if blocks_l is not None:
+                            fh.write(blocks_l[ci].numpy().tobytes())
+            fs = loader.ChunkFileStream(lay, s, w.chunk_start, w.chunk_len, paths, args.stack, depth=3, io_threads=8)
+            try:
+                file_q8_ms, _ = timed(lambda: stack.fuse_stack(lay, s, layers, g_final, resid, None, None, w.sel_start,
+                                                               q_rows, cache_stream=fs), steps, warmup)
+            finally:
+                fs.close()
     n_act = out["n_act"]
     # H(.) alone at the active rows: the call that dominates a layer once the rows are few
     attn_out = mk(n_act, s.n_q_heads, s.head_dim, std=1.0)
@@ -256,6 +275,7 @@ def stack_main(args):
         "streamed_cache_bytes": None if streamed_ms is None else
         2 * (args.stack - 2) * int(w.total_ctx) * kd * (2 if s.dtype == "bf16" else 4),
         "streamed_q8_caches_ms": streamed_q8_ms,
+        "file_q8_caches_ms": file_q8_ms,
         "streamed_q8_cache_bytes": None if streamed_q8_ms is None else
         (args.stack - 2) * int(w.total_ctx) * row,
         "block_tail": {"us_per_call": round(tail_us, 1), "rows": n_act, "flops_per_call": tail_flops,

@@ -46,7 +46,8 @@ typedef enum {
   A3_ERR_INVALID_ARG = -1,
   A3_ERR_UNSUPPORTED = -2,
   A3_ERR_WORKSPACE = -3,
-  A3_ERR_HIP = -4
+  A3_ERR_HIP = -4,
+  A3_ERR_IO = -5
 } a3_status;
 
 typedef enum { A3_F32 = 0, A3_BF16 = 1 } a3_dtype;
@@ -293,6 +294,17 @@ a3_status a3_select_chunk_edges(const a3_layout *layout, int n_head, int n_tail,
 a3_status a3_chunk_cache_load(const a3_layout *layout, const int *chunk_start_host, const int *chunk_len_host,
                               int n_chunks, const void *const *host_k, const void *const *host_v,
                               void *k_cat, void *v_cat, void *stream);
+
+/* The chunk store itself sits on persistent storage (Eq. 1; the paper names loading it as the method's limitation).
+ * a3_chunk_file_read brings one layer's blocks from already opened files into HOST staging buffers, from which
+ * a3_chunk_cache_load / a3_chunk_cache_load_q8 copy them on (asynchronously if the buffers are pinned): block c is
+ * n_bytes[c] bytes at file_offset[c] of the descriptor fds[c], read into host_dst[c].  All arguments are host
+ * arrays of n_blocks entries.  Positional reads (the descriptors' own offsets are not used or moved), continued
+ * after short reads, spread block by block over up to n_threads (1..16) threads; the call returns when every block
+ * is in memory.  No GPU call, nothing allocated beyond the threads.  Errors: A3_ERR_INVALID_ARG before any read;
+ * A3_ERR_IO when a read fails or a file ends inside a block (a3_last_error() names the block). */
+a3_status a3_chunk_file_read(int n_blocks, const int *fds, const long long *file_offset, const size_t *n_bytes,
+                             void *const *host_dst, int n_threads);
 
 /* ---- 8-bit form of the chunk caches (the paper fixes no format and calls cache quantisation orthogonal; it
  * halves what the staging above has to move) -----------------------------------------------------------------

@@ -15,7 +15,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "liba3.so")
 
-A3_OK, A3_ERR_INVALID_ARG, A3_ERR_UNSUPPORTED, A3_ERR_WORKSPACE, A3_ERR_HIP = 0, -1, -2, -3, -4
+A3_OK, A3_ERR_INVALID_ARG, A3_ERR_UNSUPPORTED, A3_ERR_WORKSPACE, A3_ERR_HIP, A3_ERR_IO = 0, -1, -2, -3, -4, -5
 A3_F32, A3_BF16 = 0, 1
 A3_ROPE_INTERLEAVED, A3_ROPE_HALF = 0, 1
 A3_POOL_MAX, A3_POOL_AVG = 0, 1
@@ -25,7 +25,7 @@ EXPORTS = ["a3_workspace_bytes", "a3_layout_prepare", "a3_rope_realign", "a3_que
            "a3_block_tail_ws_bytes", "a3_block_tail", "a3_rms_norm", "a3_question_scores_causal", "a3_window_votes",
            "a3_evict_ws_bytes", "a3_evict_select", "a3_evict_compact", "a3_value_deviation_scores",
            "a3_select_chunk_edges", "a3_chunk_cache_load", "a3_rope_realign_q8", "a3_q8_row_bytes", "a3_quantize_q8",
-           "a3_chunk_cache_load_q8", "a3_strerror", "a3_last_error", "a3_version"]
+           "a3_chunk_cache_load_q8", "a3_chunk_file_read", "a3_strerror", "a3_last_error", "a3_version"]
 
 
 class A3Error(RuntimeError):
@@ -98,6 +98,9 @@ def lib() -> C.CDLL:
     L.a3_chunk_cache_load.argtypes = [P, C.POINTER(C.c_int), C.POINTER(C.c_int), I, C.POINTER(C.c_void_p),
                                       C.POINTER(C.c_void_p), V, V, V]
     L.a3_chunk_cache_load.restype = I
+    L.a3_chunk_file_read.argtypes = [I, C.POINTER(C.c_int), C.POINTER(C.c_longlong), C.POINTER(C.c_size_t),
+                                     C.POINTER(C.c_void_p), I]
+    L.a3_chunk_file_read.restype = I
     L.a3_q8_row_bytes.argtypes = [P]
     L.a3_q8_row_bytes.restype = C.c_size_t
     L.a3_quantize_q8.argtypes = [P, V, V, V, V]
@@ -395,3 +398,16 @@ def a3_chunk_cache_load_q8(layout: Layout, chunk_start, chunk_len, host_q8, cach
     blocks = (C.c_void_p * n)(*[t.data_ptr() if t is not None else None for t in host_q8])
     _check(lib().a3_chunk_cache_load_q8(layout.ref, starts, lens, n, blocks, _ptr(cache_q8), _stream(stream)),
            "a3_chunk_cache_load_q8")
+
+
+def a3_chunk_file_read(fds, file_offset, n_bytes, host_dst, n_threads: int = 4) -> None:
+    """Blocking: block c = n_bytes[c] bytes at file_offset[c] of descriptor fds[c] into the CPU tensor host_dst[c]
+    (the GIL is released meanwhile, so a Python thread can run it beside the launches)."""
+    n = len(fds)
+    for t, b in zip(host_dst, n_bytes):
+        assert t is None or (t.device.type == "cpu" and t.is_contiguous() and t.numel() * t.element_size() >= b)
+    _check(lib().a3_chunk_file_read(n, (C.c_int * n)(*[int(f) for f in fds]),
+                                    (C.c_longlong * n)(*[int(o) for o in file_offset]),
+                                    (C.c_size_t * n)(*[int(b) for b in n_bytes]),
+                                    (C.c_void_p * n)(*[t.data_ptr() if t is not None else None for t in host_dst]),
+                                    int(n_threads)), "a3_chunk_file_read")

@@ -6,6 +6,13 @@
 
 #include "a3_internal.h"
 
+#include <errno.h>
+#include <unistd.h>
+
+#include <atomic>
+#include <thread>
+#include <vector>
+
 static thread_local char g_last_error[512] = "";
 
 a3_status a3_fail(a3_status code, const char *fmt, ...) {
@@ -57,6 +64,7 @@ extern "C" const char *a3_strerror(a3_status s) {
     case A3_ERR_UNSUPPORTED: return "unsupported shape or type";
     case A3_ERR_WORKSPACE: return "workspace too small";
     case A3_ERR_HIP: return "HIP launch failed";
+    case A3_ERR_IO: return "file read failed";
   }
   return "unknown status";
 }
@@ -99,6 +107,48 @@ extern "C" a3_status a3_chunk_cache_load(const a3_layout *L, const int *chunk_st
     hipError_t e = hipMemcpyAsync((char *)k_cat + off, host_k[c], bytes, hipMemcpyHostToDevice, st);
     if (e == hipSuccess) e = hipMemcpyAsync((char *)v_cat + off, host_v[c], bytes, hipMemcpyHostToDevice, st);
     if (e != hipSuccess) return a3_fail(A3_ERR_HIP, "a3_chunk_cache_load: chunk %d: %s", c, hipGetErrorString(e));
+  }
+  return A3_OK;
+}
+
+// The chunk store itself sits on persistent storage (Eq. 1; the paper names loading it as the method's
+// limitation).  One layer's blocks are read from already opened files into host staging buffers (pinned ones, so
+// that a3_chunk_cache_load / a3_chunk_cache_load_q8 can copy them on asynchronously): block c is n_bytes[c]
+// bytes at file_offset[c] of descriptor fds[c].  Plain positional reads, continued after short reads, spread
+// over up to n_threads threads by block; the call returns when every block is in memory.  No GPU call.
+extern "C" a3_status a3_chunk_file_read(int n_blocks, const int *fds, const long long *file_offset,
+                                        const size_t *n_bytes, void *const *host_dst, int n_threads) {
+  A3_REQUIRE(n_blocks >= 0, A3_ERR_INVALID_ARG, "a3_chunk_file_read: n_blocks %d is negative", n_blocks);
+  if (n_blocks == 0) return A3_OK;
+  A3_REQUIRE(fds && file_offset && n_bytes && host_dst, A3_ERR_INVALID_ARG, "a3_chunk_file_read: NULL argument");
+  for (int c = 0; c < n_blocks; ++c) {
+    A3_REQUIRE(fds[c] >= 0 && file_offset[c] >= 0, A3_ERR_INVALID_ARG,
+               "a3_chunk_file_read: block %d: descriptor %d, offset %lld", c, fds[c], file_offset[c]);
+    A3_REQUIRE(n_bytes[c] == 0 || host_dst[c], A3_ERR_INVALID_ARG, "a3_chunk_file_read: block %d has no destination", c);
+  }
+  std::atomic<int> next(0), failed_block(-1), failed_errno(0);
+  auto work = [&]() {
+    for (int c = next.fetch_add(1); c < n_blocks; c = next.fetch_add(1)) {
+      size_t done = 0;
+      while (done < n_bytes[c]) {
+        const ssize_t r = pread(fds[c], (char *)host_dst[c] + done, n_bytes[c] - done, (off_t)(file_offset[c] + (long long)done));
+        if (r > 0) { done += (size_t)r; continue; }
+        if (r < 0 && errno == EINTR) continue;
+        int expected = -1;                                     // r == 0: the file ends inside the block
+        if (failed_block.compare_exchange_strong(expected, c)) failed_errno.store(r < 0 ? errno : 0);
+        break;
+      }
+    }
+  };
+  const int nt = n_threads < 1 ? 1 : (n_threads > 16 ? 16 : n_threads);
+  std::vector<std::thread> pool;
+  for (int t = 1; t < nt && t < n_blocks; ++t) pool.emplace_back(work);
+  work();
+  for (auto &t : pool) t.join();
+  if (failed_block.load() >= 0) {
+    const int e = failed_errno.load();
+    return a3_fail(A3_ERR_IO, "a3_chunk_file_read: block %d: %s", failed_block.load(),
+                   e ? strerror(e) : "the file ends inside the block");
   }
   return A3_OK;
 }

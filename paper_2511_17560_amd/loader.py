@@ -71,3 +71,79 @@ class ChunkCacheStream:
         ev = torch.cuda.Event()
         ev.record(stream or torch.cuda.current_stream())
         self.free[l % self.depth] = ev
+
+
+class ChunkFileStream:
+    """The same hand-over as ChunkCacheStream for 8-bit chunk caches that live in FILES: one file per chunk holding
+    the chunk's records layer after layer, layer l (>= first_layer) at byte offset
+    (l - first_layer) * chunk_len[c] * a3_q8_row_bytes.  A worker thread reads layer l's blocks into a pinned
+    staging buffer (a3_chunk_file_read, ``io_threads`` reader threads), enqueues the copies into device buffer
+    l % depth on the copy stream (a3_chunk_cache_load_q8) and records the event the consumer waits for; staging
+    buffer and device buffer are reused only after the copies, respectively the consumer, have passed them.
+    Sequencing only; ``close()`` ends the worker and closes the files."""
+
+    q8 = True
+
+    def __init__(self, layout: api.Layout, shape, chunk_start, chunk_len, paths: Sequence[str], n_layers: int,
+                 first_layer: int = 2, depth: int = 2, io_threads: int = 4):
+        import concurrent.futures
+        import os
+        assert depth >= 2
+        self.layout, self.depth, self.io_threads = layout, depth, io_threads
+        self.chunk_start, self.chunk_len = list(map(int, chunk_start)), list(map(int, chunk_len))
+        self.n_layers, self.first_layer = n_layers, first_layer
+        self.row = api.a3_q8_row_bytes(layout)
+        self.fds = [os.open(p, os.O_RDONLY) for p in paths]
+        T = layout.total_tokens
+        self.dev = [torch.zeros((T, self.row), dtype=torch.uint8, device=layout.device) for _ in range(depth)]
+        total = sum(self.chunk_len) * self.row
+        self.staging = [torch.empty(max(total, 1), dtype=torch.uint8).pin_memory() for _ in range(depth)]
+        self.copy_stream = torch.cuda.Stream(device=layout.device)          # default priority
+        self.copied: List = [None] * depth       # event: the copies out of staging buffer i have finished
+        self.free: List = [None] * depth         # event: the consumer of device buffer i is done with it
+        self.jobs = {}                           # layer -> future returning the "loaded" event
+        self.pool = concurrent.futures.ThreadPoolExecutor(max_workers=1)
+
+    def _load(self, l: int):
+        i = l % self.depth
+        if self.copied[i] is not None:
+            self.copied[i].synchronize()         # staging buffer i is free again
+        blocks, pos = [], 0
+        for n in self.chunk_len:
+            blocks.append(self.staging[i][pos:pos + n * self.row])
+            pos += n * self.row
+        offs = [(l - self.first_layer) * n * self.row for n in self.chunk_len]
+        api.a3_chunk_file_read(self.fds, offs, [n * self.row for n in self.chunk_len], blocks, n_threads=self.io_threads)
+        if self.free[i] is not None:
+            self.copy_stream.wait_event(self.free[i])
+        api.a3_chunk_cache_load_q8(self.layout, self.chunk_start, self.chunk_len, blocks, self.dev[i],
+                                   stream=self.copy_stream)
+        ev = torch.cuda.Event()
+        ev.record(self.copy_stream)
+        self.copied[i] = ev
+        return ev
+
+    def prefetch(self, l: int) -> None:
+        """Hand layer l to the worker thread (after release() of the layer that used its buffer before)."""
+        if l < self.first_layer or l >= self.n_layers or l in self.jobs:
+            return
+        self.jobs[l] = self.pool.submit(self._load, l)
+
+    def acquire(self, l: int, stream=None):
+        """The layer's device records; the compute stream waits until the copies have landed (and this thread
+        until the file reads have: when storage is slower than the layers, this is where the time goes)."""
+        ev = self.jobs.pop(l).result()
+        (stream or torch.cuda.current_stream()).wait_event(ev)
+        return self.dev[l % self.depth]
+
+    def release(self, l: int, stream=None) -> None:
+        ev = torch.cuda.Event()
+        ev.record(stream or torch.cuda.current_stream())
+        self.free[l % self.depth] = ev
+
+    def close(self) -> None:
+        import os
+        self.pool.shutdown(wait=True)
+        for fd in self.fds:
+            os.close(fd)
+        self.fds = []

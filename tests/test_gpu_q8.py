@@ -208,3 +208,24 @@ def test_streamed_stack_on_q8_blocks(case):
     assert max_abs_rel(to_host(b["hidden"][rows]), to_host(a["hidden"][rows])) <= tol
     assert max_abs_rel(to_host(b["resid"][rows]), to_host(a["resid"][rows])) <= tol
     assert not torch.equal(a["hidden"][rows], torch.zeros_like(a["hidden"][rows]))
+    # the same records read from files (one per chunk, layer after layer) by the loader's worker thread: bit for bit
+    # what the host blocks gave, with two and with three buffers in the ring
+    import os
+    import tempfile
+    with tempfile.TemporaryDirectory() as tmp:
+        paths = []
+        for ci in range(len(w.chunk_start)):
+            paths.append(os.path.join(tmp, f"chunk{ci}.q8"))
+            with open(paths[-1], "wb") as f:
+                for l in range(2, n_layers):
+                    f.write(host[l][ci].numpy().tobytes())
+        for depth in (2, 3):
+            fs = loader.ChunkFileStream(lay, shape, w.chunk_start, w.chunk_len, paths, n_layers, depth=depth, io_threads=3)
+            try:
+                c = stack.fuse_stack(lay, shape, dev_layers, g_final, to_dev(sw["resid0"], dt), None, None, w.sel_start,
+                                     w.question_rows(), cache_stream=fs)
+                torch.cuda.synchronize()
+            finally:
+                fs.close()
+            assert torch.equal(c["act_idx"], b["act_idx"])
+            assert torch.equal(c["hidden"][rows], b["hidden"][rows]) and torch.equal(c["resid"][rows], b["resid"][rows])
