@@ -96,20 +96,12 @@ __device__ __forceinline__ int plan_scan(int v, int *wave_tot, int *total) {
 
 __global__ void __launch_bounds__(kPlanThreads)
 attn_plan_kernel(attn_plan p, const int *__restrict__ act_idx, int n_act, const int *__restrict__ seg_start,
-                 const int *__restrict__ tok_req, int total_tokens, int n_req, int G, int wgs_per_head, int item_cost) {
+                 int n_req, int G, int wgs_per_head, int item_cost) {
   __shared__ int wave_tot[kPlanThreads / 64];
   const int tid = threadIdx.x;
-  // Active rows are ascending, so the rows of request r are a contiguous range that starts at
-  // a_lo[r] = first i whose request is >= r.  Every position i in 0..n_act looks at the requests of its two
-  // neighbours (two loads deep, all positions at once; a bisection per request would be a dozen dependent
-  // round trips) and writes the entries of the requests that begin there: the requests after that of row
-  // i - 1 (none: -1) up to that of row i (past the end: n_req).
-  for (int i = tid; i <= n_act; i += kPlanThreads) {
-    // (rows are clamped into the table: a list that breaks the contract must not send a load outside it)
-    const int r_prev = i > 0 ? tok_req[min(max(act_idx[i - 1], 0), total_tokens - 1)] : -1;
-    const int r_here = i < n_act ? min(tok_req[min(max(act_idx[i], 0), total_tokens - 1)], n_req - 1) : n_req;
-    for (int r = r_prev + 1; r <= r_here; ++r) p.a_lo[r] = i;
-  }
+  // active rows are ascending, so the rows of request r are a contiguous range found by bisection
+  for (int r = tid; r <= n_req; r += kPlanThreads)
+    p.a_lo[r] = r == n_req ? n_act : lower_bound_i32(act_idx, n_act, seg_start[r]);
   __syncthreads();
   if (tid == 0) {
     int t = 0;
@@ -702,7 +694,7 @@ static a3_status attn_launch(const a3_layout *L, const void *q_act, const int *a
     a.plan.max_tiles = max_tiles; a.plan.max_items = max_items; a.plan.max_wgs = wgs_per_head;
     if (parts & 1)
       hipLaunchKernelGGL(attn_plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, a.plan, act_idx, n_act, L->seg_start,
-                         L->tok_req, L->total_tokens, L->n_req, L->n_q_heads / L->n_kv_heads, wgs_per_head, attn_item_cost());
+                         L->n_req, L->n_q_heads / L->n_kv_heads, wgs_per_head, attn_item_cost());
     if (parts & 2) {
       // blockIdx % Hkv = KV head, so with 8 KV heads each XCD's L2 serves the K/V of one head
       hipLaunchKernelGGL(attn_bf16_kernel, dim3((unsigned)wgs_per_head * Hkv), dim3(kAttnThreads), kAttnLds, st, a);
