@@ -460,7 +460,9 @@ def main():
         # one call: the stale keys are read once and the realigned cache written once
         "realign_scores_GBs": work["realign_bytes"] / (per_call_us["a3_realign_scores"]["us_per_step"] * 1e-6) / 1e9,
         "scatter_GBs": work["scatter_bytes"] / (per_call_plain["a3_kv_scatter"]["us_per_step"] * 1e-6) / 1e9,
-        "proj_TFLOPs": work["proj_flops"] / (per_call_us["a3_selected_qkv_proj_scatter"]["us_per_step"] * 1e-6) / 1e12,
+        # both projection calls of a step (Q of the question rows, then Q/K/V of the rows [Re, Q])
+        "proj_TFLOPs": work["proj_flops"] / ((per_call_us["a3_selected_qkv_proj_scatter"]["us_per_step"] +
+                                               per_call_us["a3_selected_qkv_proj"]["us_per_step"]) * 1e-6) / 1e12,
         "attn_TFLOPs": work["attn_flops"] / (per_call_us[attn_name]["us_per_step"] * 1e-6) / 1e12,
         # both passes form every logit once
         "scores_TFLOPs": 2 * work["scores_flops"] / (per_call_plain["a3_question_scores"]["us_per_step"] * 1e-6) / 1e12,

@@ -1,8 +1,8 @@
 """One pass of the whole per-layer fusion path: the sequence of C-ABI calls of one layer, on
 preallocated buffers.  Call sequencing only; all arithmetic happens inside liba3.
 
-    project question rows -> realign keys (Eq. 2) -> scores (Eq. 3) -> top-p (Eq. 3)
-    -> project selected rows (Eq. 5) -> update cache (Eq. 5) -> attention (Eq. 4 / Eq. 5)
+    Q of the question rows -> realign keys (Eq. 2) -> scores (Eq. 3) -> top-p (Eq. 3)
+    -> project the rows [Re, Q] (Eq. 5) -> update cache (Eq. 5) -> attention (Eq. 4 / Eq. 5)
 """
 from __future__ import annotations
 
@@ -76,10 +76,9 @@ def fuse_layer(layout: api.Layout, b: LayerBuffers, x_cur: torch.Tensor, k_cat: 
     """Runs steps 1-5 for one layer.  ``k_cat`` is read, ``b.k_fused`` and ``v_cache`` (in place)
     hold the fused cache afterwards, ``b.out`` the attention output of the active rows.
 
-    ``fused_scatter`` (default) lets the projections write the fresh K/V straight into the caches
-    (a3_selected_qkv_proj_scatter); otherwise the plain sequence a3_selected_qkv_proj ->
-    a3_kv_scatter is used.  Both give the same cache: the question rows are written before the
-    realign, which only writes context rows, and the selected rows after the scores were read.
+    ``fused_scatter`` (default) lets the projection of the active rows write the fresh K/V straight into the
+    caches (a3_selected_qkv_proj_scatter); otherwise the plain sequence a3_selected_qkv_proj ->
+    a3_kv_scatter is used.  Both give the same cache, written after the scores were read.
     ``fused_realign`` (default) runs steps 1 and 2 as one call (a3_realign_scores).
     ``overlap_plan`` has the attention's work laid out (a3_attention_plan, one small workgroup) on a second
     stream as soon as the active rows are known, beside the projection of the selected rows, and then calls
@@ -87,23 +86,18 @@ def fuse_layer(layout: api.Layout, b: LayerBuffers, x_cur: torch.Tensor, k_cat: 
     20 us) than the 9 us plan kernel they hide."""
     nq = b.n_act - b.total_k
     k = b.total_k
-    if b.single:
-        if fused_scatter:
-            api.a3_selected_qkv_proj_scatter(layout, x_cur, b.q_rows, nq, wq, wk, wv, q_out=b.q_act[k:],
-                                             k_fused=b.k_fused, v_fused=v_cache, stream=stream)
-        else:
-            api.a3_selected_qkv_proj(layout, x_cur, b.q_rows, nq, wq, wk, wv, q_out=b.q_act[k:], k_out=b.k_act[k:],
-                                     v_out=b.v_act[k:], stream=stream)
-    else:
-        api.a3_selected_qkv_proj(layout, x_cur, b.q_rows, nq, wq, None, None, q_out=b.q_question, stream=stream)
+    # Only Q of the question rows is needed before the selection (it scores the context); their K and V come out
+    # of the second projection, which covers all active rows: the first call then streams W_q alone, and the few
+    # question rows do not add a row tile to the second.
+    api.a3_selected_qkv_proj(layout, x_cur, b.q_rows, nq, wq, None, None, q_out=b.q_question, stream=stream)
     if fused_realign:
         api.a3_realign_scores(layout, b.q_question, k_cat, b.k_fused, b.scores, b.ws, stream=stream)
     else:
         api.a3_rope_realign(layout, k_cat, b.k_fused, stream=stream)
         api.a3_question_scores(layout, b.q_question, b.k_fused, b.scores, b.ws, stream=stream)
     api.a3_topk_select(layout, b.scores, b.sel_start, k, b.sel_idx, stream=stream)
-    rows, n_rows = (b.sel_idx, k) if b.single else (b.act_idx, b.n_act)
-    if not b.single:
+    rows, n_rows = b.act_idx, b.n_act
+    if not b.single:           # (a single request: act_idx = [selected | question], filled in place by the top-p)
         api.a3_active_rows(layout, b.sel_idx, b.sel_start, b.n_act, b.act_idx, stream=stream)
     overlap_plan = overlap_plan and b.side is not None
     if overlap_plan:
