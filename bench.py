@@ -297,6 +297,9 @@ def main():
     ap.add_argument("--stream-caches", action="store_true",
                     help="with --stack: also time the schedule with the chunk caches streamed from pinned host memory "
                          "layer by layer (a3_chunk_cache_load on a copy stream) instead of resident in HBM")
+    ap.add_argument("--two-streams", action="store_true",
+                    help="also time the same steps issued alternately on two streams (derived.two_streams_us_per_step; "
+                         "never the headline value)")
     ap.add_argument("--stack", type=int, default=0,
                     help="L >= 2: time the A^3 schedule over L decoder blocks against the plain prefill of the same "
                          "stack instead of the per-layer hot path (not the headline metric)")
@@ -371,7 +374,7 @@ def main():
 
     # ---- the same steps on two streams, alternately (outside the timed region) -----------------
     two_streams_ms = None
-    if n_layers >= 2:
+    if args.two_streams and n_layers >= 2:
         pair = [torch.cuda.Stream(device=dev), torch.cuda.Stream(device=dev)]      # default priority
         torch.cuda.synchronize()
 
