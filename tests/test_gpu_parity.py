@@ -160,12 +160,15 @@ def test_selected_qkv_proj(name):
     assert max_abs_rel(to_host(k), want) <= tol(w)
 
 
+@pytest.mark.parametrize("k64", ["1", "0"])
 @pytest.mark.parametrize("ntw", ["2", "3", "4"])
 @pytest.mark.parametrize("name", ["g7-bf16", "batched-bf16-half", "cfg2", "k64-bf16", "k128-bf16"])
-def test_selected_qkv_proj_every_tile_width(name, ntw, monkeypatch):
+def test_selected_qkv_proj_every_tile_width(name, ntw, k64, monkeypatch):
     """The large-tile GEMM kernel in each of its three workgroup shapes (the library normally
-    picks one by row count; few rows go to the weight-streaming kernel instead)."""
+    picks one by row count; few rows go to the weight-streaming kernel instead), with the main loop on
+    128-byte row pieces (the default for the two larger shapes) and on 64-byte pieces."""
     monkeypatch.setenv("A3_PROJ_NTW", ntw)
+    monkeypatch.setenv("A3_PROJ_K64", k64)
     c = ctx_of(name)
     w, b, res, lay = c["w"], c["b"], c["res"], c["lay"]
     s, t = w.shape, b["t"]
