@@ -72,6 +72,19 @@ struct a3_ws_cursor {
   bool fits() const { return off <= cap; }
 };
 
+// ---- streaming accesses: for tensors every byte of which is touched once per kernel (a cache copied, expanded,
+// realigned), nontemporal loads and stores keep them from displacing what the caches should hold and run measurably
+// faster on this chip (position recovery of 32 MiB: 14.9 -> 13.3 us) -------------------------------------------
+typedef unsigned int a3_u32x4 __attribute__((ext_vector_type(4)));
+template <typename P> __device__ __forceinline__ void a3_nt_store(P *p, uint4 v) {
+  a3_u32x4 w = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(w, reinterpret_cast<a3_u32x4 *>(p));
+}
+template <typename P> __device__ __forceinline__ uint4 a3_nt_load(const P *p) {
+  const a3_u32x4 w = __builtin_nontemporal_load(reinterpret_cast<const a3_u32x4 *>(p));
+  return make_uint4(w.x, w.y, w.z, w.w);
+}
+
 // ---- per-step launchers (one per translation unit) ---------------------------------------------
 size_t a3_scores_ws_bytes(const a3_layout *L);
 size_t a3_attn_ws_bytes(const a3_layout *L, int max_active_rows);

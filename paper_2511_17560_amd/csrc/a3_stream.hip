@@ -110,7 +110,7 @@ rope_realign_kernel(const T *k_cat, T *k_fused,   /* may alias: each item reads 
         int e = j * VEC;                       // element inside the row
         offa[u] = (size_t)t * row_elems + e;
         pair0[u] = (e % head_dim) >> 1;
-        if (chunk[u] >= 0) va[u] = *reinterpret_cast<const uint4 *>(k_cat + offa[u]);
+        if (chunk[u] >= 0) va[u] = a3_nt_load(k_cat + offa[u]);
       } else {
         int per_head = half / VEC;             // work items per head
         int h = j / per_head, e = (j % per_head) * VEC;
@@ -118,8 +118,8 @@ rope_realign_kernel(const T *k_cat, T *k_fused,   /* may alias: each item reads 
         offb[u] = offa[u] + half;
         pair0[u] = e;
         if (chunk[u] >= 0) {
-          va[u] = *reinterpret_cast<const uint4 *>(k_cat + offa[u]);
-          vb[u] = *reinterpret_cast<const uint4 *>(k_cat + offb[u]);
+          va[u] = a3_nt_load(k_cat + offa[u]);
+          vb[u] = a3_nt_load(k_cat + offb[u]);
         }
       }
     }
@@ -135,7 +135,7 @@ rope_realign_kernel(const T *k_cat, T *k_fused,   /* may alias: each item reads 
       for (int p = 0; p < VEC / 2; ++p) {
         a3_rotate_pair(x[2 * p], x[2 * p + 1], cs[p], y[2 * p], y[2 * p + 1]);
       }
-      *reinterpret_cast<uint4 *>(k_fused + offa[u]) = pack<T, VEC>(y);
+      a3_nt_store(k_fused + offa[u], pack<T, VEC>(y));
     } else {
       float xa[VEC], xb[VEC], ya[VEC], yb[VEC];
       unpack<T, VEC>(va[u], xa);
@@ -144,8 +144,8 @@ rope_realign_kernel(const T *k_cat, T *k_fused,   /* may alias: each item reads 
       for (int p = 0; p < VEC; ++p) {
         a3_rotate_pair(xa[p], xb[p], cs[p], ya[p], yb[p]);
       }
-      *reinterpret_cast<uint4 *>(k_fused + offa[u]) = pack<T, VEC>(ya);
-      *reinterpret_cast<uint4 *>(k_fused + offb[u]) = pack<T, VEC>(yb);
+      a3_nt_store(k_fused + offa[u], pack<T, VEC>(ya));
+      a3_nt_store(k_fused + offb[u], pack<T, VEC>(yb));
     }
   }
 }
