@@ -357,12 +357,15 @@ def test_chained_layer(name, fused_scatter=True, fused_realign=True):
     assert np.array_equal(to_host(v_cache)[stale], res["v_fused"][stale])
 
 
-@pytest.mark.parametrize("case", ["ties", "all-equal", "k-zero-and-full", "long-global-path", "negatives", "vector-tail-4k", "vector-tail-16k"])
+@pytest.mark.parametrize("case", ["ties", "all-equal", "k-zero-and-full", "long-global-path", "negatives", "vector-tail-4k",
+                                  "vector-tail-16k", "dups-at-cut"])
 def test_topk_select_edge_cases(case):
     """Top-p on hand-made score arrays, bit-exact against the oracle: heavy ties across the cut,
     all-equal scores (lowest rows win), k = 0 and k = N per request, a request longer than the
-    register-resident limit (global re-read path), scores of both signs with +-0, and lengths that end
-    inside a lane's vector load."""
+    register-resident limit (global re-read path), scores of both signs with +-0, lengths that end
+    inside a lane's vector load, and otherwise distinct scores whose k-th largest value occurs several
+    times (the few candidates left after two radix rounds are ranked by one wave: some of the equal ones
+    are taken, in row order, the others are not)."""
     rng = np.random.default_rng(99)
     shape = synth.ModelShape("topk", "f32", 32, 1, 1, 64, 1e4)
     if case == "long-global-path":
@@ -386,6 +389,15 @@ def test_topk_select_edge_cases(case):
         sc[3::11] = -0.0
     else:
         sc = rng.random(T).astype(np.float32) * np.exp(rng.uniform(-8, 3, T)).astype(np.float32)
+    if case == "dups-at-cut":
+        for r in range(w.n_req):
+            rows = w.ctx_rows(r)
+            k_r = int(w.sel_start[r + 1] - w.sel_start[r])
+            order = rows[np.argsort(-sc[rows], kind="stable")]
+            kth = sc[order[k_r - 1]]
+            lower = order[k_r + 5:]                          # rows that would not be selected
+            sc[np.sort(rng.choice(lower, size=6, replace=False))] = kth          # 7 equal values, one is wanted
+            sc[order[k_r - 2]] = kth                                             # and the one above the cut too: 8, two wanted
     sc[w.question_rows()] = -np.inf
     sel_start = w.sel_start.copy()
     if case == "k-zero-and-full":
