@@ -229,3 +229,33 @@ def test_streamed_stack_on_q8_blocks(case):
                 fs.close()
             assert torch.equal(c["act_idx"], b["act_idx"])
             assert torch.equal(c["hidden"][rows], b["hidden"][rows]) and torch.equal(c["resid"][rows], b["resid"][rows])
+
+
+def test_chunk_file_stream_reports_a_short_file(tmp_path):
+    """A chunk file that ends inside the requested layer: the read fails in the worker thread and the error
+    reaches the caller of acquire(); nothing is copied for that layer and close() still works."""
+    from paper_2511_17560_amd import loader
+    c = ctx_of("ragged-bf16")
+    w, lay = c["w"], c["lay"]
+    row = api.a3_q8_row_bytes(lay)
+    paths = []
+    for ci, n in enumerate(w.chunk_len):
+        p = tmp_path / f"c{ci}.q8"
+        layers_in_file = 1 if ci == 1 else 2                   # chunk 1 holds one layer only
+        p.write_bytes(bytes([ci + 1]) * (int(n) * row * layers_in_file))
+        paths.append(str(p))
+    fs = loader.ChunkFileStream(lay, w.shape, w.chunk_start, w.chunk_len, paths, n_layers=4, first_layer=2, depth=2)
+    try:
+        fs.prefetch(2)
+        rec = fs.acquire(2)
+        torch.cuda.synchronize()
+        got = rec.cpu().numpy()
+        for ci, (s0, n) in enumerate(zip(w.chunk_start, w.chunk_len)):
+            assert np.all(got[s0:s0 + n] == ci + 1)
+        fs.release(2)
+        fs.prefetch(3)
+        with pytest.raises(api.A3Error) as e:
+            fs.acquire(3)
+        assert e.value.status == api.A3_ERR_IO and "block 1" in str(e.value)
+    finally:
+        fs.close()
