@@ -500,12 +500,18 @@ __device__ __forceinline__ void small_finish(const proj_args &a, const head_sel 
 // path of the L1, not HBM, then sets the pace.)  LDS slot s of row r holds the 16-byte piece
 // s ^ ((r/2) % 8) of the row's 128 bytes: the 16 consecutive rows a quarter wave reads at one piece
 // index touch all 64 banks once.
-constexpr int kSmStageBytes = 96 * 128;
+// RB = row blocks of 32 per workgroup: 2 (64 rows), or 1 when that leaves more than half of the CUs without a
+// workgroup (a call with few heads: Q of the question rows alone): twice the workgroups, each re-reading half as
+// many hidden rows.
 constexpr int kSmRing = 3;
-constexpr size_t kSmLdsBytes = (size_t)4 * kSmRing * kSmStageBytes;      // 144 KB
+constexpr int sm_stage_bytes(int rb) { return (32 + 32 * rb) * 128; }
+constexpr size_t sm_lds_bytes(int rb) { return (size_t)4 * kSmRing * sm_stage_bytes(rb); }      // 144 KB / 96 KB
 
+template <int RB>
 __global__ void __launch_bounds__(256)
 proj_small_dma_bf16_kernel(proj_args a) {
+  constexpr int kSmStageBytes = sm_stage_bytes(RB);
+  constexpr int kSmLoads = 4 + 4 * RB;                         // direct-to-LDS loads per stage
   extern __shared__ __align__(16) unsigned char lds[];
 
   const int head_all = blockIdx.x >> 2, sb = blockIdx.x & 3;
@@ -513,12 +519,12 @@ proj_small_dma_bf16_kernel(proj_args a) {
   if (a.out[hs.which] == nullptr) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, lhi = lane >> 5;
-  const int tok0 = blockIdx.y * 64;
+  const int tok0 = blockIdx.y * 32 * RB;
   const int kq = a.K / 4;                                      // this wave's share: a multiple of 64
 
   // loading role: one instruction brings 8 rows x 128 B, lane -> (row lane/8, slot lane%8)
   const int drow = lane >> 3, dslot = lane & 7;
-  const char *wsrc[4], *xsrc[8];
+  const char *wsrc[4], *xsrc[4 * RB];
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const int row = 8 * j + drow;                              // MFMA row of the weight block
@@ -527,7 +533,7 @@ proj_small_dma_bf16_kernel(proj_args a) {
               16 * (dslot ^ ((row >> 1) & 7));
   }
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
+  for (int j = 0; j < 4 * RB; ++j) {
     const int row = 8 * j + drow;
     const int m = min(tok0 + row, a.n_rows - 1);               // clamp: computed but never stored
     const int src_row = a.row_idx ? a.row_idx[m] : m;
@@ -544,14 +550,14 @@ proj_small_dma_bf16_kernel(proj_args a) {
       asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"                                       \
                    :: "s"(__builtin_amdgcn_readfirstlane(lds_ring + (SLOT) * kSmStageBytes + 1024 * j)),       \
                       "v"(wsrc[j] + 2 * (K0)) : "memory");                                                     \
-    _Pragma("unroll") for (int j = 0; j < 8; ++j)                                                              \
+    _Pragma("unroll") for (int j = 0; j < 4 * RB; ++j)                                                         \
       asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"                                       \
                    :: "s"(__builtin_amdgcn_readfirstlane(lds_ring + (SLOT) * kSmStageBytes + 4096 + 1024 * j)), \
                       "v"(xsrc[j] + 2 * (K0)) : "memory");                                                     \
   }
-  f32x16 acc[2];
+  f32x16 acc[RB];
 #pragma unroll
-  for (int tb = 0; tb < 2; ++tb)
+  for (int tb = 0; tb < RB; ++tb)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[tb][r] = 0.f;
   // everything the compiler loaded itself (row indices) has arrived: from here on only the
@@ -565,9 +571,9 @@ proj_small_dma_bf16_kernel(proj_args a) {
   for (int s = 0; s < n_st; ++s) {
     if (s + 2 < n_st) {
       A3_SM_ISSUE(slot2, 64 * (s + 2))
-      __builtin_amdgcn_s_waitcnt(vmcnt_imm(24));               // 12 loads per stage: stage s has landed
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * kSmLoads));     // stage s has landed: two younger ones may be on their way
     } else if (s + 1 < n_st) {
-      __builtin_amdgcn_s_waitcnt(vmcnt_imm(12));
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm(kSmLoads));
     } else {
       __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     }
@@ -579,13 +585,13 @@ proj_small_dma_bf16_kernel(proj_args a) {
       const int po = 16 * ((2 * u + lhi) ^ fswz);
       wf[u] = *reinterpret_cast<const bf16x8 *>(st + po);
       xa[u] = *reinterpret_cast<const bf16x8 *>(st + 4096 + po);
-      xb[u] = *reinterpret_cast<const bf16x8 *>(st + 8192 + po);
+      if (RB == 2) xb[u] = *reinterpret_cast<const bf16x8 *>(st + 8192 + po);
     }
     __builtin_amdgcn_sched_barrier(0);                         // all twelve reads in flight before the first MFMA
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[u], xa[u], acc[0], 0, 0, 0);
-      acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[u], xb[u], acc[1], 0, 0, 0);
+      if (RB == 2) acc[RB - 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[u], xb[u], acc[RB - 1], 0, 0, 0);
     }
     // the fragments are in registers before the next trip overwrites the slot read two trips ago
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -596,12 +602,12 @@ proj_small_dma_bf16_kernel(proj_args a) {
   // the wave's own ring is free now: it holds the wave's partial tile, [row block][register][lane]
   float *red = reinterpret_cast<float *>(ring);
 #pragma unroll
-  for (int tb = 0; tb < 2; ++tb)
+  for (int tb = 0; tb < RB; ++tb)
 #pragma unroll
     for (int r = 0; r < 16; ++r) red[(tb * 16 + r) * 64 + lane] = acc[tb][r];
   __syncthreads();
-  if (wave >= 2) return;
-  const int tb = wave;                                         // waves 0 and 1 finish one row block each
+  if (wave >= RB) return;
+  const int tb = wave;                                         // one wave per row block finishes it
   small_finish<4>(a, hs, sb, tok0 + tb * 32 + l32, lhi, reinterpret_cast<const float *>(lds) + tb * 16 * 64 + lane,
                   kSmRing * kSmStageBytes / 4);
 }
@@ -808,12 +814,20 @@ static a3_status proj_launch(const a3_layout *L, const void *hidden, const int *
       if (L->hidden % 256 == 0) {
         static bool small_attr_done = false;
         if (!small_attr_done) {
-          hipError_t e = hipFuncSetAttribute((const void *)proj_small_dma_bf16_kernel,
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSmLdsBytes);
-          if (e != hipSuccess) return a3_fail(A3_ERR_HIP, "a3_selected_qkv_proj: cannot raise the dynamic LDS limit");
+          hipError_t e = hipFuncSetAttribute((const void *)proj_small_dma_bf16_kernel<2>,
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm_lds_bytes(2));
+          hipError_t e1 = hipFuncSetAttribute((const void *)proj_small_dma_bf16_kernel<1>,
+                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm_lds_bytes(1));
+          if (e != hipSuccess || e1 != hipSuccess)
+            return a3_fail(A3_ERR_HIP, "a3_selected_qkv_proj: cannot raise the dynamic LDS limit");
           small_attr_done = true;
         }
-        hipLaunchKernelGGL(proj_small_dma_bf16_kernel, grid, dim3(256), kSmLdsBytes, st, a);
+        // workgroups that have an output: 4 per head of the tensors asked for, per 64 rows
+        const int heads_out = (q_out ? L->n_q_heads : 0) + (k_out ? L->n_kv_heads : 0) + (v_out ? L->n_kv_heads : 0);
+        if (4 * heads_out * (int)grid.y <= 128 && n_rows > 32)
+          hipLaunchKernelGGL(proj_small_dma_bf16_kernel<1>, dim3(grid.x, (n_rows + 31) / 32), dim3(256), sm_lds_bytes(1), st, a);
+        else
+          hipLaunchKernelGGL(proj_small_dma_bf16_kernel<2>, grid, dim3(256), sm_lds_bytes(2), st, a);
       } else if (L->hidden % 128 == 0) {
         hipLaunchKernelGGL(proj_small_bf16_kernel<2>, grid, dim3(128), 0, st, a);
       } else {

@@ -150,6 +150,18 @@ def test_selected_qkv_proj(name):
         assert max_abs_rel(to_host(q), wantq) <= tol(w)
         assert max_abs_rel(to_host(k), wantk) <= tol(w)
         assert max_abs_rel(to_host(v), wantv) <= tol(w)
+    # Q of the question rows alone (what the layer pass asks for first; few heads: the few-row kernel then runs
+    # with 32 rows per workgroup), and K and V alone
+    rows_np = res["q_rows"]
+    n = len(rows_np)
+    q = torch.zeros((n, s.n_q_heads, s.head_dim), dtype=api.torch_dtype(dt), device="cuda")
+    api.a3_selected_qkv_proj(lay, x, idev(rows_np), n, wq, None, None, q_out=q)
+    assert max_abs_rel(to_host(q), res["q_question"]) <= tol(w)
+    k = torch.zeros((n, s.n_kv_heads, s.head_dim), dtype=api.torch_dtype(dt), device="cuda")
+    v = torch.zeros_like(k)
+    api.a3_selected_qkv_proj(lay, x, idev(rows_np), n, None, wk, wv, k_out=k, v_out=v)
+    assert max_abs_rel(to_host(k), res["k_question"]) <= tol(w)
+    assert max_abs_rel(to_host(v), res["v_question"]) <= tol(w)
     # NULL row list = rows 0..n-1, only K requested, with a bias
     n = min(w.total_tokens, 150)
     bk_np = synth.round_to_storage(np.random.default_rng(9).standard_normal(s.n_kv_heads * s.head_dim), dt)
