@@ -14,9 +14,11 @@
  * Conventions shared by every entry point
  *   - Pointers named in a3_layout and every tensor / index argument are DEVICE pointers unless
  *     stated otherwise; the a3_layout struct itself lives in HOST memory.
- *   - Everything is allocated and freed by the caller.  The library allocates nothing, keeps no
- *     state between calls, and only enqueues kernels on `stream` (a hipStream_t, NULL = the
- *     null stream).  No call synchronises with the host or copies between host and device.
+ *   - Everything is allocated and freed by the caller.  The library allocates nothing and only
+ *     enqueues kernels on `stream` (a hipStream_t, NULL = the null stream).  No call synchronises
+ *     with the host or copies between host and device.  The only state kept between calls is
+ *     set-up that is done once per process and device (kernel attributes, the tuning knobs
+ *     listed at the end of this header, the address of a3_question_scores_noalloc's scratch array).
  *   - Tensors are dense row-major.  "packed rows": requests back to back, each request being
  *     its context chunks followed by its question tokens.  T = total_tokens.
  *       hidden            [T, hidden]
@@ -113,6 +115,19 @@ a3_status a3_rope_realign(const a3_layout *layout, const void *k_cat, void *k_fu
  * question rows are set to -inf.  ws: at least a3_workspace_bytes() bytes. */
 a3_status a3_question_scores(const a3_layout *layout, const void *q_question, const void *k_fused,
                              float *scores, void *ws, size_t ws_bytes, void *stream);
+
+/* a3_question_scores for callers that cannot allocate device memory or hand over a workspace: code running
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments (minus the
+ * workspace), same kernels, bit-identical scores.  The scratch memory the step needs lives in a fixed array of
+ * A3_SCORES_SCRATCH_BYTES inside the library's device image (each GPU the library runs on holds one until the
+ * process ends); the call allocates and frees nothing.  A batch that needs more (the need grows with
+ * n_req * max_q_len * n_q_heads * max_ctx_len / 256 and with n_kv_heads * total_tokens; the 16K-context
+ * Llama-3-8B layer takes 1.6 MB, the 32K-context Qwen2.5-7B layer 4.4 MB) is refused with A3_ERR_WORKSPACE
+ * before anything is launched.  All calls on one GPU share that GPU's array: calls that overlap in time on
+ * one GPU (different streams, different threads) race; calls on one stream are ordered and safe. */
+#define A3_SCORES_SCRATCH_BYTES (8u << 20)
+a3_status a3_question_scores_noalloc(const a3_layout *layout, const void *q_question, const void *k_fused,
+                                     float *scores, void *stream);
 
 /* Steps 1 and 2 in one call: Eq. 2 followed by Eq. 3, first line.  Same results as a3_rope_realign
  * (k_cat -> k_fused, bit for bit) followed by a3_question_scores on k_fused; on the bf16 path the first

@@ -20,7 +20,7 @@ A3_F32, A3_BF16 = 0, 1
 A3_ROPE_INTERLEAVED, A3_ROPE_HALF = 0, 1
 A3_POOL_MAX, A3_POOL_AVG = 0, 1
 
-EXPORTS = ["a3_workspace_bytes", "a3_layout_prepare", "a3_rope_realign", "a3_question_scores", "a3_realign_scores", "a3_topk_select",
+EXPORTS = ["a3_workspace_bytes", "a3_layout_prepare", "a3_rope_realign", "a3_question_scores", "a3_question_scores_noalloc", "a3_realign_scores", "a3_topk_select",
            "a3_selected_qkv_proj", "a3_selected_qkv_proj_scatter", "a3_kv_scatter", "a3_fused_attention", "a3_attention_plan", "a3_fused_attention_planned", "a3_active_rows",
            "a3_block_tail_ws_bytes", "a3_block_tail", "a3_rms_norm", "a3_question_scores_causal", "a3_window_votes",
            "a3_evict_ws_bytes", "a3_evict_select", "a3_evict_compact", "a3_value_deviation_scores",
@@ -71,6 +71,8 @@ def lib() -> C.CDLL:
     L.a3_rope_realign.argtypes = [P, V, V, V]
     L.a3_question_scores.argtypes = [P, V, V, V, V, C.c_size_t, V]
     L.a3_realign_scores.argtypes = [P, V, V, V, V, V, C.c_size_t, V]
+    L.a3_question_scores_noalloc.argtypes = [P, V, V, V, V]
+    L.a3_question_scores_noalloc.restype = I
     L.a3_topk_select.argtypes = [P, V, V, I, V, V, C.c_size_t, V]
     L.a3_selected_qkv_proj.argtypes = [P, V, V, I, V, V, V, V, V, V, V, V, V, V]
     L.a3_selected_qkv_proj_scatter.argtypes = [P, V, V, I, V, V, V, V, V, V, V, V, V, V]
@@ -225,6 +227,12 @@ def a3_question_scores(layout: Layout, q_question: torch.Tensor, k_fused: torch.
                        ws: torch.Tensor, stream=None) -> None:
     _check(lib().a3_question_scores(layout.ref, _ptr(q_question), _ptr(k_fused), _ptr(scores), _ptr(ws),
                                     ws.numel() if ws is not None else 0, _stream(stream)), "a3_question_scores")
+
+
+def a3_question_scores_noalloc(layout: Layout, q_question: torch.Tensor, k_fused: torch.Tensor, scores: torch.Tensor,
+                               stream=None) -> None:
+    _check(lib().a3_question_scores_noalloc(layout.ref, _ptr(q_question), _ptr(k_fused), _ptr(scores),
+                                            _stream(stream)), "a3_question_scores_noalloc")
 
 
 def a3_realign_scores(layout: Layout, q_question: torch.Tensor, k_cat: torch.Tensor, k_fused: torch.Tensor,

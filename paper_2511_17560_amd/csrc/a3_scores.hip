@@ -15,6 +15,8 @@
 // the L2 once per pass.  Pass B leaves one partial score per KV head; a last small kernel adds the
 // heads in order.  exp2 with log2(e) folded into the scale.
 // fp32: plain FMA kernels (correctness configuration).
+#include <mutex>
+
 #include "a3_internal.h"
 
 namespace {
@@ -599,6 +601,47 @@ extern "C" a3_status a3_realign_scores(const a3_layout *L, const void *q_questio
   if (k_cat == nullptr) return a3_fail(A3_ERR_INVALID_ARG, "a3_realign_scores: k_cat is NULL");
   if (!a3_aligned16(k_cat)) return a3_fail(A3_ERR_INVALID_ARG, "a3_realign_scores: tensors must be 16-byte aligned");
   return scores_launch(L, q_question, k_cat, k_fused, scores, ws, ws_bytes, stream);
+}
+
+// ---------------------------------------------------------------------------------------
+// a3_question_scores for callers that cannot allocate (code under graph capture, serving loops that forbid
+// it): the partial row statistics and per-head partial scores that a3_question_scores keeps in the caller's
+// workspace live in a fixed array of the library's own device image instead.  One array per GPU, shared by
+// every call on that GPU and holding the last call's contents; every word a call reads it has written itself
+// before, so nothing has to be cleared between calls.
+// ---------------------------------------------------------------------------------------
+constexpr size_t kScratchBytes = (size_t)A3_SCORES_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::once_flag scratch_once[kMaxDevices];
+void *scratch_ptr[kMaxDevices];          // device address of `scratch` on each GPU (the symbol itself is a host stand-in)
+hipError_t scratch_err[kMaxDevices];
+}  // namespace
+
+extern "C" a3_status a3_question_scores_noalloc(const a3_layout *L, const void *q_question, const void *k_fused,
+                                                float *scores, void *stream) {
+  a3_status s = a3_check_layout(L, "a3_question_scores_noalloc", true);
+  if (s != A3_OK) return s;
+  A3_REQUIRE(q_question && k_fused && scores, A3_ERR_INVALID_ARG, "a3_question_scores_noalloc: NULL tensor");
+  const size_t need = a3_scores_ws_bytes(L);
+  A3_REQUIRE(need <= kScratchBytes, A3_ERR_WORKSPACE,
+             "a3_question_scores_noalloc: this batch needs %zu bytes of scratch, the built-in array holds %zu "
+             "(use a3_question_scores with a workspace)", need, kScratchBytes);
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return a3_fail(A3_ERR_HIP, "a3_question_scores_noalloc: hipGetDevice: %s", hipGetErrorString(e));
+  A3_REQUIRE(dev >= 0 && dev < kMaxDevices, A3_ERR_UNSUPPORTED, "a3_question_scores_noalloc: device %d", dev);
+  // once per device, with that device current: each GPU holds its own copy of the array at its own address
+  std::call_once(scratch_once[dev], [dev]() {
+    void *p = nullptr;
+    scratch_err[dev] = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    scratch_ptr[dev] = scratch_err[dev] == hipSuccess ? p : nullptr;
+  });
+  if (scratch_err[dev] != hipSuccess || scratch_ptr[dev] == nullptr)
+    return a3_fail(A3_ERR_HIP, "a3_question_scores_noalloc: hipGetSymbolAddress: %s", hipGetErrorString(scratch_err[dev]));
+  return scores_launch(L, q_question, nullptr, const_cast<void *>(k_fused), scores, scratch_ptr[dev], kScratchBytes, stream);
 }
 
 // Eq. 3, first line, with the softmax of a question token taken over every key it sees: the context keys
