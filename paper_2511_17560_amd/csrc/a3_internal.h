@@ -29,6 +29,24 @@ static inline float a3_scale_of(const a3_layout *L) {
 }
 static inline size_t a3_align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// ---- set-up that has to happen once per device (kernel attributes): thread-safe, per device ----------
+#include <mutex>
+constexpr int kA3MaxDevices = 64;
+struct a3_once_per_device {
+  std::once_flag flag[kA3MaxDevices];
+  hipError_t err[kA3MaxDevices];
+};
+// runs fn() (returning a hipError_t) the first time it is called with the current device; returns what fn returned
+template <typename F>
+static inline hipError_t a3_once(a3_once_per_device &o, F fn) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kA3MaxDevices) return hipErrorInvalidDevice;
+  std::call_once(o.flag[dev], [&]() { o.err[dev] = fn(); });
+  return o.err[dev];
+}
+
 // ---- device-side numeric helpers ----------------------------------------------------------
 typedef __bf16 bf16_t;
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));

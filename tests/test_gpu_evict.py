@@ -17,7 +17,8 @@ from test_gpu_parity import ctx_of
 
 pytestmark = pytest.mark.gpu
 
-NAMES = ["cfg1", "ragged-bf16", "batched-bf16-half", "g7-bf16", "batched-f32-d128", "cfg2"]
+NAMES = ["cfg1", "ragged-bf16", "batched-bf16-half", "g7-bf16", "batched-f32-d128", "cfg2", "manyq-bf16",
+         "manyq-g7-bf16"]
 
 
 def _inputs(name):

@@ -39,6 +39,10 @@ def _workload(name):
         return synth.custom(SMALL_BF16_HALF, [[130, 70], [33], [257, 64, 90]], [5, 33, 12], ratio=(20, 100), seed=42)
     if name == "g7-bf16":
         return synth.custom(SMALL_G7, [[200, 150, 93]], [9], ratio=(25, 100), seed=43)
+    if name == "manyq-bf16":     # more than 256 (question token, head) rows per KV head: two row chunks in the scoring step
+        return synth.custom(SMALL_BF16, [[300, 129, 260]], [90], ratio=(10, 100), n_planted=2, seed=48)
+    if name == "manyq-g7-bf16":  # the same with 7 query heads per KV head, two requests, one of them with a single row chunk
+        return synth.custom(SMALL_G7, [[140, 200], [90]], [40, 11], ratio=(20, 100), seed=49)
     if name == "cfg3-layer0":    # the 16K benchmark configuration, first and last of its 32 independent layers
         return synth.config(3, layer=0)
     if name == "cfg3-layer31":
@@ -59,7 +63,8 @@ def _workload(name):
     raise KeyError(name)
 
 
-NAMES = ["cfg1", "cfg1-half", "ragged-bf16", "batched-bf16-half", "g7-bf16", "batched-f32-d128", "cfg2", "long-bf16"]
+NAMES = ["cfg1", "cfg1-half", "ragged-bf16", "batched-bf16-half", "g7-bf16", "batched-f32-d128", "cfg2", "long-bf16",
+         "manyq-bf16", "manyq-g7-bf16"]
 # full-size configurations: one oracle layer each takes tens of seconds, so each is built once and runs
 # the chained test and the teacher-forced tests of the three kernels whose behaviour depends on scale
 BIG_NAMES = ["cfg3-layer0", "cfg3-layer31", "cfg4", "cfg5"]
