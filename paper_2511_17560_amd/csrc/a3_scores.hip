@@ -36,13 +36,12 @@ struct scores_args {
   const void *k;            // [T, Hkv, d]
   const int *seg_start, *ctx_len, *q_len, *q_start;
   float2 *part;             // [n_tiles, total_rows] partial (max, sum) in the exp2 domain
-  float2 *stats;            // [total_rows] (max + log2(sum), unused)
+  float2 *stats;            // [total_rows] (max + log2(sum), unused): written by the combine kernel
+  int merged;               // bf16 path: the combine kernel has run (more than 32 runs of keys, rows in chunks, or
+                            // question keys in the denominator); otherwise the second pass merges the partials itself
   float *scores;            // [T]
   float *part_scores;       // [Hkv, T] bf16 path: per KV head partial scores
   int n_req, Hq, Hkv, d, T, total_rows, n_tiles, tile_keys;
-  int n_row_chunks;         // bf16 path: workgroups of 256 rows per KV head (1 unless max_q_len * G > 256)
-  float *votes;             // bf16 path, n_row_chunks > 1: [Hkv, T] per KV head sums (written by the head-sum kernel)
-  const int *tok_req;       // [T]
   uint32_t inv_G;           // ceil(2^32 / G) for G > 1: m / G = umulhi(m, inv_G) for every m < 2^32 / G
   float scale2;             // sm_scale * log2(e)
   float inv_scale2;
@@ -198,7 +197,9 @@ struct row_map {
   }
 };
 
-template <int PASS, bool REALIGN>
+// MULTI: more than 256 rows per KV head may occur (the host then makes runs of 256 keys, which stay in slots 0-3
+// while the row chunks pass by).
+template <int PASS, bool REALIGN, bool MULTI>
 __global__ void __launch_bounds__(kScoreThreads, 2)
 scores_bf16_kernel(scores_args a) {
   extern __shared__ __align__(16) unsigned char lds_raw[];
@@ -206,7 +207,6 @@ scores_bf16_kernel(scores_args a) {
   // holds that head's Q rows and partial statistics) ----------------------------------------------------
   const int g = blockIdx.x % a.Hkv;
   int rest = blockIdx.x / a.Hkv;
-  const int chunk = rest % a.n_row_chunks; rest /= a.n_row_chunks;
   const int t = rest % a.n_tiles, r = rest / a.n_tiles;
   // (a batch of one request: its lengths are the layout's maxima, known on the host; no loads before the first keys
   // are requested)
@@ -215,8 +215,8 @@ scores_bf16_kernel(scores_args a) {
   if (i0 >= N) return;
   const int G = a.Hq / a.Hkv;
   const int Mg = (a.one_ctx_len >= 0 ? a.one_q_len : a.q_len[r]) * G;   // rows of this KV head: m = j * G + hh
-  const int m_base = chunk * kChunkRows;
-  if (m_base >= Mg) return;
+  if (Mg <= 0) return;
+  const int n_row_chunks = MULTI ? (Mg + kChunkRows - 1) / kChunkRows : 1;
   const int s = a.one_ctx_len >= 0 ? 0 : a.seg_start[r], qrow0 = a.one_ctx_len >= 0 ? 0 : a.q_start[r];
   const row_map row_of{G, a.Hq, g, qrow0, a.inv_G};
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -250,22 +250,31 @@ scores_bf16_kernel(scores_args a) {
   const int dpiece = (lane & 15) ^ (drow & 15);                // (drow + 16 j) % 16 does not depend on j
 #define A3_KDMA(I)                                                                                             \
   _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                              \
-    const int row_ = min(s + i0 + (I) * kSlotKeys + drow + 16 * j, a.T - 1);   /* past the run: loaded, masked */ \
+    const int row_ = min(s + i0k + (I) * kSlotKeys + drow + 16 * j, a.T - 1);  /* past the run: loaded, masked */ \
     const bf16_t *gp_ = K + ((size_t)row_ * a.Hkv + g) * kD + dpiece * 8;                                      \
     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"                                         \
                  :: "s"(__builtin_amdgcn_readfirstlane(lds_base + ((I) & (kSlots - 1)) * kSlotBytes +           \
                                                        4 * (4 * j + (wave & 3)) * kKRowBytes)), "v"(gp_) : "memory"); \
   }
-  if (loads) {
+  // the Q tile: rows MBASE .. + 255 of this head (rows past Mg: a copy of the last row, ignored later)
+#define A3_QDMA(MBASE)                                                                                         \
+  _Pragma("unroll") for (int j = 0; j < 16; ++j) {                                                             \
+    const int m_ = min((MBASE) + drow + 16 * j, Mg - 1);                                                       \
+    const bf16_t *gp_ = Q + (size_t)row_of(m_) * kD + dpiece * 8;                                              \
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"                                         \
+                 :: "s"(__builtin_amdgcn_readfirstlane(lds_base + kLdsQ + 4 * (4 * j + wave) * kKRowBytes)), "v"(gp_) \
+                 : "memory");                                                                                  \
+  }
+  for (int chunk = 0; chunk < n_row_chunks; ++chunk) {
+  const int m_base = chunk * kChunkRows;
+  const bool first = !MULTI || chunk == 0;                      // later chunks find the keys in the ring and their Q tile on its way
+  // (what only the first chunk needs, the addresses of the keys, is formed from these copies: the compiler then
+  // leaves that arithmetic inside the iteration instead of keeping dozens of registers alive across the loop)
+  int i0k = i0, total_rows = a.total_rows;
+  if (MULTI) asm volatile("" : "+s"(i0k), "+s"(total_rows));
+  if (loads && first) {
     if (!REALIGN) { A3_KDMA(0) }
-#pragma unroll
-    for (int j = 0; j < 16; ++j) {                             // the Q tile: rows m_base .. + 255 of this head
-      const int m_ = min(m_base + drow + 16 * j, Mg - 1);      // rows past Mg: a copy of the last row, ignored later
-      const bf16_t *gp_ = Q + (size_t)row_of(m_) * kD + dpiece * 8;
-      asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
-                   :: "s"(__builtin_amdgcn_readfirstlane(lds_base + kLdsQ + 4 * (4 * j + wave) * kKRowBytes)), "v"(gp_)
-                   : "memory");
-    }
+    A3_QDMA(0)
     if (!REALIGN) {
       if (nQ > 1) { A3_KDMA(1) }
       if (nQ > 2) { A3_KDMA(2) }
@@ -273,36 +282,30 @@ scores_bf16_kernel(scores_args a) {
     }
   }
   // ---- PASS 1, waves 4-7: max + log2(sum exp) of the 256 rows from the partials of all runs (every workgroup
-  // of the row chunk forms the same numbers in the same order): first the maximum over the runs, then the
-  // sums rescaled to it, added in run order ------------------------------------------------------------
+  // of the row chunk forms the same numbers in the same order) --------------------------------------------
   if (PASS == 1 && wave >= 4) {
     const int ml = tid - 256, m = m_base + ml;
     float st = INFINITY;                                       // rows past Mg add nothing (see acc0 below)
     if (m < Mg) {
       const int row_id = row_of(m);
       const int runs = (N + a.tile_keys - 1) / a.tile_keys;
-      float mx = -INFINITY, z = 0.f;
-      if (runs <= 32 && !a.causal_q) {
+      if (a.merged) {
+        st = a.stats[row_id].x;                                // many runs: a small kernel has merged them already
+      } else {
+        // first the maximum over the runs, then the sums rescaled to it, added in run order (at most 32 runs)
+        float mx = -INFINITY, z = 0.f;
         float2 p[32];
 #pragma unroll
         for (int u = 0; u < 32; ++u)
-          p[u] = u < runs ? a.part[(size_t)u * a.total_rows + row_id] : make_float2(-INFINITY, 0.f);
+          p[u] = u < runs ? a.part[(size_t)u * total_rows + row_id] : make_float2(-INFINITY, 0.f);
 #pragma unroll
         for (int u = 0; u < 32; ++u) mx = fmaxf(mx, p[u].x);
         // a run that saw no key has (max, sum) = (-inf, 0): its factor must not become exp2(nan)
 #pragma unroll
         for (int u = 0; u < 32; ++u) z += p[u].y > 0.f ? p[u].y * fast_exp2(p[u].x - mx) : 0.f;
-      } else {
-        const int slots = runs + (a.causal_q ? 1 : 0);          // the question keys' share sits behind the last run
-        auto slot_of = [&](int u) { return u < runs ? u : a.n_tiles; };
-        for (int u = 0; u < slots; ++u) mx = fmaxf(mx, a.part[(size_t)slot_of(u) * a.total_rows + row_id].x);
-        for (int u = 0; u < slots; ++u) {
-          const float2 p = a.part[(size_t)slot_of(u) * a.total_rows + row_id];
-          z += p.y > 0.f ? p.y * fast_exp2(p.x - mx) : 0.f;
-        }
+        // exp2(l - m) / z = exp2(l - (m + log2 z)): one number per row
+        st = z > 0.f ? mx + log2f(z) : INFINITY;
       }
-      // exp2(l - m) / z = exp2(l - (m + log2 z)): one number per row
-      st = z > 0.f ? mx + log2f(z) : INFINITY;
     }
     St[ml] = st;
   }
@@ -328,18 +331,17 @@ scores_bf16_kernel(scores_args a) {
 #define A3_RLOAD(I, P)                                                                                         \
   {                                                                                                            \
     const int key_ = (I) * kSlotKeys + rkey;                                                                   \
-    const int row_ = min(s + i0 + key_, a.T - 1);                /* past the run: loaded, never stored */      \
+    const int row_ = min(s + i0k + key_, a.T - 1);               /* past the run: loaded, never stored */      \
     const size_t off_ = ((size_t)row_ * a.Hkv + g) * kD;                                                       \
     plo[P] = *reinterpret_cast<const bf16x8 *>(Kc + off_ + 8 * rc);                                            \
     phi[P] = *reinterpret_cast<const bf16x8 *>(Kc + off_ + 64 + 8 * rc);                                       \
     pchunk[P] = key_ < n_keys ? a.tok_chunk[row_] : -1;                                                        \
   }
-  // turns the registers of slot I and stores them; only the row chunk 0 workgroup writes the cache (all of a
-  // run's row chunks compute the same values)
+  // turns the registers of slot I and stores them
 #define A3_RSTORE(I, P)                                                                                        \
   {                                                                                                            \
     const int key_ = (I) * kSlotKeys + rkey;                                                                   \
-    const int row_ = min(s + i0 + key_, a.T - 1);                                                              \
+    const int row_ = min(s + i0k + key_, a.T - 1);                                                             \
     const size_t off_ = ((size_t)row_ * a.Hkv + g) * kD;                                                       \
     bf16x8 rlo = plo[P], rhi = phi[P];                                                                         \
     if (pchunk[P] >= 0) {                                                                                      \
@@ -365,7 +367,7 @@ scores_bf16_kernel(scores_args a) {
         }                                                                                                      \
       }                                                                                                        \
     }                                                                                                          \
-    if (key_ < n_keys && chunk == 0) {                                                                         \
+    if (key_ < n_keys) {                                                                                       \
       *reinterpret_cast<bf16x8 *>(Ko + off_ + 8 * rc) = rlo;                                                   \
       *reinterpret_cast<bf16x8 *>(Ko + off_ + 64 + 8 * rc) = rhi;                                              \
     }                                                                                                          \
@@ -392,7 +394,9 @@ scores_bf16_kernel(scores_args a) {
   }
 
   // ---- slot 0 and the Q tile have landed -------------------------------------------------------------
-  if (REALIGN) {
+  if (!first) {
+    if (loads) A3_VMCNT(0);                                    // the Q tile requested during the previous chunk
+  } else if (REALIGN) {
     // (in waves 0-3 the Q tile's loads are older than these: the compiler's wait for the keys of slot 0 covers them)
     A3_RLOAD(0, 0)
     if (nQ > 1) { A3_RLOAD(1, 1) }
@@ -418,9 +422,10 @@ scores_bf16_kernel(scores_args a) {
 #pragma unroll
     for (int x = 0; x < 16; ++x)     // PASS 1 lane: key; registers: rows 8 (x / 4) + 4 lhi + x % 4 of row block b
       acc0[b][x] = PASS == 1 ? -St[rg * 64 + b * 32 + 8 * (x >> 2) + 4 * lhi + (x & 3)] * a.inv_scale2 : 0.f;
-  if (nQ > 4) {
-    A3_LDS_BARRIER();                                          // everybody has its Q fragments: their place joins the ring
-    if (!REALIGN && loads) {
+  if (nQ > 4 || n_row_chunks > 1) {
+    A3_LDS_BARRIER();                                          // everybody has its Q fragments: their place is free
+    if (loads && chunk + 1 < n_row_chunks) { A3_QDMA(m_base + kChunkRows) }
+    if (!REALIGN && loads && first && nQ > 4) {                // ... and joins the ring
       A3_KDMA(4)
       if (nQ > 5) { A3_KDMA(5) }
       if (nQ > 6) { A3_KDMA(6) }
@@ -477,7 +482,10 @@ scores_bf16_kernel(scores_args a) {
         p1 += fast_exp2(acc[b][x + 1] * a.scale2);                                                             \
       }                                                                                                        \
       const float part_ = halves_sum(p0 + p1);                                                                 \
-      if (lhi == 0) red[rg * a.tile_keys + (I) * kSlotKeys + kh * 32 + l32] = part_;                           \
+      if (lhi == 0) {                                            /* this wave's own entries: chunk after chunk */ \
+        float *r_ = &red[rg * a.tile_keys + (I) * kSlotKeys + kh * 32 + l32];                                  \
+        *r_ = first ? part_ : *r_ + part_;                                                                     \
+      }                                                                                                        \
     }                                                                                                          \
   }
 
@@ -485,11 +493,13 @@ scores_bf16_kernel(scores_args a) {
   A3_LOGITS()
   if (kh == 0) { A3_FOLD(0) }
   for (int i = 0; i + 1 < nQ; ++i) {
-    if (REALIGN) { A3_RSTEP_STORE(i) } else if (loads) { A3_WAIT_SLOT(i) }
-    A3_LDS_BARRIER();                                          // slot i + 1 is in the ring
-    if (REALIGN) { A3_RSTEP_LOAD(i) }
-    // every wave has read slot i (its MFMAs were issued before the barrier): refill its place
-    else if (loads && i + kSlots < nQ) { A3_KDMA(i + kSlots) }
+    if (first) {                                               // (a later chunk: every slot is in the ring already)
+      if (REALIGN) { A3_RSTEP_STORE(i) } else if (loads) { A3_WAIT_SLOT(i) }
+      A3_LDS_BARRIER();                                        // slot i + 1 is in the ring
+      if (REALIGN) { A3_RSTEP_LOAD(i) }
+      // every wave has read slot i (its MFMAs were issued before the barrier): refill its place
+      else if (loads && i + kSlots < nQ) { A3_KDMA(i + kSlots) }
+    }
     A3_KFRAGS(i + 1)
     if (kh == 0) {
       A3_LOGITS()
@@ -528,6 +538,8 @@ scores_bf16_kernel(scores_args a) {
       }
     }
   }
+  }   // row chunks
+#undef A3_QDMA
 #undef A3_WAIT_SLOT
 #undef A3_RSTEP_LOAD
 #undef A3_RSTEP_STORE
@@ -538,7 +550,7 @@ scores_bf16_kernel(scores_args a) {
   if (PASS == 1) {
     __syncthreads();
     // column sums of this (KV head, row chunk): the four row groups in a fixed order
-    float *mine = a.part_scores + ((size_t)g * a.n_row_chunks + chunk) * a.T + s + i0;
+    float *mine = a.part_scores + (size_t)g * a.T + s + i0;
     for (int key = tid; key < n_keys; key += kScoreThreads)
       mine[key] = (red[key] + red[a.tile_keys + key]) + (red[2 * a.tile_keys + key] + red[3 * a.tile_keys + key]);
   }
@@ -546,27 +558,17 @@ scores_bf16_kernel(scores_args a) {
 #undef A3_VMCNT
 #undef A3_LDS_BARRIER
 
-// scores[t] = sum over KV heads (in head order) of that head's column sum, itself the sum over the request's row
-// chunks in order; question rows get -inf.  With several row chunks the per-head sums are also what the
-// eviction extension asks for (votes).
+// scores[t] = sum over KV heads of their column sums, in head order; question rows get -inf
 __global__ void __launch_bounds__(256)
 scores_head_sum_kernel(scores_args a, const int *__restrict__ tok_chunk) {
   const int t = blockIdx.x * 256 + threadIdx.x;
   if (t >= a.T) return;
-  float total = -INFINITY;
+  float v = -INFINITY;
   if (tok_chunk[t] >= 0) {
-    total = 0.f;
-    int chunks = 1;
-    if (a.n_row_chunks > 1) chunks = (a.q_len[a.tok_req[t]] * (a.Hq / a.Hkv) + kChunkRows - 1) / kChunkRows;
-    for (int g = 0; g < a.Hkv; ++g) {
-      const float *p = a.part_scores + (size_t)g * a.n_row_chunks * a.T + t;
-      float v = p[0];
-      for (int c = 1; c < chunks; ++c) v += p[(size_t)c * a.T];
-      if (a.votes) a.votes[(size_t)g * a.T + t] = v;
-      total += v;
-    }
+    v = 0.f;
+    for (int g = 0; g < a.Hkv; ++g) v += a.part_scores[(size_t)g * a.T + t];
   }
-  if (a.scores) a.scores[t] = total;
+  a.scores[t] = v;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -653,7 +655,10 @@ static int scores_row_chunks(const a3_layout *L) {
 // workgroups (one per CU at a time: 150 KB of LDS) fill the 256 CUs in as few, as full rounds as possible; a
 // workgroup's fixed cost (its Q tile, the merge of the partials, the start-up of the ring) is worth about 192 keys.
 static int scores_tile_keys_bf16(const a3_layout *L) {
-  const long long per_tile = (long long)L->n_req * L->n_kv_heads * scores_row_chunks(L);
+  // more than 256 rows per KV head: the keys of a run have to stay in four slots of the ring while the row chunks
+  // pass by
+  if (scores_row_chunks(L) > 1) return kMinTileKeys;
+  const long long per_tile = (long long)L->n_req * L->n_kv_heads;
   long long best_cost = -1;
   int best = kMinTileKeys;
   for (int tk = kMinTileKeys; tk <= kMaxTileKeys; tk += kSlotKeys) {
@@ -670,7 +675,7 @@ size_t a3_scores_ws_bytes(const a3_layout *L) {
   const int tk = L->dtype == A3_BF16 ? kMinTileKeys : kTileKeys;         // the most runs of keys either path can have
   const size_t n_tiles = (size_t)(L->max_ctx_len + tk - 1) / tk;
   return a3_align_up((n_tiles + 1) * total_rows * sizeof(float2), 256) + a3_align_up(total_rows * sizeof(float2), 256) +
-         a3_align_up((size_t)L->n_kv_heads * scores_row_chunks(L) * L->total_tokens * sizeof(float), 256) + 256;
+         a3_align_up((size_t)L->n_kv_heads * L->total_tokens * sizeof(float), 256) + 256;
 }
 
 // k_cat != nullptr: the first pass of the bf16 path also realigns (k_cat -> k_fused); the fp32 path runs the
@@ -697,28 +702,22 @@ static a3_status scores_launch(const a3_layout *L, const void *q_question, const
   const int n_tiles = (L->max_ctx_len + tk - 1) / tk;
   const int tk_min = bf16 ? kMinTileKeys : kTileKeys;
   const int max_tiles = (L->max_ctx_len + tk_min - 1) / tk_min;               // what the workspace is sized for
-  const int row_chunks = bf16 ? scores_row_chunks(L) : 1;
   a3_ws_cursor cur(ws, ws_bytes);
   scores_args a;
   a.q = q_question; a.k = k_fused;
   a.seg_start = L->seg_start; a.ctx_len = L->ctx_len; a.q_len = L->q_len; a.q_start = L->q_start;
   a.part = (float2 *)cur.take((size_t)(max_tiles + 1) * total_rows * sizeof(float2));
   a.stats = (float2 *)cur.take(total_rows * sizeof(float2));
-  a.part_scores = (float *)cur.take((size_t)L->n_kv_heads * row_chunks * L->total_tokens * sizeof(float));
-  a.votes = nullptr;
-  if (bf16) {
-    // one row chunk: a workgroup's column sums are the votes of its KV head
-    if (votes && row_chunks == 1) a.part_scores = votes; else a.votes = votes;
-  } else {
-    a.part_scores = votes;                                     // fp32 path adds the heads itself
-  }
-  a.tok_req = L->tok_req;
+  a.part_scores = (float *)cur.take((size_t)L->n_kv_heads * L->total_tokens * sizeof(float));
+  if (votes) a.part_scores = votes;                            // a KV head's column sums are its votes
+  else if (!bf16) a.part_scores = nullptr;                     // fp32 path adds the heads itself
   const int G = L->n_q_heads / L->n_kv_heads;
   a.inv_G = G > 1 ? (uint32_t)(((1ull << 32) + G - 1) / G) : 0u;
   a.causal_q = causal_q;
+  a.merged = 0;
   a.scores = scores;
   a.n_req = L->n_req; a.Hq = L->n_q_heads; a.Hkv = L->n_kv_heads; a.d = L->head_dim; a.T = L->total_tokens;
-  a.total_rows = (int)total_rows; a.n_tiles = n_tiles; a.tile_keys = tk; a.n_row_chunks = row_chunks;
+  a.total_rows = (int)total_rows; a.n_tiles = n_tiles; a.tile_keys = tk;
   a.scale2 = a3_scale_of(L) * kLog2e;
   a.inv_scale2 = 1.0f / a.scale2;
   const bool one = L->n_req == 1 && L->max_ctx_len + L->max_q_len == L->total_tokens;
@@ -739,22 +738,32 @@ static a3_status scores_launch(const a3_layout *L, const void *q_question, const
   if (bf16) {
     static a3_once_per_device lds_once;
     const hipError_t e = a3_once(lds_once, []() {
-      hipError_t e0 = hipFuncSetAttribute((const void *)scores_bf16_kernel<0, false>,
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)kScoresLds);
-      hipError_t e1 = hipFuncSetAttribute((const void *)scores_bf16_kernel<1, false>,
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)kScoresLds);
-      hipError_t e2 = hipFuncSetAttribute((const void *)scores_bf16_kernel<0, true>,
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)kScoresLds);
-      return e0 != hipSuccess ? e0 : (e1 != hipSuccess ? e1 : e2);
+      const void *fns[] = {(const void *)scores_bf16_kernel<0, false, false>, (const void *)scores_bf16_kernel<1, false, false>,
+                           (const void *)scores_bf16_kernel<0, true, false>, (const void *)scores_bf16_kernel<0, false, true>,
+                           (const void *)scores_bf16_kernel<1, false, true>, (const void *)scores_bf16_kernel<0, true, true>};
+      for (const void *fn : fns) {
+        const hipError_t e_ = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kScoresLds);
+        if (e_ != hipSuccess) return e_;
+      }
+      return hipSuccess;
     });
     if (e != hipSuccess) return a3_fail(A3_ERR_HIP, "a3_question_scores: cannot raise the dynamic LDS limit: %s", hipGetErrorString(e));
-    const long long wgs = (long long)L->n_req * n_tiles * row_chunks * L->n_kv_heads;
+    a.merged = (n_tiles > 32 || scores_row_chunks(L) > 1 || causal_q) ? 1 : 0;
+    const long long wgs = (long long)L->n_req * n_tiles * L->n_kv_heads;
     A3_REQUIRE(wgs < (1LL << 31), A3_ERR_UNSUPPORTED, "a3_question_scores: batch too large");
     const dim3 grid((unsigned)wgs);
-    if (fuse) hipLaunchKernelGGL((scores_bf16_kernel<0, true>), grid, dim3(kScoreThreads), kScoresLds, st, a);
-    else hipLaunchKernelGGL((scores_bf16_kernel<0, false>), grid, dim3(kScoreThreads), kScoresLds, st, a);
-    hipLaunchKernelGGL((scores_bf16_kernel<1, false>), grid, dim3(kScoreThreads), kScoresLds, st, a);
-    if (scores || a.votes)
+    if (scores_row_chunks(L) > 1) {
+      if (fuse) hipLaunchKernelGGL((scores_bf16_kernel<0, true, true>), grid, dim3(kScoreThreads), kScoresLds, st, a);
+      else hipLaunchKernelGGL((scores_bf16_kernel<0, false, true>), grid, dim3(kScoreThreads), kScoresLds, st, a);
+      hipLaunchKernelGGL(scores_combine_kernel, dim3((unsigned)((total_rows + 15) / 16)), dim3(256), 0, st, a);
+      hipLaunchKernelGGL((scores_bf16_kernel<1, false, true>), grid, dim3(kScoreThreads), kScoresLds, st, a);
+    } else {
+      if (fuse) hipLaunchKernelGGL((scores_bf16_kernel<0, true, false>), grid, dim3(kScoreThreads), kScoresLds, st, a);
+      else hipLaunchKernelGGL((scores_bf16_kernel<0, false, false>), grid, dim3(kScoreThreads), kScoresLds, st, a);
+      if (a.merged) hipLaunchKernelGGL(scores_combine_kernel, dim3((unsigned)((total_rows + 15) / 16)), dim3(256), 0, st, a);
+      hipLaunchKernelGGL((scores_bf16_kernel<1, false, false>), grid, dim3(kScoreThreads), kScoresLds, st, a);
+    }
+    if (scores)
       hipLaunchKernelGGL(scores_head_sum_kernel, dim3((L->total_tokens + 255) / 256), dim3(256), 0, st, a, L->tok_chunk);
   } else {
     const dim3 grid(n_tiles, L->n_req), cgrid((unsigned)((total_rows + 15) / 16));
