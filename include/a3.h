@@ -197,6 +197,17 @@ a3_status a3_fused_attention_planned(const a3_layout *layout, const void *q_act,
                                      const void *k_fused, const void *v_fused, void *out,
                                      void *ws, size_t ws_bytes, void *stream);
 
+/* Step 3, the row list [Re, Q] and the layout of the attention's work in one call (Eq. 3 second line; Eq. 4 /
+ * Eq. 5 act on the rows [Re, Q]): what a3_topk_select (-> sel_idx), a3_active_rows (-> act_idx) and
+ * a3_attention_plan (-> ws) give when called one after the other, bit for bit.  For a batch of one request it is a
+ * single launch: the workgroup that ranks the scores also writes the row list and the plan.  sel_idx: device
+ * int32 [total_k]; in a batch of one request it may be act_idx itself (the selection is the head of the row
+ * list).  act_idx: device int32 [n_act], n_act = total_k + sum q_len.  ws: at least
+ * a3_workspace_bytes(layout, n_act) bytes; a3_fused_attention_planned with the same act_idx, n_act and ws follows
+ * (nothing else may write ws in between). */
+a3_status a3_topk_select_plan(const a3_layout *layout, const float *scores, const int *sel_start, int total_k,
+                              int *sel_idx, int n_act, int *act_idx, void *ws, size_t ws_bytes, void *stream);
+
 /* Helper between steps 3 and 4: the active rows [Re, Q] of Eq. 4 / Eq. 5 in ascending packed order.
  * For request r, act_idx receives its k_r selected rows followed by its q_len[r] question rows, at
  * offset sel_start[r] + q_start[r].  sel_idx: device int32 [total_k] as written by a3_topk_select;
@@ -344,6 +355,18 @@ a3_status a3_rope_realign_q8(const a3_layout *layout, const void *cache_q8, void
                              void *stream);
 a3_status a3_chunk_cache_load_q8(const a3_layout *layout, const int *chunk_start_host, const int *chunk_len_host,
                                  int n_chunks, const void *const *host_q8, void *cache_q8, void *stream);
+
+/* ---- tuning values (for tests and measurements; the defaults are what the library picks by itself) -----------
+ * Process-wide integers, read when a call is made; value < 0 restores the library's own choice.  Names:
+ *   "attn_wgs"        workgroups (shares of the work) per KV head in a3_fused_attention, 1 .. 1024
+ *   "attn_item_cost"  start-up cost of a row tile, in 64-key steps, that the shares are balanced with, 0 .. 64
+ *   "proj_ntw"        row-tile width (2, 3, 4: 128, 192, 256 rows) of the projection GEMM; set, it also sends
+ *                     calls with few rows to that kernel instead of the weight-streaming one
+ *   "proj_k64"        0: the projection's main loop on 64-byte instead of 128-byte row pieces
+ *   "gemm_tb", "gemm_k64"   the same two for the GEMMs of a3_block_tail
+ * A value must not change between a3_attention_plan and the a3_fused_attention_planned calls that use its plan.
+ * Host only; A3_ERR_INVALID_ARG for an unknown name. */
+a3_status a3_set_tuning(const char *name, int value);
 
 const char *a3_strerror(a3_status status);
 /* Text of the last error raised on the calling thread ("" if none). */

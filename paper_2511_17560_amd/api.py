@@ -20,12 +20,12 @@ A3_F32, A3_BF16 = 0, 1
 A3_ROPE_INTERLEAVED, A3_ROPE_HALF = 0, 1
 A3_POOL_MAX, A3_POOL_AVG = 0, 1
 
-EXPORTS = ["a3_workspace_bytes", "a3_layout_prepare", "a3_rope_realign", "a3_question_scores", "a3_question_scores_noalloc", "a3_realign_scores", "a3_topk_select",
+EXPORTS = ["a3_workspace_bytes", "a3_layout_prepare", "a3_rope_realign", "a3_question_scores", "a3_question_scores_noalloc", "a3_realign_scores", "a3_topk_select", "a3_topk_select_plan",
            "a3_selected_qkv_proj", "a3_selected_qkv_proj_scatter", "a3_kv_scatter", "a3_fused_attention", "a3_attention_plan", "a3_fused_attention_planned", "a3_active_rows",
            "a3_block_tail_ws_bytes", "a3_block_tail", "a3_rms_norm", "a3_question_scores_causal", "a3_window_votes",
            "a3_evict_ws_bytes", "a3_evict_select", "a3_evict_compact", "a3_value_deviation_scores",
            "a3_select_chunk_edges", "a3_chunk_cache_load", "a3_rope_realign_q8", "a3_q8_row_bytes", "a3_quantize_q8",
-           "a3_chunk_cache_load_q8", "a3_chunk_file_read", "a3_strerror", "a3_last_error", "a3_version"]
+           "a3_chunk_cache_load_q8", "a3_chunk_file_read", "a3_set_tuning", "a3_strerror", "a3_last_error", "a3_version"]
 
 
 class A3Error(RuntimeError):
@@ -117,6 +117,10 @@ def lib() -> C.CDLL:
     for name in ("a3_realign_scores", "a3_selected_qkv_proj_scatter", "a3_active_rows", "a3_layout_prepare", "a3_rope_realign", "a3_question_scores", "a3_topk_select",
                  "a3_selected_qkv_proj", "a3_selected_qkv_proj_scatter", "a3_kv_scatter", "a3_fused_attention"):
         getattr(L, name).restype = I
+    L.a3_topk_select_plan.argtypes = [P, V, V, I, V, I, V, V, C.c_size_t, V]
+    L.a3_topk_select_plan.restype = I
+    L.a3_set_tuning.argtypes = [C.c_char_p, I]
+    L.a3_set_tuning.restype = I
     L.a3_strerror.restype = C.c_char_p
     L.a3_strerror.argtypes = [I]
     L.a3_last_error.restype = C.c_char_p
@@ -211,6 +215,10 @@ def a3_version() -> int:
     return lib().a3_version()
 
 
+def a3_set_tuning(name: str, value: int) -> None:
+    _check(lib().a3_set_tuning(name.encode(), int(value)), "a3_set_tuning")
+
+
 def a3_workspace_bytes(layout: Layout, max_active_rows: int) -> int:
     return int(lib().a3_workspace_bytes(layout.ref, int(max_active_rows)))
 
@@ -245,6 +253,13 @@ def a3_topk_select(layout: Layout, scores: torch.Tensor, sel_start: torch.Tensor
                    sel_idx: torch.Tensor, ws: Optional[torch.Tensor] = None, stream=None) -> None:
     _check(lib().a3_topk_select(layout.ref, _ptr(scores), _ptr(sel_start), int(total_k), _ptr(sel_idx), _ptr(ws),
                                 ws.numel() if ws is not None else 0, _stream(stream)), "a3_topk_select")
+
+
+def a3_topk_select_plan(layout: Layout, scores: torch.Tensor, sel_start: torch.Tensor, total_k: int,
+                        sel_idx: torch.Tensor, n_act: int, act_idx: torch.Tensor, ws: torch.Tensor, stream=None) -> None:
+    _check(lib().a3_topk_select_plan(layout.ref, _ptr(scores), _ptr(sel_start), int(total_k), _ptr(sel_idx), int(n_act),
+                                     _ptr(act_idx), _ptr(ws), ws.numel() if ws is not None else 0, _stream(stream)),
+           "a3_topk_select_plan")
 
 
 def a3_selected_qkv_proj(layout: Layout, hidden: torch.Tensor, row_idx: Optional[torch.Tensor], n_rows: int,

@@ -461,23 +461,23 @@ a3_status gemm_bf16_launch(const gemm_args &a0, hipStream_t st, const char *who)
   gemm_args a = a0;
   a.n_ftiles = EPI == EPI_RESID ? (a.N + 255) / 256 : (a.N + 127) / 128;
   int tb = pick_tb(a.n_rows, a.n_ftiles);
-  if (const char *e = getenv("A3_GEMM_TB")) { const int t = atoi(e); if (t >= 2 && t <= 4) tb = t; }   // tuning override
+  { const int t = a3_knob(A3_KNOB_GEMM_TB); if (t >= 2 && t <= 4) tb = t; }   // tuning value "gemm_tb"
   a.n_tok_tiles = (a.n_rows + 64 * tb - 1) / (64 * tb);
-  // 128-byte row pieces whenever K allows (tuning override A3_GEMM_K64=0: the 64-byte loop)
+  // 128-byte row pieces whenever K allows (tuning value "gemm_k64" = 0: the 64-byte loop)
   bool k64 = a.K % 64 == 0;
-  if (const char *e = getenv("A3_GEMM_K64")) k64 = k64 && atoi(e) != 0;
-  static bool attr_done = false;
-  if (!attr_done) {
+  if (a3_knob(A3_KNOB_GEMM_K64) == 0) k64 = false;
+  static a3_once_per_device lds_once;
+  const hipError_t once_err = a3_once(lds_once, []() {
     hipError_t e1 = hipFuncSetAttribute((const void *)gemm_bf16_kernel<2, EPI, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes(2));
     hipError_t e2 = hipFuncSetAttribute((const void *)gemm_bf16_kernel<3, EPI, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes(3));
     hipError_t e3 = hipFuncSetAttribute((const void *)gemm_bf16_kernel<4, EPI, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes(4));
     hipError_t e4 = hipFuncSetAttribute((const void *)gemm_bf16_kernel<3, EPI, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes_k64(3));
     hipError_t e5 = hipFuncSetAttribute((const void *)gemm_bf16_kernel<4, EPI, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes_k64(4));
     hipError_t e6 = hipFuncSetAttribute((const void *)gemm_bf16_kernel<2, EPI, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes_k64(2));
-    if (e1 != hipSuccess || e2 != hipSuccess || e3 != hipSuccess || e4 != hipSuccess || e5 != hipSuccess || e6 != hipSuccess)
-      return a3_fail(A3_ERR_HIP, "%s: cannot raise the dynamic LDS limit", who);
-    attr_done = true;
-  }
+    for (hipError_t e : {e1, e2, e3, e4, e5, e6}) if (e != hipSuccess) return e;
+    return hipSuccess;
+  });
+  if (once_err != hipSuccess) return a3_fail(A3_ERR_HIP, "%s: cannot raise the dynamic LDS limit", who);
   const unsigned grid = 8u * (unsigned)((a.n_ftiles + 7) / 8) * (unsigned)a.n_tok_tiles;
   if (tb == 2 && k64) hipLaunchKernelGGL((gemm_bf16_kernel<2, EPI, true>), dim3(grid), dim3(256), gemm_lds_bytes_k64(2), st, a);
   else if (tb == 2) hipLaunchKernelGGL((gemm_bf16_kernel<2, EPI, false>), dim3(grid), dim3(256), gemm_lds_bytes(2), st, a);

@@ -15,6 +15,21 @@
 
 static thread_local char g_last_error[512] = "";
 
+static std::atomic<int> g_knobs[A3_KNOB_COUNT] = {{-1}, {-1}, {-1}, {-1}, {-1}, {-1}};
+static const char *const kKnobNames[A3_KNOB_COUNT] = {"attn_wgs", "attn_item_cost", "proj_ntw", "proj_k64", "gemm_tb", "gemm_k64"};
+
+int a3_knob(int which) { return g_knobs[which].load(std::memory_order_relaxed); }
+
+extern "C" a3_status a3_set_tuning(const char *name, int value) {
+  A3_REQUIRE(name != nullptr, A3_ERR_INVALID_ARG, "a3_set_tuning: name is NULL");
+  for (int i = 0; i < A3_KNOB_COUNT; ++i)
+    if (strcmp(name, kKnobNames[i]) == 0) {
+      g_knobs[i].store(value < 0 ? -1 : value, std::memory_order_relaxed);
+      return A3_OK;
+    }
+  return a3_fail(A3_ERR_INVALID_ARG, "a3_set_tuning: unknown name '%s'", name);
+}
+
 a3_status a3_fail(a3_status code, const char *fmt, ...) {
   va_list ap;
   va_start(ap, fmt);

@@ -47,6 +47,18 @@ static inline hipError_t a3_once(a3_once_per_device &o, F fn) {
   return o.err[dev];
 }
 
+// ---- tuning values (a3_set_tuning): process-wide, -1 = the library's own choice ------------------------
+enum a3_knob {
+  A3_KNOB_ATTN_WGS = 0,        // workgroups (shares) per KV head in the attention plan
+  A3_KNOB_ATTN_ITEM_COST,      // start-up cost of a tile in the plan, in key steps
+  A3_KNOB_PROJ_NTW,            // row-tile width (2, 3, 4 x 64 rows) of the projection GEMM; also sends few rows there
+  A3_KNOB_PROJ_K64,            // 0: the projection's main loop on 64-byte row pieces
+  A3_KNOB_GEMM_TB,             // row-tile width of the GEMMs of H(.)
+  A3_KNOB_GEMM_K64,            // 0: their main loop on 64-byte row pieces
+  A3_KNOB_COUNT
+};
+int a3_knob(int which);
+
 // ---- device-side numeric helpers ----------------------------------------------------------
 typedef __bf16 bf16_t;
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));

@@ -808,20 +808,20 @@ static a3_status proj_launch(const a3_layout *L, const void *hidden, const int *
     a.n_pairs = (n_heads_total + 1) / 2;
     a.n_tok_tiles = 0;
     a.scatter_kv = scatter_kv;
-    if (n_rows <= 192 && L->hidden % 64 == 0 && !getenv("A3_PROJ_NTW")) {
+    const int ntw_knob = a3_knob(A3_KNOB_PROJ_NTW);            // tuning value "proj_ntw": the GEMM kernel in this width
+    if (n_rows <= 192 && L->hidden % 64 == 0 && ntw_knob < 0) {
       // few rows: stream the weights with 4 x n_heads x ceil(rows/64) small workgroups
       const dim3 grid(4 * n_heads_total, (n_rows + 63) / 64);
       if (L->hidden % 256 == 0) {
-        static bool small_attr_done = false;
-        if (!small_attr_done) {
+        static a3_once_per_device small_once;
+        const hipError_t once_err = a3_once(small_once, []() {
           hipError_t e = hipFuncSetAttribute((const void *)proj_small_dma_bf16_kernel<2>,
                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm_lds_bytes(2));
           hipError_t e1 = hipFuncSetAttribute((const void *)proj_small_dma_bf16_kernel<1>,
                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm_lds_bytes(1));
-          if (e != hipSuccess || e1 != hipSuccess)
-            return a3_fail(A3_ERR_HIP, "a3_selected_qkv_proj: cannot raise the dynamic LDS limit");
-          small_attr_done = true;
-        }
+          return e != hipSuccess ? e : e1;
+        });
+        if (once_err != hipSuccess) return a3_fail(A3_ERR_HIP, "a3_selected_qkv_proj: cannot raise the dynamic LDS limit");
         // workgroups that have an output: 4 per head of the tensors asked for, per 64 rows
         const int heads_out = (q_out ? L->n_q_heads : 0) + (k_out ? L->n_kv_heads : 0) + (v_out ? L->n_kv_heads : 0);
         if (4 * heads_out * (int)grid.y <= 128 && n_rows > 32)
@@ -839,7 +839,7 @@ static a3_status proj_launch(const a3_layout *L, const void *hidden, const int *
     // rows per workgroup: 128, 192 or 256.  Estimate each choice by (useful rows / padded rows) x (how
     // evenly the workgroups fill 256 CUs) x a bonus for the lower L2 traffic of larger tiles.
     int ntw = 2;
-    if (const char *e = getenv("A3_PROJ_NTW")) ntw = atoi(e);
+    if (ntw_knob >= 0) ntw = ntw_knob;
     else {
       double best = -1.0;
       for (int c = 2; c <= 4; ++c) {
@@ -857,20 +857,21 @@ static a3_status proj_launch(const a3_layout *L, const void *hidden, const int *
     if (ntw < 2 || ntw > 4) ntw = 2;
     a.n_tok_tiles = (n_rows + 64 * ntw - 1) / (64 * ntw);
     const unsigned grid = 8u * (unsigned)((a.n_pairs + 7) / 8) * (unsigned)a.n_tok_tiles;
-    // 128-byte row pieces for the 192- and 256-row tiles when the hidden size allows (tuning override A3_PROJ_K64)
+    // 128-byte row pieces for the 192- and 256-row tiles when the hidden size allows (tuning value "proj_k64" = 0:
+    // the 64-byte loop)
     bool k64 = ntw >= 3 && L->hidden % 64 == 0;
-    if (const char *e = getenv("A3_PROJ_K64")) k64 = k64 && atoi(e) != 0;
-    static bool attr_done = false;
-    if (!attr_done) {
+    if (a3_knob(A3_KNOB_PROJ_K64) == 0) k64 = false;
+    static a3_once_per_device lds_once;
+    const hipError_t once_err = a3_once(lds_once, []() {
       hipError_t e1 = hipFuncSetAttribute((const void *)proj_bf16_kernel<2, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)proj_lds_bytes(2));
       hipError_t e2 = hipFuncSetAttribute((const void *)proj_bf16_kernel<3, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)proj_lds_bytes(3));
       hipError_t e3 = hipFuncSetAttribute((const void *)proj_bf16_kernel<4, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)proj_lds_bytes(4));
       hipError_t e4 = hipFuncSetAttribute((const void *)proj_bf16_kernel<3, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)proj_lds_bytes_k64(3));
       hipError_t e5 = hipFuncSetAttribute((const void *)proj_bf16_kernel<4, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)proj_lds_bytes_k64(4));
-      if (e1 != hipSuccess || e2 != hipSuccess || e3 != hipSuccess || e4 != hipSuccess || e5 != hipSuccess)
-        return a3_fail(A3_ERR_HIP, "a3_selected_qkv_proj: cannot raise the dynamic LDS limit");
-      attr_done = true;
-    }
+      for (hipError_t e : {e1, e2, e3, e4, e5}) if (e != hipSuccess) return e;
+      return hipSuccess;
+    });
+    if (once_err != hipSuccess) return a3_fail(A3_ERR_HIP, "a3_selected_qkv_proj: cannot raise the dynamic LDS limit");
     if (ntw == 2) hipLaunchKernelGGL((proj_bf16_kernel<2, false>), dim3(grid), dim3(256), proj_lds_bytes(2), st, a);
     else if (ntw == 3 && k64) hipLaunchKernelGGL((proj_bf16_kernel<3, true>), dim3(grid), dim3(256), proj_lds_bytes_k64(3), st, a);
     else if (ntw == 3) hipLaunchKernelGGL((proj_bf16_kernel<3, false>), dim3(grid), dim3(256), proj_lds_bytes(3), st, a);

@@ -9,6 +9,7 @@
 // Requests of up to 36 K rows keep every key in a register of the lane that owns it (a contiguous
 // run of rows per lane); longer ones re-read the scores from global memory in every pass.
 #include "a3_internal.h"
+#include "a3_attn_plan.h"
 
 namespace {
 
@@ -166,9 +167,8 @@ topk_select_kernel(const float *__restrict__ scores, topk_problem prob, int *__r
 // ceil(N / 1024) <= KPT consecutive rows).  The scores are read once, coalesced, into LDS and
 // from there into the registers of their owners; every later step works on registers.
 template <int KPT>
-__global__ void __launch_bounds__(kBlock)
-topk_select_reg_kernel(const float *__restrict__ scores, topk_problem prob, int *__restrict__ sel_idx) {
-  extern __shared__ uint32_t keys[];                         // [N + N/32]
+__device__ __forceinline__ void topk_select_reg_body(const float *__restrict__ scores, const topk_problem &prob,
+                                                     int *__restrict__ sel_idx, uint32_t *keys /* LDS [N + N/32] */) {
   __shared__ uint32_t hist[256];
   __shared__ uint32_t wave_min[kWaves], wave_max[kWaves];
   __shared__ int wave_gt[kWaves], wave_eq[kWaves];
@@ -304,6 +304,34 @@ topk_select_reg_kernel(const float *__restrict__ scores, topk_problem prob, int 
   }
 }
 
+template <int KPT>
+__global__ void __launch_bounds__(kBlock)
+topk_select_reg_kernel(const float *__restrict__ scores, topk_problem prob, int *__restrict__ sel_idx) {
+  extern __shared__ uint32_t keys[];
+  topk_select_reg_body<KPT>(scores, prob, sel_idx, keys);
+}
+
+// Step 3, the active rows [Re, Q] and the layout of the attention's work in one launch, for a batch of one
+// request (one workgroup ranks it anyway): the selection goes to sel_idx and to the head of act_idx, the question
+// rows behind it, and the same workgroup then lays out the attention (a3_attn_plan.h) from the list it just wrote.
+template <int KPT>
+__global__ void __launch_bounds__(kBlock)
+topk_select_plan_kernel(const float *__restrict__ scores, topk_problem prob, int *__restrict__ sel_idx,
+                        int *act_idx, int n_act, attn_plan plan, int G, int wgs_per_head, int item_cost) {
+  extern __shared__ uint32_t keys[];
+  __shared__ int wave_tot[kPlanThreads / 64];
+  static_assert(kPlanThreads == kBlock, "one workgroup shape for both parts");
+  topk_select_reg_body<KPT>(scores, prob, sel_idx, keys);
+  __syncthreads();                                           // the selection is written (and has left this CU's L1 path)
+  const int k = prob.sel_start[1] - prob.sel_start[0], s = prob.seg_start[0], N = prob.ctx_len[0];
+  if (sel_idx != act_idx)
+    for (int i = threadIdx.x; i < k; i += kBlock) act_idx[i] = sel_idx[i];
+  for (int i = threadIdx.x; k + i < n_act; i += kBlock) act_idx[k + i] = s + N + i;   // the question rows
+  __threadfence_block();
+  __syncthreads();
+  attn_plan_body(plan, act_idx, n_act, prob.seg_start, 1, G, wgs_per_head, item_cost, wave_tot);
+}
+
 constexpr int kMaxLdsKeys = 36 * 1024;   // 148.5 KB of padded keys next to the small static arrays
 
 // One launch of the ranking kernels over grid (requests, heads).
@@ -312,16 +340,15 @@ a3_status topk_launch(const a3_layout *L, const float *scores, const topk_proble
   const dim3 grid(L->n_req, n_heads);
   if (L->max_ctx_len <= kMaxLdsKeys) {
     const size_t lds = ((size_t)L->max_ctx_len + L->max_ctx_len / 32 + 1) * sizeof(uint32_t);
-    static bool attr_done = false;
-    if (!attr_done) {
+    static a3_once_per_device lds_once;
+    const hipError_t once_err = a3_once(lds_once, []() {
       const int cap = (int)((kMaxLdsKeys + kMaxLdsKeys / 32 + 1) * sizeof(uint32_t));
       hipError_t e1 = hipFuncSetAttribute((const void *)topk_select_reg_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, cap);
       hipError_t e2 = hipFuncSetAttribute((const void *)topk_select_reg_kernel<16>, hipFuncAttributeMaxDynamicSharedMemorySize, cap);
       hipError_t e3 = hipFuncSetAttribute((const void *)topk_select_reg_kernel<36>, hipFuncAttributeMaxDynamicSharedMemorySize, cap);
-      if (e1 != hipSuccess || e2 != hipSuccess || e3 != hipSuccess)
-        return a3_fail(A3_ERR_HIP, "%s: cannot raise the dynamic LDS limit", who);
-      attr_done = true;
-    }
+      return e1 != hipSuccess ? e1 : (e2 != hipSuccess ? e2 : e3);
+    });
+    if (once_err != hipSuccess) return a3_fail(A3_ERR_HIP, "%s: cannot raise the dynamic LDS limit", who);
     const int per = (L->max_ctx_len + kBlock - 1) / kBlock;  // keys per lane of the longest request
     if (per <= 4) hipLaunchKernelGGL(topk_select_reg_kernel<4>, grid, dim3(kBlock), lds, st, scores, prob, sel_idx);
     else if (per <= 16) hipLaunchKernelGGL(topk_select_reg_kernel<16>, grid, dim3(kBlock), lds, st, scores, prob, sel_idx);
@@ -460,5 +487,64 @@ extern "C" a3_status a3_evict_compact(const a3_layout *L, const void *k_fused, c
                      (const uint4 *)k_fused, (const uint4 *)v_fused, keep_idx, total_keep, L->n_kv_heads, head_bytes / 16,
                      (uint4 *)k_out, (uint4 *)v_out);
   A3_CHECK_LAUNCH("a3_evict_compact");
+  return A3_OK;
+}
+
+// Step 3 -> the rows [Re, Q] -> the layout of the attention's work, as one call: what a3_topk_select,
+// a3_active_rows and a3_attention_plan do one after the other.  A batch of one request takes a single launch
+// (the workgroup that ranks the request goes on to write the row list and the plan); larger batches run the
+// three kernels.
+extern "C" a3_status a3_topk_select_plan(const a3_layout *L, const float *scores, const int *sel_start, int total_k,
+                                         int *sel_idx, int n_act, int *act_idx, void *ws, size_t ws_bytes,
+                                         void *stream) {
+  a3_status s = a3_check_layout(L, "a3_topk_select_plan", true);
+  if (s != A3_OK) return s;
+  A3_REQUIRE(total_k >= 0 && n_act >= total_k && n_act <= L->total_tokens, A3_ERR_INVALID_ARG,
+             "a3_topk_select_plan: total_k %d, n_act %d (of %d rows)", total_k, n_act, L->total_tokens);
+  A3_REQUIRE(scores && sel_start && act_idx && (sel_idx || total_k == 0), A3_ERR_INVALID_ARG,
+             "a3_topk_select_plan: NULL argument");
+  const bool one = L->n_req == 1 && L->dtype == A3_BF16 && L->max_ctx_len <= kMaxLdsKeys && total_k > 0 && n_act > 0;
+  if (!one) {
+    A3_REQUIRE(sel_idx != act_idx || L->n_req == 1, A3_ERR_INVALID_ARG,
+               "a3_topk_select_plan: sel_idx may only be act_idx itself in a batch of one request");
+    s = a3_topk_select(L, scores, sel_start, total_k, sel_idx, nullptr, 0, stream);
+    if (s != A3_OK) return s;
+    if (sel_idx == act_idx) {
+      // one request, selection already at the head of act_idx: only the question rows are missing
+      int *tmp = act_idx;   // a3_active_rows reads sel_idx[j] and writes act_idx[j] for the same j: in place is fine
+      s = a3_active_rows(L, tmp, sel_start, n_act, act_idx, stream);
+    } else {
+      s = a3_active_rows(L, sel_idx, sel_start, n_act, act_idx, stream);
+    }
+    if (s != A3_OK) return s;
+    return a3_attention_plan(L, act_idx, n_act, ws, ws_bytes, stream);
+  }
+  A3_REQUIRE((long long)total_k <= (long long)L->max_ctx_len, A3_ERR_INVALID_ARG,
+             "a3_topk_select_plan: total_k %d exceeds the number of context rows", total_k);
+  A3_REQUIRE(ws != nullptr && ws_bytes >= a3_attn_ws_bytes(L, n_act), A3_ERR_WORKSPACE,
+             "a3_topk_select_plan: workspace %zu bytes, need %zu", ws_bytes, a3_attn_ws_bytes(L, n_act));
+  attn_plan plan;
+  attn_plan_carve(L, n_act, ws, ws_bytes, &plan);
+  const topk_problem prob{L->seg_start, L->ctx_len, sel_start, nullptr, nullptr, 0, 0};
+  const size_t lds = ((size_t)L->max_ctx_len + L->max_ctx_len / 32 + 1) * sizeof(uint32_t);
+  static a3_once_per_device lds_once;
+  const hipError_t once_err = a3_once(lds_once, []() {
+    const int cap = (int)((kMaxLdsKeys + kMaxLdsKeys / 32 + 1) * sizeof(uint32_t));
+    hipError_t e1 = hipFuncSetAttribute((const void *)topk_select_plan_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, cap);
+    hipError_t e2 = hipFuncSetAttribute((const void *)topk_select_plan_kernel<16>, hipFuncAttributeMaxDynamicSharedMemorySize, cap);
+    hipError_t e3 = hipFuncSetAttribute((const void *)topk_select_plan_kernel<36>, hipFuncAttributeMaxDynamicSharedMemorySize, cap);
+    return e1 != hipSuccess ? e1 : (e2 != hipSuccess ? e2 : e3);
+  });
+  if (once_err != hipSuccess) return a3_fail(A3_ERR_HIP, "a3_topk_select_plan: cannot raise the dynamic LDS limit");
+  hipStream_t st = (hipStream_t)stream;
+  const int G = L->n_q_heads / L->n_kv_heads, wgs = plan.max_wgs, cost = attn_item_cost();
+  const int per = (L->max_ctx_len + kBlock - 1) / kBlock;
+  if (per <= 4)
+    hipLaunchKernelGGL(topk_select_plan_kernel<4>, dim3(1), dim3(kBlock), lds, st, scores, prob, sel_idx, act_idx, n_act, plan, G, wgs, cost);
+  else if (per <= 16)
+    hipLaunchKernelGGL(topk_select_plan_kernel<16>, dim3(1), dim3(kBlock), lds, st, scores, prob, sel_idx, act_idx, n_act, plan, G, wgs, cost);
+  else
+    hipLaunchKernelGGL(topk_select_plan_kernel<36>, dim3(1), dim3(kBlock), lds, st, scores, prob, sel_idx, act_idx, n_act, plan, G, wgs, cost);
+  A3_CHECK_LAUNCH("a3_topk_select_plan");
   return A3_OK;
 }

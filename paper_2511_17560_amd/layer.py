@@ -72,7 +72,7 @@ def make_buffers(layout: api.Layout, sel_start: np.ndarray, q_rows: np.ndarray, 
 
 def fuse_layer(layout: api.Layout, b: LayerBuffers, x_cur: torch.Tensor, k_cat: torch.Tensor, v_cache: torch.Tensor,
                wq: torch.Tensor, wk: torch.Tensor, wv: torch.Tensor, stream=None, fused_scatter: bool = True,
-               fused_realign: bool = True, overlap_plan: bool = False) -> None:
+               fused_realign: bool = True, overlap_plan: bool = False, fused_plan: bool = True) -> None:
     """Runs steps 1-5 for one layer.  ``k_cat`` is read, ``b.k_fused`` and ``v_cache`` (in place)
     hold the fused cache afterwards, ``b.out`` the attention output of the active rows.
 
@@ -80,6 +80,9 @@ def fuse_layer(layout: api.Layout, b: LayerBuffers, x_cur: torch.Tensor, k_cat: 
     caches (a3_selected_qkv_proj_scatter); otherwise the plain sequence a3_selected_qkv_proj ->
     a3_kv_scatter is used.  Both give the same cache, written after the scores were read.
     ``fused_realign`` (default) runs steps 1 and 2 as one call (a3_realign_scores).
+    ``fused_plan`` (default) runs the selection, the row list [Re, Q] and the layout of the attention's work as
+    one call (a3_topk_select_plan; a single launch for a batch of one request) and attends with
+    a3_fused_attention_planned; otherwise a3_topk_select, a3_active_rows and a3_fused_attention.
     ``overlap_plan`` has the attention's work laid out (a3_attention_plan, one small workgroup) on a second
     stream as soon as the active rows are known, beside the projection of the selected rows, and then calls
     a3_fused_attention_planned.  Off by default: on this hardware the two cross-stream waits cost more (about
@@ -95,11 +98,14 @@ def fuse_layer(layout: api.Layout, b: LayerBuffers, x_cur: torch.Tensor, k_cat: 
     else:
         api.a3_rope_realign(layout, k_cat, b.k_fused, stream=stream)
         api.a3_question_scores(layout, b.q_question, b.k_fused, b.scores, b.ws, stream=stream)
-    api.a3_topk_select(layout, b.scores, b.sel_start, k, b.sel_idx, stream=stream)
     rows, n_rows = b.act_idx, b.n_act
-    if not b.single:           # (a single request: act_idx = [selected | question], filled in place by the top-p)
-        api.a3_active_rows(layout, b.sel_idx, b.sel_start, b.n_act, b.act_idx, stream=stream)
-    overlap_plan = overlap_plan and b.side is not None
+    overlap_plan = overlap_plan and b.side is not None and not fused_plan
+    if fused_plan:
+        api.a3_topk_select_plan(layout, b.scores, b.sel_start, k, b.sel_idx, b.n_act, b.act_idx, b.ws, stream=stream)
+    else:
+        api.a3_topk_select(layout, b.scores, b.sel_start, k, b.sel_idx, stream=stream)
+        if not b.single:       # (a single request: act_idx = [selected | question], filled in place by the top-p)
+            api.a3_active_rows(layout, b.sel_idx, b.sel_start, b.n_act, b.act_idx, stream=stream)
     if overlap_plan:
         main = stream if stream is not None else torch.cuda.current_stream()
         b.ev_rows.record(main)
@@ -115,6 +121,7 @@ def fuse_layer(layout: api.Layout, b: LayerBuffers, x_cur: torch.Tensor, k_cat: 
         api.a3_kv_scatter(layout, b.k_act, b.v_act, b.act_idx, b.n_act, b.k_fused, v_cache, stream=stream)
     if overlap_plan:
         main.wait_event(b.ev_plan)
+    if overlap_plan or fused_plan:
         api.a3_fused_attention_planned(layout, b.q_act, b.act_idx, b.n_act, b.k_fused, v_cache, b.out, b.ws,
                                        stream=stream)
     else:

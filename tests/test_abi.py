@@ -209,3 +209,12 @@ def test_struct_layout_matches_header_order():
     body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
     fields = re.findall(r"\b\*?\s*([a-z_]+)\s*;", body)
     assert fields == [f[0] for f in api.a3_layout._fields_]
+
+
+def test_set_tuning_knows_its_names():
+    L = api.lib()
+    for name in (b"attn_wgs", b"attn_item_cost", b"proj_ntw", b"proj_k64", b"gemm_tb", b"gemm_k64"):
+        assert L.a3_set_tuning(name, 3) == api.A3_OK
+        assert L.a3_set_tuning(name, -1) == api.A3_OK
+    assert L.a3_set_tuning(b"no_such_value", 1) == api.A3_ERR_INVALID_ARG
+    assert L.a3_set_tuning(None, 1) == api.A3_ERR_INVALID_ARG

@@ -180,12 +180,12 @@ def test_selected_qkv_proj(name):
 @pytest.mark.parametrize("k64", ["1", "0"])
 @pytest.mark.parametrize("ntw", ["2", "3", "4"])
 @pytest.mark.parametrize("name", ["g7-bf16", "batched-bf16-half", "cfg2", "k64-bf16", "k128-bf16"])
-def test_selected_qkv_proj_every_tile_width(name, ntw, k64, monkeypatch):
+def test_selected_qkv_proj_every_tile_width(name, ntw, k64, tuning):
     """The large-tile GEMM kernel in each of its three workgroup shapes (the library normally
     picks one by row count; few rows go to the weight-streaming kernel instead), with the main loop on
     128-byte row pieces (the default for the two larger shapes) and on 64-byte pieces."""
-    monkeypatch.setenv("A3_PROJ_NTW", ntw)
-    monkeypatch.setenv("A3_PROJ_K64", k64)
+    tuning("proj_ntw", ntw)
+    tuning("proj_k64", k64)
     c = ctx_of(name)
     w, b, res, lay = c["w"], c["b"], c["res"], c["lay"]
     s, t = w.shape, b["t"]
@@ -301,15 +301,15 @@ def test_fused_attention(name):
 @pytest.mark.parametrize("wgs,item_cost", [("1", None), ("3", None), ("37", None), ("300", None), ("37", "0"),
                                            ("5", "64"), ("300", "1"), ("32", "30")])
 @pytest.mark.parametrize("name", ["ragged-bf16", "batched-bf16-half", "g7-bf16", "cfg2", "long-bf16"])
-def test_fused_attention_with_other_share_counts(name, wgs, item_cost, monkeypatch):
+def test_fused_attention_with_other_share_counts(name, wgs, item_cost, tuning):
     """The work of all tiles (key steps plus a start-up cost per tile) is cut into one equal share per
     workgroup of a KV head.  Other numbers of workgroups and other start-up costs move the cuts: none at
     all (1), a few long shares, many short ones (tiles cut into several items, items that start or end
     exactly on a tile boundary, cuts that fall into a tile's start-up units, rows that see nothing of a
     later item, ordered merge of the partial results)."""
-    monkeypatch.setenv("A3_ATTN_WGS", wgs)
+    tuning("attn_wgs", wgs)
     if item_cost is not None:
-        monkeypatch.setenv("A3_ATTN_ITEM_COST", item_cost)
+        tuning("attn_item_cost", item_cost)
     c = ctx_of(name)
     w, res, lay = c["w"], c["res"], c["lay"]
     s = w.shape
@@ -321,16 +321,63 @@ def test_fused_attention_with_other_share_counts(name, wgs, item_cost, monkeypat
     assert max_abs_rel(to_host(out), res["out"]) <= tol(w)
 
 
+@pytest.mark.parametrize("name", NAMES)
+def test_topk_select_plan_equals_the_three_calls(name):
+    """a3_topk_select_plan = a3_topk_select, a3_active_rows, a3_attention_plan: the same selection, the same row
+    list, and an attention that gives the same output bit for bit with either plan.  In a batch of one request
+    (one launch) the selection may be written straight into the head of the row list."""
+    c = ctx_of(name)
+    w, res, lay = c["w"], c["res"], c["lay"]
+    s = w.shape
+    dt = s.dtype
+    scores = torch.from_numpy(np.asarray(res["scores"], dtype=np.float32)).cuda()
+    n_act = w.total_k + w.total_q
+    k = w.total_k
+    sel_start = idev(w.sel_start)
+    q, kf, vf = to_dev(res["q_act"], dt), to_dev(res["k_fused"], dt), to_dev(res["v_fused"], dt)
+    # the three calls
+    sel3 = torch.full((max(k, 1),), -1, dtype=torch.int32, device="cuda")
+    act3 = torch.full((n_act,), -1, dtype=torch.int32, device="cuda")
+    ws3 = lay.workspace(n_act)
+    api.a3_topk_select(lay, scores, sel_start, k, sel3)
+    api.a3_active_rows(lay, sel3, sel_start, n_act, act3)
+    api.a3_attention_plan(lay, act3, n_act, ws3)
+    out3 = torch.zeros((n_act, s.n_q_heads, s.head_dim), dtype=api.torch_dtype(dt), device="cuda")
+    api.a3_fused_attention_planned(lay, q, act3, n_act, kf, vf, out3, ws3)
+    assert np.array_equal(act3.cpu().numpy(), res["act_idx"])
+    variants = [False] + ([True] if w.n_req == 1 else [])
+    for in_place in variants:
+        act1 = torch.full((n_act,), -1, dtype=torch.int32, device="cuda")
+        sel1 = act1 if in_place else torch.full((max(k, 1),), -1, dtype=torch.int32, device="cuda")
+        ws1 = lay.workspace(n_act)
+        ws1.fill_(0xAB)
+        api.a3_topk_select_plan(lay, scores, sel_start, k, sel1, n_act, act1, ws1)
+        out1 = torch.zeros_like(out3)
+        api.a3_fused_attention_planned(lay, q, act1, n_act, kf, vf, out1, ws1)
+        torch.cuda.synchronize()
+        assert torch.equal(act1, act3)
+        assert torch.equal(sel1[:k], sel3[:k])
+        assert torch.equal(out1, out3)
+    assert max_abs_rel(to_host(out3), res["out"]) <= tol(w)
+
+
+@pytest.mark.parametrize("name", ["cfg1", "ragged-bf16", "batched-bf16-half", "cfg2"])
+def test_chained_layer_separate_select_rows_plan(name):
+    """Same as test_chained_layer with a3_topk_select, a3_active_rows and a3_fused_attention instead of
+    a3_topk_select_plan and a3_fused_attention_planned."""
+    test_chained_layer(name, fused_plan=False)
+
+
 @pytest.mark.parametrize("name", ["cfg1", "ragged-bf16", "batched-bf16-half", "cfg2"])
 def test_chained_layer_plain_six_call_sequence(name):
     """Same as test_chained_layer, through the six plain calls: a3_rope_realign and a3_question_scores
     instead of a3_realign_scores, a3_selected_qkv_proj + a3_kv_scatter instead of the projection that
     writes into the caches."""
-    test_chained_layer(name, fused_scatter=False, fused_realign=False)
+    test_chained_layer(name, fused_scatter=False, fused_realign=False, fused_plan=False)
 
 
 @pytest.mark.parametrize("name", NAMES)
-def test_chained_layer(name, fused_scatter=True, fused_realign=True):
+def test_chained_layer(name, fused_scatter=True, fused_realign=True, fused_plan=True):
     """All steps on the GPU's own intermediates.  The selected set must equal the oracle's up to
     near-ties: a row in the symmetric difference must score within 1e-3 (relative) of the
     oracle's k-th score.  Planted rows must be selected.  Downstream tensors are compared on the
@@ -343,7 +390,8 @@ def test_chained_layer(name, fused_scatter=True, fused_realign=True):
     x = to_dev(t.x_cur, dt)
     k_cat, v_cache = to_dev(b["k_cat"], dt), to_dev(b["v_cat"], dt)
     wq, wk, wv = to_dev(t.wq, dt), to_dev(t.wk, dt), to_dev(t.wv, dt)
-    layer.fuse_layer(lay, bufs, x, k_cat, v_cache, wq, wk, wv, fused_scatter=fused_scatter, fused_realign=fused_realign)
+    layer.fuse_layer(lay, bufs, x, k_cat, v_cache, wq, wk, wv, fused_scatter=fused_scatter, fused_realign=fused_realign,
+                     fused_plan=fused_plan)
     torch.cuda.synchronize()
     got_act = bufs.act_idx.cpu().numpy()[:bufs.n_act]
     want_act = res["act_idx"]

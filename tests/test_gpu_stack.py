@@ -71,12 +71,12 @@ TAIL_CASES = {
 
 @pytest.mark.parametrize("case", ["bf16-small", "bf16-ragged-tiles", "bf16-llama"])
 @pytest.mark.parametrize("tb", ["2", "3", "4"])
-def test_block_tail_other_gemm_loops(case, tb, monkeypatch):
+def test_block_tail_other_gemm_loops(case, tb, tuning):
     """The GEMMs of H(.) with every row-tile width forced, and on the 64-byte-piece main loop (the library
     picks the width per GEMM and uses 128-byte pieces)."""
-    monkeypatch.setenv("A3_GEMM_TB", tb)
+    tuning("gemm_tb", tb)
     test_block_tail(case)
-    monkeypatch.setenv("A3_GEMM_K64", "0")
+    tuning("gemm_k64", 0)
     test_block_tail(case)
 
 
