@@ -1,7 +1,9 @@
 """Seeded synthetic workloads for the A^3 KV-cache fusion path.
 
-This module only draws random numbers and lays out index arrays.  It holds none of
-the method's arithmetic (no RoPE, no projection, no softmax, no selection): the
+A module of its own, owned neither by the HIP library's package nor by the CPU oracle: both are fed from it.
+It only draws random numbers and lays out index arrays.  It holds none of
+the method's arithmetic (no RoPE, no projection, no softmax, no selection, not even the number of recomputed
+tokens p = r * n of Eq. 3: whoever uses a workload says how that is counted, see ``use_recompute_count``): the
 stale per-chunk K/V cache and the planted relevant tokens are produced by whoever
 calls it (the tests do that with the CPU oracle, the benchmark draws the cache
 directly with a matched standard deviation).
@@ -21,6 +23,16 @@ from dataclasses import dataclass, field, replace
 from typing import List, Tuple
 
 import numpy as np
+
+_count_fn = None
+
+
+def use_recompute_count(fn) -> None:
+    """``fn(n_ctx, ratio_num, ratio_den) -> int``: how many context tokens of a request are recomputed (Eq. 3,
+    p = r * n).  The library's binding and the oracle each bring their own; ``Workload.sel_start`` calls it."""
+    global _count_fn
+    _count_fn = fn
+
 
 ROPE_INTERLEAVED = 0   # pairs (2i, 2i+1): the rotation matrix printed in "Position Recovery"
 ROPE_HALF = 1          # pairs (i, i+d/2): the layout common runtimes use for Llama/Qwen checkpoints
@@ -66,7 +78,7 @@ class Workload:
     chunk_len: np.ndarray = field(init=False)
     chunk_delta: np.ndarray = field(init=False)
     chunk_req: np.ndarray = field(init=False)
-    sel_start: np.ndarray = field(init=False)
+    _sel_start: object = field(init=False, default=None, repr=False)
 
     def __post_init__(self):
         R = len(self.chunk_lens)
@@ -95,10 +107,22 @@ class Workload:
         self.chunk_len = np.asarray(cl, dtype=np.int32)
         self.chunk_delta = np.asarray(cd, dtype=np.int32)
         self.chunk_req = np.asarray(cr, dtype=np.int32)
-        num, den = self.ratio
-        # p = r * n with n the request's context length, floor, in integer arithmetic
-        k = (ctx_len.astype(np.int64) * num) // den
-        self.sel_start = np.concatenate([[0], np.cumsum(k)]).astype(np.int32)
+
+    @property
+    def sel_start(self) -> np.ndarray:
+        """[R+1] offsets of the requests' selections in a packed list; the counts come from the function given
+        to ``use_recompute_count`` (this module does not know how p = r * n is rounded)."""
+        if self._sel_start is None:
+            if _count_fn is None:
+                raise RuntimeError("a3_synth.use_recompute_count(fn) has not been called")
+            num, den = self.ratio
+            k = [int(_count_fn(int(n), int(num), int(den))) for n in self.ctx_len]
+            self._sel_start = np.concatenate([[0], np.cumsum(k)]).astype(np.int32)
+        return self._sel_start
+
+    @sel_start.setter
+    def sel_start(self, value) -> None:
+        self._sel_start = np.asarray(value, dtype=np.int32)
 
     # ---- sizes -------------------------------------------------------------------
     @property

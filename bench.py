@@ -93,31 +93,44 @@ def measured_traffic(workload_name):
 
 
 def cpu_baseline(cfg, max_seconds=60.0):
-    """The CPU oracle, as it is, on one layer of the same configuration (host cores)."""
+    """The CPU oracle, as it is (float64 NumPy), on layers of the same configuration, on the host's cores; plus
+    the time of one layer of configurations 1 and 2 with the BLAS pool held to one thread."""
     import numpy as np
-    from threadpoolctl import threadpool_info
+    from threadpoolctl import threadpool_info, threadpool_limits
     from oracle import a3_oracle as ora
     from oracle import workload as wl
-    from paper_2511_17560_amd import synth
+    import a3_synth as synth
 
-    dt, n_layers, n_sel = 0.0, 0, 0
-    for layer_i in range(3):                     # three of the 32 layers: about 10 s of CPU work
-        w = synth.config(cfg, layer=layer_i)
+    def one_layer(w):
         t = synth.draw_tensors(w)
         k_cat, v_cat = synth.draw_cache(w, "k"), synth.draw_cache(w, "v")
         t0 = time.perf_counter()
         res = ora.fuse_layer(t.x_cur, k_cat, v_cat, t.wq, t.wk, t.wv, **wl.layout_kwargs(w))
-        dt += time.perf_counter() - t0
+        return time.perf_counter() - t0, int(len(res["sel_idx"]))
+
+    dt, n_layers, n_sel = 0.0, 0, 0
+    for layer_i in range(3):                     # three of the 32 layers: about 10 s of CPU work
+        w = synth.config(cfg, layer=layer_i)
+        sec, n_sel = one_layer(w)
+        dt += sec
         n_layers += 1
-        n_sel = int(len(res["sel_idx"]))
         if dt > max_seconds:
             break
     threads = max([p.get("num_threads", 1) for p in threadpool_info() if p.get("user_api") == "blas"] + [1])
+    single = {}
+    with threadpool_limits(limits=1):
+        for c in (1, 2):
+            single[f"cfg{c}"] = round(one_layer(synth.config(c))[0], 3)
+    try:
+        usable = len(os.sched_getaffinity(0))
+    except AttributeError:
+        usable = os.cpu_count()
     return {
         "value": n_layers * w.total_ctx / dt, "unit": "fused-context tokens/s/layer", "cores": int(threads), "kind": "oracle",
         "sample": f"{n_layers} of the 32 layers of {w.name} (float64 NumPy oracle, all steps, stale cache drawn directly), "
                   f"{dt:.1f} s wall",
-        "seconds": dt, "n_selected": n_sel,
+        "seconds": dt, "n_selected": n_sel, "oracle_dtype": "float64", "nproc": os.cpu_count(), "usable_cpus": usable,
+        "blas_threads": int(threads), "one_thread_seconds_per_layer": single,
     }
 
 
@@ -128,7 +141,9 @@ def stack_main(args):
     the matched standard deviation)."""
     import numpy as np
     import torch
-    from paper_2511_17560_amd import api, stack, synth
+    import a3_synth as synth
+    from paper_2511_17560_amd import api, stack
+    synth.use_recompute_count(api.a3_recompute_count)
 
     w = synth.config(args.config)
     s = w.shape
@@ -318,7 +333,9 @@ def main():
 
     import numpy as np
     import torch
-    from paper_2511_17560_amd import api, layer, synth
+    import a3_synth as synth
+    from paper_2511_17560_amd import api, layer
+    synth.use_recompute_count(api.a3_recompute_count)
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     api.lib()                                   # fail loudly if the HIP library is missing
@@ -345,20 +362,45 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    # set-up, outside the warm-up / steps accounting: every buffer set is run once, so that first-use costs (page
+    # mappings of the 32 sets, kernel attributes) do not land in the timed region when --warmup is small
+    for i in range(n_layers):
+        step(i)
+    torch.cuda.synchronize()
+
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
 
-    # ---- timed region: exactly --steps steps; events bracket the dominant call inside it ----
+    # ---- timed region: exactly --steps steps.  Inside it the dominant call is bracketed twice on the stream the
+    # kernels run on: torch events around the whole a3_fused_attention_planned call (main kernel + the kernel that
+    # merges partial results; the work layout was made by a3_topk_select_plan), raw HIP events recorded by the
+    # library right before / after the main kernel alone.
+    import ctypes
+    hip = ctypes.CDLL("libamdhip64.so")
+
+    def raw_event():
+        e = ctypes.c_void_p()
+        assert hip.hipEventCreate(ctypes.byref(e)) == 0
+        return e
+
+    def raw_elapsed_ms(e0, e1):
+        ms = ctypes.c_float()
+        assert hip.hipEventElapsedTime(ctypes.byref(ms), e0, e1) == 0
+        return ms.value
+
     attn_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-    attn_name = "a3_fused_attention"
+    main_ev = [(raw_event(), raw_event()) for _ in range(args.steps)]
+    attn_name = "a3_fused_attention_planned"
     orig_attn = getattr(api, attn_name)
     cur = {"i": 0}
 
-    def timed_attn(*a, **kw):
+    def timed_attn(layout, q_act, act_idx, n_act, k_fused, v_fused, out, ws, stream=None):
         e0, e1 = attn_ev[cur["i"]]
+        m0, m1 = main_ev[cur["i"]]
         e0.record()
-        orig_attn(*a, **kw)
+        api.a3_fused_attention_planned_events(layout, q_act, act_idx, n_act, k_fused, v_fused, out, ws, m0.value, m1.value,
+                                              stream=stream)
         e1.record()
 
     setattr(api, attn_name, timed_attn)
@@ -371,6 +413,10 @@ def main():
     elapsed = time.perf_counter() - t0
     setattr(api, attn_name, orig_attn)
     attn_ms = float(np.mean([a.elapsed_time(b) for a, b in attn_ev]))
+    attn_main_ms = float(np.mean([raw_elapsed_ms(a, b) for a, b in main_ev]))
+    for a, b in main_ev:
+        hip.hipEventDestroy(a)
+        hip.hipEventDestroy(b)
 
     # ---- the same steps on two streams, alternately (outside the timed region) -----------------
     two_streams_ms = None
@@ -396,7 +442,8 @@ def main():
     # straight into the caches) and once with the plain six-call sequence (a3_rope_realign,
     # a3_question_scores, a3_selected_qkv_proj + a3_kv_scatter), so every entry point is reported
     names = ["a3_selected_qkv_proj", "a3_selected_qkv_proj_scatter", "a3_rope_realign", "a3_question_scores", "a3_realign_scores",
-             "a3_topk_select", "a3_active_rows", "a3_kv_scatter", "a3_fused_attention"]
+             "a3_topk_select", "a3_topk_select_plan", "a3_active_rows", "a3_kv_scatter", "a3_fused_attention",
+             "a3_fused_attention_planned"]
     originals = {n: getattr(api, n) for n in names}
     reps = min(args.steps, 2 * n_layers)
 
@@ -417,7 +464,7 @@ def main():
         for i in range(reps):
             L, B = layers[i % n_layers], bufs[i % n_layers]
             layer.fuse_layer(lay, B, L["x"], L["k_cat"], L["v"], L["wq"], L["wk"], L["wv"], fused_scatter=fused,
-                             fused_realign=fused)
+                             fused_realign=fused, fused_plan=fused)
         torch.cuda.synchronize()
         for n in names:
             setattr(api, n, originals[n])
@@ -456,7 +503,8 @@ def main():
     work = algorithmic_work(w, pos)
     ms_per_step = elapsed * 1e3 / args.steps
     value = w.total_ctx / (ms_per_step * 1e-3)
-    attn_tflops = work["attn_flops"] / (attn_ms * 1e-3) / 1e12
+    attn_tflops = work["attn_flops"] / (attn_main_ms * 1e-3) / 1e12          # the main kernel alone
+    attn_call_tflops = work["attn_flops"] / (attn_ms * 1e-3) / 1e12          # main kernel + merge of partial results
     derived = {
         "realign_GBs": work["realign_bytes"] / (per_call_plain["a3_rope_realign"]["us_per_step"] * 1e-6) / 1e9,
         "scores_GBs": work["scores_bytes"] / (per_call_plain["a3_question_scores"]["us_per_step"] * 1e-6) / 1e9,
@@ -467,8 +515,8 @@ def main():
         "proj_TFLOPs": work["proj_flops"] / ((per_call_us["a3_selected_qkv_proj_scatter"]["us_per_step"] +
                                                per_call_us["a3_selected_qkv_proj"]["us_per_step"]) * 1e-6) / 1e12,
         "attn_TFLOPs": work["attn_flops"] / (per_call_us[attn_name]["us_per_step"] * 1e-6) / 1e12,
-        # both passes form every logit once
-        "scores_TFLOPs": 2 * work["scores_flops"] / (per_call_plain["a3_question_scores"]["us_per_step"] * 1e-6) / 1e12,
+        # the method's own work: one Q K^T (the two passes of the kernel form every logit twice)
+        "scores_TFLOPs": work["scores_flops"] / (per_call_plain["a3_question_scores"]["us_per_step"] * 1e-6) / 1e12,
         "plain_copy_same_size_GBs": copy_gbs,
         # the same steps issued alternately on two streams (the layer problems of this workload are independent
         # of each other): what the launch floors of the dozen small kernels of a step cost when nothing fills them.
@@ -484,9 +532,15 @@ def main():
         "config": {"workload": w.name, "ctx_tokens": w.total_ctx, "question_tokens": w.total_q,
                    "selected_tokens": w.total_k, "layers_cycled": n_layers, "requests": w.n_req,
                    "shape": f"h{s.hidden}/Hq{s.n_q_heads}/Hkv{s.n_kv_heads}/d{s.head_dim}"},
-        "roofline": {"bound": "mfma", "kernel": "a3_fused_attention (attn_bf16_kernel)", "achieved": attn_tflops,
-                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": attn_tflops / PEAK_BF16_TFLOPS,
-                     "traffic": measured_traffic(w.name), "avg_launch_ms": attn_ms, "flops_per_launch": work["attn_flops"]},
+        # `achieved` / `frac`: the dominant kernel alone (attn_bf16_kernel, HIP events recorded by the library around it
+        # inside the timed region); `whole_call_*`: the a3_fused_attention_planned call (that kernel plus the merge
+        # of partial results)
+        "roofline": {"bound": "mfma", "kernel": "attn_bf16_kernel (main kernel of a3_fused_attention_planned)",
+                     "achieved": attn_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": attn_tflops / PEAK_BF16_TFLOPS, "frac_is": "main kernel alone",
+                     "traffic": measured_traffic(w.name), "avg_launch_ms": attn_main_ms,
+                     "flops_per_launch": work["attn_flops"], "whole_call_ms": attn_ms,
+                     "whole_call_achieved": attn_call_tflops, "whole_call_frac": attn_call_tflops / PEAK_BF16_TFLOPS},
         "per_call_us": per_call_us,
         "per_call_us_plain_sequence": per_call_plain,
         "derived": {k: (None if v is None else round(v, 2)) for k, v in derived.items()},

@@ -138,6 +138,11 @@ a3_status a3_question_scores_noalloc(const a3_layout *layout, const void *q_ques
 a3_status a3_realign_scores(const a3_layout *layout, const void *q_question, const void *k_cat, void *k_fused,
                             float *scores, void *ws, size_t ws_bytes, void *stream);
 
+/* Eq. 3, p = r * n: the number of context tokens of a request that are recomputed, n = n_ctx its context length
+ * (question tokens are always recomputed and are no candidates), r = ratio_num / ratio_den in [0, 1], rounded down
+ * in integer arithmetic.  Host only; -1 on a bad argument.  The caller sums these into sel_start. */
+int a3_recompute_count(int n_ctx, int ratio_num, int ratio_den);
+
 /* Step 3, Eq. 3 second line (Re = top_p(s)).  For request r the k_r = sel_start[r+1] -
  * sel_start[r] context rows with the largest scores; equal scores go to the lowest row;
  * sel_idx[sel_start[r] .. sel_start[r+1]) receives packed rows in ascending order.
@@ -196,6 +201,14 @@ a3_status a3_attention_plan(const a3_layout *layout, const int *act_idx, int n_a
 a3_status a3_fused_attention_planned(const a3_layout *layout, const void *q_act, const int *act_idx, int n_act,
                                      const void *k_fused, const void *v_fused, void *out,
                                      void *ws, size_t ws_bytes, void *stream);
+
+/* a3_fused_attention_planned for measurements: ev_main_begin / ev_main_end are hipEvent_t handles the caller created
+ * (either may be NULL); they are recorded on the stream right before and right after the main attention kernel, so
+ * their distance is that kernel's duration alone (the small kernel that merges partial results runs after the
+ * second one).  Everything else as a3_fused_attention_planned. */
+a3_status a3_fused_attention_planned_events(const a3_layout *layout, const void *q_act, const int *act_idx, int n_act,
+                                            const void *k_fused, const void *v_fused, void *out, void *ws,
+                                            size_t ws_bytes, void *stream, void *ev_main_begin, void *ev_main_end);
 
 /* Step 3, the row list [Re, Q] and the layout of the attention's work in one call (Eq. 3 second line; Eq. 4 /
  * Eq. 5 act on the rows [Re, Q]): what a3_topk_select (-> sel_idx), a3_active_rows (-> act_idx) and
@@ -305,6 +318,10 @@ a3_status a3_value_deviation_scores(const a3_layout *layout, const void *v_true,
  * total_k = sel_start[n_req] (host value). */
 a3_status a3_select_chunk_edges(const a3_layout *layout, int n_head, int n_tail, const int *sel_start, int total_k,
                                 int *sel_idx, void *stream);
+/* The sel_start that rule needs, from HOST copies of the layout's arrays: sel_start[r+1] - sel_start[r] = sum over the
+ * chunks of request r of min(chunk_len, n_head + n_tail).  sel_start: host int32 [n_req + 1].  Host only. */
+a3_status a3_chunk_edge_sel_start(int n_req, const int *seg_start, const int *ctx_len, int n_chunks,
+                                  const int *chunk_start, const int *chunk_len, int n_head, int n_tail, int *sel_start);
 
 /* ---- chunk-cache staging (Eq. 1's per-chunk K/V store lives outside the GPU; the paper names loading it as
  * the method's limitation) ---------------------------------------------------------------------------------

@@ -180,6 +180,21 @@ def question_scores(q_question, k_fused, seg_start, ctx_len, q_len, sm_scale, dt
 # step 3: Re = top_p(s), second line of Eq. 3
 # ---------------------------------------------------------------------------------------
 
+def recompute_count(n_ctx: int, ratio_num: int, ratio_den: int) -> int:
+    """Eq. 3, p = r * n: the number of context tokens of a request that are recomputed.  n is the request's
+    context length (its question tokens are always recomputed and are no candidates), r = ratio_num / ratio_den
+    exactly, and p is rounded down."""
+    from fractions import Fraction
+    import math
+    return math.floor(Fraction(int(ratio_num), int(ratio_den)) * int(n_ctx))
+
+
+def sel_start_from_ratio(ctx_len, ratio_num: int, ratio_den: int) -> np.ndarray:
+    """[R+1] offsets of the requests' selections in a packed list: running sum of recompute_count."""
+    k = [recompute_count(int(n), ratio_num, ratio_den) for n in ctx_len]
+    return np.concatenate([[0], np.cumsum(k)]).astype(np.int32)
+
+
 def topk_select(scores, seg_start, ctx_len, sel_start):
     """Per request, the packed rows of the k largest context scores (k = sel_start[r+1] -
     sel_start[r]); equal scores go to the lowest index; rows are returned ascending.

@@ -9,7 +9,7 @@ from __future__ import annotations
 
 import numpy as np
 
-from paper_2511_17560_amd import synth
+import a3_synth as synth
 from . import a3_oracle as ora
 
 
@@ -20,7 +20,8 @@ def sm_scale_of(w: synth.Workload) -> float:
 def layout_kwargs(w: synth.Workload) -> dict:
     s = w.shape
     return dict(seg_start=w.seg_start, ctx_len=w.ctx_len, q_len=w.q_lens, chunk_start=w.chunk_start,
-                chunk_len=w.chunk_len, chunk_delta=w.chunk_delta, sel_start=w.sel_start,
+                chunk_len=w.chunk_len, chunk_delta=w.chunk_delta,
+                sel_start=ora.sel_start_from_ratio(w.ctx_len, *w.ratio),       # the oracle's own count (Eq. 3, p = r n)
                 positions=w.token_positions(), n_q_heads=s.n_q_heads, n_kv_heads=s.n_kv_heads,
                 head_dim=s.head_dim, base=s.rope_base, layout=s.rope_layout,
                 sm_scale=sm_scale_of(w), storage=s.dtype)

@@ -2,9 +2,8 @@
 
 ``api``   ctypes binding of liba3.so (HIP kernels behind a C ABI, see include/a3.h)
 ``layer`` the call sequence of one layer on preallocated buffers
-``synth`` seeded synthetic workloads (index layout and random draws only)
 ``build`` compiles liba3.so with hipcc for gfx950
 
 Importing the package does not load the library; ``api.lib()`` does, and raises if it is missing.
 """
-__all__ = ["api", "layer", "synth", "build"]
+__all__ = ["api", "layer", "build"]

@@ -21,11 +21,11 @@ A3_ROPE_INTERLEAVED, A3_ROPE_HALF = 0, 1
 A3_POOL_MAX, A3_POOL_AVG = 0, 1
 
 EXPORTS = ["a3_workspace_bytes", "a3_layout_prepare", "a3_rope_realign", "a3_question_scores", "a3_question_scores_noalloc", "a3_realign_scores", "a3_topk_select", "a3_topk_select_plan",
-           "a3_selected_qkv_proj", "a3_selected_qkv_proj_scatter", "a3_kv_scatter", "a3_fused_attention", "a3_attention_plan", "a3_fused_attention_planned", "a3_active_rows",
+           "a3_selected_qkv_proj", "a3_selected_qkv_proj_scatter", "a3_kv_scatter", "a3_fused_attention", "a3_attention_plan", "a3_fused_attention_planned", "a3_fused_attention_planned_events", "a3_active_rows",
            "a3_block_tail_ws_bytes", "a3_block_tail", "a3_rms_norm", "a3_question_scores_causal", "a3_window_votes",
            "a3_evict_ws_bytes", "a3_evict_select", "a3_evict_compact", "a3_value_deviation_scores",
            "a3_select_chunk_edges", "a3_chunk_cache_load", "a3_rope_realign_q8", "a3_q8_row_bytes", "a3_quantize_q8",
-           "a3_chunk_cache_load_q8", "a3_chunk_file_read", "a3_set_tuning", "a3_strerror", "a3_last_error", "a3_version"]
+           "a3_chunk_cache_load_q8", "a3_chunk_file_read", "a3_set_tuning", "a3_recompute_count", "a3_chunk_edge_sel_start", "a3_strerror", "a3_last_error", "a3_version"]
 
 
 class A3Error(RuntimeError):
@@ -81,6 +81,8 @@ def lib() -> C.CDLL:
     L.a3_active_rows.argtypes = [P, V, V, I, V, V]
     L.a3_attention_plan.argtypes = [P, V, I, V, C.c_size_t, V]
     L.a3_fused_attention_planned.argtypes = [P, V, V, I, V, V, V, V, C.c_size_t, V]
+    L.a3_fused_attention_planned_events.argtypes = [P, V, V, I, V, V, V, V, C.c_size_t, V, V, V]
+    L.a3_fused_attention_planned_events.restype = I
     L.a3_attention_plan.restype = I
     L.a3_fused_attention_planned.restype = I
     L.a3_block_tail_ws_bytes.restype = C.c_size_t
@@ -119,6 +121,11 @@ def lib() -> C.CDLL:
         getattr(L, name).restype = I
     L.a3_topk_select_plan.argtypes = [P, V, V, I, V, I, V, V, C.c_size_t, V]
     L.a3_topk_select_plan.restype = I
+    L.a3_recompute_count.argtypes = [I, I, I]
+    L.a3_recompute_count.restype = I
+    L.a3_chunk_edge_sel_start.argtypes = [I, C.POINTER(C.c_int), C.POINTER(C.c_int), I, C.POINTER(C.c_int),
+                                          C.POINTER(C.c_int), I, I, C.POINTER(C.c_int)]
+    L.a3_chunk_edge_sel_start.restype = I
     L.a3_set_tuning.argtypes = [C.c_char_p, I]
     L.a3_set_tuning.restype = I
     L.a3_strerror.restype = C.c_char_p
@@ -167,6 +174,21 @@ class Layout:
         self.chunk_start, self.chunk_len, self.chunk_delta = i32(chunk_start), i32(chunk_len), i32(chunk_delta)
         n_req, n_chunks = len(ctx_len), len(chunk_start)
         T = int(np.asarray(seg_start)[-1])
+        # what the kernels take for granted about the index arrays (they cannot check device memory): every
+        # request is [context | question], the chunks tile the context rows exactly, in ascending order
+        seg_h, ctx_h, q_h = (np.asarray(a, dtype=np.int64) for a in (seg_start, ctx_len, q_len))
+        if not (len(seg_h) == n_req + 1 and np.array_equal(np.diff(seg_h), ctx_h + q_h) and np.all(ctx_h >= 0)
+                and np.all(q_h >= 0)):
+            raise ValueError("Layout: seg_start, ctx_len and q_len do not describe [context | question] segments")
+        cs_h, cl_h = np.asarray(chunk_start, dtype=np.int64), np.asarray(chunk_len, dtype=np.int64)
+        covered = np.zeros(max(T, 1), dtype=np.int32)
+        for s0, n in zip(cs_h, cl_h):
+            covered[s0:s0 + n] += 1
+        want = np.zeros(max(T, 1), dtype=np.int32)
+        for r in range(n_req):
+            want[seg_h[r]:seg_h[r] + ctx_h[r]] = 1
+        if n_chunks and not (np.all(np.diff(cs_h) > 0) and np.array_equal(covered, want)):
+            raise ValueError("Layout: the chunks do not tile the context rows exactly")
         max_ctx = int(np.max(ctx_len)) if n_req else 0
         max_q = int(np.max(q_len)) if n_req else 0
         self.total_tokens, self.n_req, self.n_chunks = T, n_req, n_chunks
@@ -355,13 +377,22 @@ def a3_value_deviation_scores(layout: Layout, v_true: torch.Tensor, v_cat: torch
            "a3_value_deviation_scores")
 
 
-def chunk_edge_sel_start(seg_start, ctx_len, chunk_start, chunk_len, n_head: int, n_tail: int) -> np.ndarray:
-    """sel_start [R+1] for a3_select_chunk_edges: request r holds, per chunk, min(chunk_len, n_head + n_tail) rows."""
-    counts = []
-    for r in range(len(ctx_len)):
-        lo, hi = int(seg_start[r]), int(seg_start[r]) + int(ctx_len[r])
-        counts.append(sum(min(int(n), n_head + n_tail) for s, n in zip(chunk_start, chunk_len) if lo <= int(s) < hi))
-    return np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+def a3_recompute_count(n_ctx: int, ratio_num: int, ratio_den: int) -> int:
+    k = int(lib().a3_recompute_count(int(n_ctx), int(ratio_num), int(ratio_den)))
+    if k < 0:
+        raise A3Error(A3_ERR_INVALID_ARG, "a3_recompute_count", lib().a3_last_error().decode())
+    return k
+
+
+def a3_chunk_edge_sel_start(seg_start, ctx_len, chunk_start, chunk_len, n_head: int, n_tail: int) -> np.ndarray:
+    """sel_start [R+1] for a3_select_chunk_edges, from host arrays."""
+    i32 = lambda a: np.ascontiguousarray(a, dtype=np.int32)
+    seg, ctx, cs, cl = i32(seg_start), i32(ctx_len), i32(chunk_start), i32(chunk_len)
+    out = np.zeros(len(ctx) + 1, dtype=np.int32)
+    p = lambda a: a.ctypes.data_as(C.POINTER(C.c_int))
+    _check(lib().a3_chunk_edge_sel_start(len(ctx), p(seg), p(ctx), len(cs), p(cs), p(cl), int(n_head), int(n_tail), p(out)),
+           "a3_chunk_edge_sel_start")
+    return out
 
 
 def a3_select_chunk_edges(layout: Layout, n_head: int, n_tail: int, sel_start: torch.Tensor, total_k: int,
@@ -396,6 +427,16 @@ def a3_fused_attention_planned(layout: Layout, q_act: torch.Tensor, act_idx: tor
     _check(lib().a3_fused_attention_planned(layout.ref, _ptr(q_act), _ptr(act_idx), int(n_act), _ptr(k_fused),
                                             _ptr(v_fused), _ptr(out), _ptr(ws), ws.numel() if ws is not None else 0,
                                             _stream(stream)), "a3_fused_attention_planned")
+
+
+def a3_fused_attention_planned_events(layout: Layout, q_act: torch.Tensor, act_idx: torch.Tensor, n_act: int,
+                                      k_fused: torch.Tensor, v_fused: torch.Tensor, out: torch.Tensor, ws: torch.Tensor,
+                                      ev_main_begin: Optional[int], ev_main_end: Optional[int], stream=None) -> None:
+    """ev_main_begin / ev_main_end: raw hipEvent_t handles (integers) or None."""
+    _check(lib().a3_fused_attention_planned_events(layout.ref, _ptr(q_act), _ptr(act_idx), int(n_act), _ptr(k_fused),
+                                                   _ptr(v_fused), _ptr(out), _ptr(ws),
+                                                   ws.numel() if ws is not None else 0, _stream(stream), ev_main_begin,
+                                                   ev_main_end), "a3_fused_attention_planned_events")
 
 
 def a3_q8_row_bytes(layout: Layout) -> int:

@@ -475,7 +475,7 @@ size_t a3_attn_ws_bytes(const a3_layout *L, int max_active_rows) {
 // active rows, so a caller may have it made beside whatever else precedes the attention.
 static a3_status attn_launch(const a3_layout *L, const void *q_act, const int *act_idx, int n_act,
                              const void *k_fused, const void *v_fused, void *out, void *ws, size_t ws_bytes,
-                             void *stream, int parts) {
+                             void *stream, int parts, hipEvent_t ev_begin = nullptr, hipEvent_t ev_end = nullptr) {
   a3_status s = a3_check_layout(L, "a3_fused_attention", true);
   if (s != A3_OK) return s;
   A3_REQUIRE(n_act >= 0 && n_act <= L->total_tokens, A3_ERR_INVALID_ARG,
@@ -495,6 +495,10 @@ static a3_status attn_launch(const a3_layout *L, const void *q_act, const int *a
   a.scale2 = a3_scale_of(L) * kLog2e;
   memset(&a.plan, 0, sizeof(a.plan));
   if (L->dtype == A3_BF16) {
+    // the kernel addresses a request's K/V rows with 32-bit byte offsets
+    A3_REQUIRE(((long long)L->max_ctx_len + L->max_q_len + 128) * L->n_kv_heads * kD * 2 < (1LL << 32), A3_ERR_UNSUPPORTED,
+               "a3_fused_attention: a request of %d rows is too long for 32-bit cache offsets",
+               L->max_ctx_len + L->max_q_len);
     A3_REQUIRE(ws != nullptr, A3_ERR_WORKSPACE, "a3_fused_attention: workspace is NULL");
     A3_REQUIRE(ws_bytes >= a3_attn_ws_bytes(L, n_act), A3_ERR_WORKSPACE,
                "a3_fused_attention: workspace %zu bytes, need %zu", ws_bytes, a3_attn_ws_bytes(L, n_act));
@@ -510,7 +514,9 @@ static a3_status attn_launch(const a3_layout *L, const void *q_act, const int *a
                          L->n_req, L->n_q_heads / L->n_kv_heads, wgs_per_head, attn_item_cost());
     if (parts & 2) {
       // blockIdx % Hkv = KV head, so with 8 KV heads each XCD's L2 serves the K/V of one head
+      if (ev_begin) (void)hipEventRecord(ev_begin, st);
       hipLaunchKernelGGL(attn_bf16_kernel, dim3((unsigned)wgs_per_head * Hkv), dim3(kAttnThreads), kAttnLds, st, a);
+      if (ev_end) (void)hipEventRecord(ev_end, st);
       hipLaunchKernelGGL(attn_combine_kernel, dim3((unsigned)max_tiles, Hkv, kTM / 32), dim3(256), 0, st, a);
     }
   } else if (parts & 2) {
@@ -535,4 +541,14 @@ extern "C" a3_status a3_fused_attention_planned(const a3_layout *L, const void *
                                                 const void *k_fused, const void *v_fused, void *out, void *ws,
                                                 size_t ws_bytes, void *stream) {
   return attn_launch(L, q_act, act_idx, n_act, k_fused, v_fused, out, ws, ws_bytes, stream, 2);
+}
+
+// a3_fused_attention_planned with two HIP events recorded on the stream right before and right after the main
+// kernel (the merge of the partial results follows the second one): for measurements of that kernel alone.
+extern "C" a3_status a3_fused_attention_planned_events(const a3_layout *L, const void *q_act, const int *act_idx,
+                                                       int n_act, const void *k_fused, const void *v_fused, void *out,
+                                                       void *ws, size_t ws_bytes, void *stream, void *ev_main_begin,
+                                                       void *ev_main_end) {
+  return attn_launch(L, q_act, act_idx, n_act, k_fused, v_fused, out, ws, ws_bytes, stream, 2, (hipEvent_t)ev_main_begin,
+                     (hipEvent_t)ev_main_end);
 }

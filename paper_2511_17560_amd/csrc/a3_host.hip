@@ -85,6 +85,39 @@ extern "C" const char *a3_strerror(a3_status s) {
 }
 
 extern "C" const char *a3_last_error(void) { return g_last_error; }
+
+// Eq. 3, p = r * n: recomputed context tokens of a request with n_ctx context tokens at ratio num / den, rounded
+// down, in integer arithmetic.
+extern "C" int a3_recompute_count(int n_ctx, int ratio_num, int ratio_den) {
+  if (n_ctx < 0 || ratio_num < 0 || ratio_den <= 0 || ratio_num > ratio_den) {
+    a3_fail(A3_ERR_INVALID_ARG, "a3_recompute_count: n_ctx %d, ratio %d / %d", n_ctx, ratio_num, ratio_den);
+    return -1;
+  }
+  return (int)(((long long)n_ctx * ratio_num) / ratio_den);
+}
+
+// sel_start for a3_select_chunk_edges: request r holds, per chunk, min(chunk_len, n_head + n_tail) rows.  Host arrays.
+extern "C" a3_status a3_chunk_edge_sel_start(int n_req, const int *seg_start, const int *ctx_len, int n_chunks,
+                                             const int *chunk_start, const int *chunk_len, int n_head, int n_tail,
+                                             int *sel_start) {
+  A3_REQUIRE(n_req >= 0 && n_chunks >= 0 && n_head >= 0 && n_tail >= 0, A3_ERR_INVALID_ARG,
+             "a3_chunk_edge_sel_start: negative count");
+  A3_REQUIRE(sel_start && (n_req == 0 || (seg_start && ctx_len)) && (n_chunks == 0 || (chunk_start && chunk_len)),
+             A3_ERR_INVALID_ARG, "a3_chunk_edge_sel_start: NULL argument");
+  long long run = 0;
+  sel_start[0] = 0;
+  for (int r = 0; r < n_req; ++r) {
+    const long long lo = seg_start[r], hi = lo + ctx_len[r];
+    for (int c = 0; c < n_chunks; ++c)
+      if (chunk_start[c] >= lo && chunk_start[c] < hi) {
+        const long long edge = (long long)n_head + n_tail;
+        run += chunk_len[c] < edge ? chunk_len[c] : edge;
+      }
+    A3_REQUIRE(run < (1LL << 31), A3_ERR_UNSUPPORTED, "a3_chunk_edge_sel_start: too many rows");
+    sel_start[r + 1] = (int)run;
+  }
+  return A3_OK;
+}
 extern "C" int a3_version(void) { return A3_VERSION; }
 
 extern "C" size_t a3_workspace_bytes(const a3_layout *L, int max_active_rows) {

@@ -8,6 +8,25 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 
+def _recompute_count(n_ctx, num, den):
+    """p = r * n of Eq. 3 for the shared workload generator: the oracle's count, checked against the library's own
+    host routine (the library loads without a GPU); a disagreement is an error right here."""
+    from oracle import a3_oracle as ora
+    k = ora.recompute_count(n_ctx, num, den)
+    try:
+        from paper_2511_17560_amd import api
+        k_lib = api.a3_recompute_count(n_ctx, num, den)
+    except RuntimeError:          # library not built: oracle-only test runs
+        k_lib = k
+    assert k == k_lib, (n_ctx, num, den, k, k_lib)
+    return k
+
+
+import a3_synth  # noqa: E402
+
+a3_synth.use_recompute_count(_recompute_count)
+
+
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
 

@@ -218,3 +218,14 @@ def test_set_tuning_knows_its_names():
         assert L.a3_set_tuning(name, -1) == api.A3_OK
     assert L.a3_set_tuning(b"no_such_value", 1) == api.A3_ERR_INVALID_ARG
     assert L.a3_set_tuning(None, 1) == api.A3_ERR_INVALID_ARG
+
+
+def test_recompute_count_and_chunk_edge_counts_on_the_host():
+    L = api.lib()
+    assert L.a3_recompute_count(512, 15, 100) == 76 and L.a3_recompute_count(16384, 10, 100) == 1638
+    assert L.a3_recompute_count(100, 0, 100) == 0 and L.a3_recompute_count(100, 100, 100) == 100
+    assert L.a3_recompute_count(-1, 15, 100) == -1 and L.a3_recompute_count(10, 3, 2) == -1
+    assert L.a3_recompute_count(10, 1, 0) == -1
+    # two requests: chunks of 100, 30 | 50 rows; 20 + 20 edge rows per chunk, a shorter chunk counts once
+    got = api.a3_chunk_edge_sel_start([0, 140, 200], [130, 50], [0, 100, 140], [100, 30, 50], 20, 20)
+    assert got.tolist() == [0, 70, 110]

@@ -11,7 +11,8 @@ import torch
 
 from oracle import a3_oracle as ora
 from oracle import evict_oracle as ev
-from paper_2511_17560_amd import api, synth
+import a3_synth as synth
+from paper_2511_17560_amd import api
 from gpu_util import idev, max_abs_rel, to_dev, to_host
 from test_gpu_parity import ctx_of
 
@@ -167,7 +168,7 @@ def test_value_deviation_scores_and_selection(name):
 def test_select_chunk_edges(name, n_head, n_tail):
     c, w, res, lay, kw, scale = _inputs(name)
     want_idx, want_start = sel_ora.chunk_edge_rows(w.seg_start, w.ctx_len, w.chunk_start, w.chunk_len, n_head, n_tail)
-    start = api.chunk_edge_sel_start(w.seg_start, w.ctx_len, w.chunk_start, w.chunk_len, n_head, n_tail)
+    start = api.a3_chunk_edge_sel_start(w.seg_start, w.ctx_len, w.chunk_start, w.chunk_len, n_head, n_tail)
     assert np.array_equal(start, want_start)
     total = int(start[-1])
     out = torch.full((max(total, 1),), -1, dtype=torch.int32, device="cuda")

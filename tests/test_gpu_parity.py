@@ -15,7 +15,8 @@ import torch
 
 from oracle import a3_oracle as ora
 from oracle import workload as wl
-from paper_2511_17560_amd import api, layer, synth
+import a3_synth as synth
+from paper_2511_17560_amd import api, layer
 from gpu_util import idev, max_abs_rel, to_dev, to_host
 
 pytestmark = pytest.mark.gpu

@@ -166,7 +166,8 @@ def test_streamed_stack_on_q8_blocks(case):
     selection happens on layer 1's true keys and must be identical; the two differ afterwards only in where the
     keys are rounded (once after the turn, against once before and once after it), so the hidden states of the
     active rows agree to a few storage roundings: 1e-4 in float32, 3e-2 in bf16."""
-    from paper_2511_17560_amd import loader, stack, synth
+    import a3_synth as synth
+    from paper_2511_17560_amd import loader, stack
     from gpu_util import to_dev
     from test_gpu_stack import STACK_CASES
     shape, chunk_lens, q_lens, ratio, _ = STACK_CASES[case]

@@ -13,7 +13,8 @@ import torch
 
 from oracle import a3_oracle as ora
 from oracle import stack_oracle as st
-from paper_2511_17560_amd import api, stack, synth
+import a3_synth as synth
+from paper_2511_17560_amd import api, stack
 from gpu_util import idev, max_abs_rel, to_dev, to_host
 
 pytestmark = pytest.mark.gpu

@@ -9,7 +9,7 @@ import torch
 
 from oracle import a3_oracle as ora
 from oracle import workload as wl
-from paper_2511_17560_amd import synth
+import a3_synth as synth
 
 SMALL = synth.ModelShape("small", "f32", 48, 4, 2, 8, 1e4)
 

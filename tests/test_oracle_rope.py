@@ -9,7 +9,7 @@ import pytest
 
 from oracle import a3_oracle as ora
 from oracle import workload as wl
-from paper_2511_17560_amd import synth
+import a3_synth as synth
 
 GOLD = os.path.join(os.path.dirname(__file__), "golden")
 

@@ -8,7 +8,7 @@ import torch
 
 from oracle import a3_oracle as ora
 from oracle import workload as wl
-from paper_2511_17560_amd import synth
+import a3_synth as synth
 
 
 def _rand_problem(seed, ctx_lens=(23, 40), q_lens=(3, 5), Hq=4, Hkv=2, d=8):
@@ -168,3 +168,30 @@ def test_invariant_planted_relevant_tokens_are_selected(cfg):
     # and they rank in the upper half of the selection
     rank = np.argsort(np.argsort(-sc[:w.ctx_len[0]], kind="stable"), kind="stable")
     assert rank[b["planted"]].max() < w.total_k // 2
+
+
+def test_recompute_count_of_the_five_configurations():
+    """Eq. 3, p = r * n with n the request's context length, rounded down: 76 of 512 at 15 %, 768 of 5120 at 15 %,
+    1638 of 16384 at 10 %, and floor(0.2 N) / floor(0.15 N_r) for the drawn lengths of configurations 4 and 5
+    (checked against exact rational arithmetic written out here, not against the oracle's own expression)."""
+    assert ora.recompute_count(512, 15, 100) == 76
+    assert ora.recompute_count(5120, 15, 100) == 768
+    assert ora.recompute_count(16384, 10, 100) == 1638
+    w4, w5 = synth.config(4), synth.config(5)
+    n4 = int(w4.ctx_len[0])
+    k4 = ora.recompute_count(n4, 20, 100)
+    assert 5 * k4 <= n4 < 5 * (k4 + 1)                      # k = floor(N / 5)
+    for n in w5.ctx_len:
+        k = ora.recompute_count(int(n), 15, 100)
+        assert 20 * k <= 3 * int(n) < 20 * (k + 1)          # k = floor(3 N / 20)
+    # the running sums the path is handed
+    assert np.array_equal(ora.sel_start_from_ratio([512], 15, 100), [0, 76])
+    assert np.array_equal(ora.sel_start_from_ratio(w5.ctx_len, 15, 100),
+                          np.concatenate([[0], np.cumsum([(3 * int(n)) // 20 for n in w5.ctx_len])]))
+    # ends of the range, monotone in both arguments, never more than there are tokens, no float rounding upwards
+    assert ora.recompute_count(1000, 0, 100) == 0 and ora.recompute_count(1000, 100, 100) == 1000
+    assert ora.recompute_count(0, 15, 100) == 0
+    assert ora.recompute_count(100, 29, 100) == 29 and ora.recompute_count(7, 1, 3) == 2
+    ks = [ora.recompute_count(n, 15, 100) for n in range(0, 2000)]
+    assert all(b - a in (0, 1) for a, b in zip(ks, ks[1:])) and all(k <= n for n, k in enumerate(ks))
+    assert [ora.recompute_count(999, r, 100) for r in range(101)] == sorted(ora.recompute_count(999, r, 100) for r in range(101))

@@ -6,7 +6,7 @@ import pytest
 
 from oracle import a3_oracle as ora
 from oracle import stack_oracle as st
-from paper_2511_17560_amd import synth
+import a3_synth as synth
 
 F64 = np.float64
 

@@ -10,7 +10,8 @@ import pytest
 import torch
 
 from oracle import workload as wl
-from paper_2511_17560_amd import api, synth
+import a3_synth as synth
+from paper_2511_17560_amd import api
 from gpu_util import max_abs_rel, to_dev
 
 SHAPE = synth.ModelShape("noalloc-bf16", "bf16", 256, 8, 2, 128, 500000.0)
