@@ -19,6 +19,16 @@ def to_host(t: torch.Tensor) -> np.ndarray:
     return t.detach().to(torch.float64).cpu().numpy()
 
 
+def max_elem_rel(got: np.ndarray, want: np.ndarray, floor: float = 1e-3) -> float:
+    """Worst element-wise relative error, max |a - b| / max(|b|, floor * max |b|): an element is measured against
+    its own size, down to a floor of one thousandth of the tensor's largest entry."""
+    want = np.asarray(want, dtype=np.float64)
+    scale = float(np.abs(want).max())
+    if scale == 0.0:
+        return float(np.abs(got - want).max())
+    return float((np.abs(got - want) / np.maximum(np.abs(want), floor * scale)).max())
+
+
 def max_abs_rel(got: np.ndarray, want: np.ndarray) -> float:
     """max |a - b| / max |b| over the tensor."""
     denom = float(np.abs(want).max())

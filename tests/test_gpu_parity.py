@@ -5,9 +5,14 @@ stage), then the chained layer.  Sizes span several tiles and ragged tails.
 Tolerances (max |a-b| / max |b| per tensor):
   realigned keys   fp32 1e-5; bf16 one rounding of the stored value (checked as <= 2^-7 with
                    at most 2% of elements differing at all)
-  scores           1e-4
+  scores           1e-4 of the request's largest score; and, over the rows without a planted key (whose huge
+                   scores would hide everything else), 2e-5 both of their largest score and element by element
   selected rows    bit-exact on the oracle's float32 scores
   projections, fused K/V, attention output   fp32 1e-5, bf16 2e-2
+Element by element (|a-b| / max(|b|, 1e-3 max |b|)): projections 1e-2 in bf16 (the one rounding of the stored
+value, 2^-8 .. 2^-7 of the element) and 1e-3 in fp32 (accumulation order over `hidden` products); attention output
+|a-b| <= 2^-8 |b| + 2^-8 max |V| (the stored rounding of the output plus the bf16 rounding of the softmax weights
+in front of the PV product, each 2^-9, with a factor of two in hand).
 """
 import numpy as np
 import pytest
@@ -17,7 +22,7 @@ from oracle import a3_oracle as ora
 from oracle import workload as wl
 import a3_synth as synth
 from paper_2511_17560_amd import api, layer
-from gpu_util import idev, max_abs_rel, to_dev, to_host
+from gpu_util import idev, max_abs_rel, max_elem_rel, to_dev, to_host
 
 pytestmark = pytest.mark.gpu
 
@@ -46,8 +51,8 @@ def _workload(name):
         return synth.custom(SMALL_G7, [[140, 200], [90]], [40, 11], ratio=(20, 100), seed=49)
     if name == "cfg3-layer0":    # the 16K benchmark configuration, first and last of its 32 independent layers
         return synth.config(3, layer=0)
-    if name == "cfg3-layer31":
-        return synth.config(3, layer=31)
+    if name in ("cfg3-layer1", "cfg3-layer15", "cfg3-layer31"):
+        return synth.config(3, layer=int(name[len("cfg3-layer"):]))
     if name == "cfg4":
         return synth.config(4)
     if name == "cfg5":
@@ -68,7 +73,7 @@ NAMES = ["cfg1", "cfg1-half", "ragged-bf16", "batched-bf16-half", "g7-bf16", "ba
          "manyq-bf16", "manyq-g7-bf16"]
 # full-size configurations: one oracle layer each takes tens of seconds, so each is built once and runs
 # the chained test and the teacher-forced tests of the three kernels whose behaviour depends on scale
-BIG_NAMES = ["cfg3-layer0", "cfg3-layer31", "cfg4", "cfg5"]
+BIG_NAMES = ["cfg3-layer0", "cfg3-layer1", "cfg3-layer15", "cfg3-layer31", "cfg4", "cfg5"]
 _cache = {}
 
 
@@ -156,6 +161,9 @@ def test_selected_qkv_proj(name):
         assert max_abs_rel(to_host(q), wantq) <= tol(w)
         assert max_abs_rel(to_host(k), wantk) <= tol(w)
         assert max_abs_rel(to_host(v), wantv) <= tol(w)
+        etol = 1e-3 if dt == "f32" else 1e-2
+        assert max_elem_rel(to_host(q), wantq) <= etol and max_elem_rel(to_host(k), wantk) <= etol
+        assert max_elem_rel(to_host(v), wantv) <= etol
     # Q of the question rows alone (what the layer pass asks for first; few heads: the few-row kernel then runs
     # with 32 rows per workgroup), and K and V alone
     rows_np = res["q_rows"]
@@ -218,6 +226,8 @@ def test_question_scores(name):
     for r in range(w.n_req):
         rows = w.ctx_rows(r)
         assert max_abs_rel(got[rows], want[rows]) <= 1e-4
+        plain = np.setdiff1d(rows, c["b"]["planted"])        # without the planted keys' scores, which dwarf the rest
+        assert max_abs_rel(got[plain], want[plain]) <= 2e-5 and max_elem_rel(got[plain], want[plain]) <= 2e-5
         # every softmax row sums to one
         assert abs(got[rows].sum() - w.shape.n_q_heads * w.q_lens[r]) <= 1e-3 * w.shape.n_q_heads * w.q_lens[r]
     assert np.all(np.isneginf(got[w.question_rows()]))
@@ -296,7 +306,10 @@ def test_fused_attention(name):
     ws = lay.workspace(len(act))
     api.a3_fused_attention(lay, to_dev(res["q_act"], dt), idev(act), len(act), to_dev(res["k_fused"], dt),
                            to_dev(res["v_fused"], dt), out, ws)
-    assert max_abs_rel(to_host(out), res["out"]) <= tol(w)
+    got = to_host(out)
+    assert max_abs_rel(got, res["out"]) <= tol(w)
+    ulp = 2.0 ** -8 if dt == "bf16" else 1e-5
+    assert np.all(np.abs(got - res["out"]) <= ulp * np.abs(res["out"]) + ulp * np.abs(res["v_fused"]).max())
 
 
 @pytest.mark.parametrize("wgs,item_cost", [("1", None), ("3", None), ("37", None), ("300", None), ("37", "0"),

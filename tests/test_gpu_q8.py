@@ -165,7 +165,7 @@ def test_streamed_stack_on_q8_blocks(case):
     oracle) against the same schedule on resident caches that hold the oracle's dequantised values.  The
     selection happens on layer 1's true keys and must be identical; the two differ afterwards only in where the
     keys are rounded (once after the turn, against once before and once after it), so the hidden states of the
-    active rows agree to a few storage roundings: 1e-4 in float32, 3e-2 in bf16."""
+    active rows agree to a few storage roundings: 1e-4 in float32, 2e-2 in bf16."""
     import a3_synth as synth
     from paper_2511_17560_amd import loader, stack
     from gpu_util import to_dev
@@ -205,7 +205,7 @@ def test_streamed_stack_on_q8_blocks(case):
     torch.cuda.synchronize()
     assert torch.equal(a["act_idx"], b["act_idx"])
     rows = a["act_idx"].long()
-    tol = 1e-4 if dt == "f32" else 3e-2
+    tol = 1e-4 if dt == "f32" else 2e-2
     assert max_abs_rel(to_host(b["hidden"][rows]), to_host(a["hidden"][rows])) <= tol
     assert max_abs_rel(to_host(b["resid"][rows]), to_host(a["resid"][rows])) <= tol
     assert not torch.equal(a["hidden"][rows], torch.zeros_like(a["hidden"][rows]))

@@ -5,7 +5,12 @@ Tolerances (max |a-b| / max |b| per tensor unless stated):
   RMSNorm                      fp32 1e-5; bf16 one rounding of the stored value (2^-7)
   H(.) (a3_block_tail)         fp32 2e-5; bf16 2e-2 (five stored tensors in a row, each rounded once, and
                                K up to 14336 products per sum), mean |a-b| <= 2e-3 of the scale
-  stack                        fp32 1e-4; bf16 4e-2 after four blocks, mean |a-b| <= 4e-3 of the scale
+  stack                        fp32 1e-4; bf16 2e-2 after four blocks, mean |a-b| <= 4e-3 of the scale.  A block
+                               stores five bf16 tensors in a row, each within 2^-8 of its value: were the twenty
+                               roundings of four blocks all to line up, 20 * 2^-9 = 4e-2; they are independent,
+                               their sum has a deviation of sqrt(20) * 2^-9 / sqrt(3) = 5e-3 of the element, and the
+                               bar stands at four of those deviations
+  selection                    a row picked on one side only has an oracle score within 1e-3 of the k-th largest
 """
 import numpy as np
 import pytest
@@ -210,7 +215,7 @@ def test_fuse_stack(case):
         kth = np.sort(want["scores"][rows])[::-1][k_r - 1]
         for row in flips:
             if rows[0] <= row <= rows[-1]:
-                assert abs(want["scores"][row] - kth) <= 2e-3 * abs(kth), (row, want["scores"][row], kth)
+                assert abs(want["scores"][row] - kth) <= 1e-3 * abs(kth), (row, want["scores"][row], kth)
     assert len(flips) <= max(2, len(got_act) // 25)
     sc_tol = 1e-4 if dt == "f32" else 2e-2
     ctx = np.concatenate([w.ctx_rows(r) for r in range(w.n_req)])
@@ -218,7 +223,7 @@ def test_fuse_stack(case):
     if flips:   # same selection on both sides from here on
         want = st.fuse_stack(r0, k_cat, v_cat, layers64, g_final, sh, storage=dt,
                              forced_sel_idx=got["sel_idx"].cpu().numpy(), **idx)
-    tol, mtol = (1e-4, 1e-5) if dt == "f32" else (4e-2, 4e-3)
+    tol, mtol = (1e-4, 1e-5) if dt == "f32" else (2e-2, 4e-3)
     for l in range(n_layers):
         g_out = to_host(got["per_layer"][l]["out"])
         assert max_abs_rel(g_out, want["per_layer"][l]["out"]) <= tol, l
@@ -249,7 +254,7 @@ def test_prefill_stack(case):
     dev_layers = [{k: to_dev(v, dt) for k, v in lw.items()} for lw in sw["layers"]]
     got = stack.prefill_stack(lay, shape, dev_layers, to_dev(sw["g_final"], dt), to_dev(sw["resid0"], dt), keep_kv=True)
     torch.cuda.synchronize()
-    tol, mtol = (1e-4, 1e-5) if dt == "f32" else (4e-2, 4e-3)
+    tol, mtol = (1e-4, 1e-5) if dt == "f32" else (2e-2, 4e-3)
     for l in range(n_layers):
         assert max_abs_rel(to_host(got["k"][l]), want["k"][l]) <= tol, l
         assert max_abs_rel(to_host(got["v"][l]), want["v"][l]) <= tol, l
