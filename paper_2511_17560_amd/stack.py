@@ -28,7 +28,9 @@ def fuse_stack(layout: api.Layout, shape, layers: Sequence[Dict[str, torch.Tenso
     from host memory into a ring of device buffers while the layers before it compute, and ``k_cat`` / ``v_cat``
     are ignored; its blocks may be 8-bit (position recovery and dequantisation then run in one kernel).
     Returns dict(sel_idx, act_idx, n_act, scores, resid, hidden): ``hidden`` [T, h] holds the final-normed
-    output at the active rows.  With ``keep`` the per-layer attention outputs and caches are kept too."""
+    output at the active rows.  With ``keep`` every layer's attention output, caches, residual stream and the
+    hidden states handed to the next layer are kept too (``per_layer[l]``: k, v, out, resid, x_next; whole arrays
+    for block 0, the active rows afterwards), so that a test can check each layer on the inputs it really had."""
     dev, dt = layout.device, api.torch_dtype(layout.dtype)
     T, h = layout.total_tokens, shape.hidden
     Hq, Hkv, d = shape.n_q_heads, shape.n_kv_heads, shape.head_dim
@@ -71,7 +73,7 @@ def fuse_stack(layout: api.Layout, shape, layers: Sequence[Dict[str, torch.Tenso
     api.a3_fused_attention(layout, q_all, all_idx, T, k_l, v_l, out_all, ws_attn, stream=stream)
     tail(0, out_all, None, T)
     if keep:
-        kept.append(dict(k=k_l.clone(), v=v_l.clone(), out=out_all.clone()))
+        kept.append(dict(k=k_l.clone(), v=v_l.clone(), out=out_all.clone(), resid=resid.clone(), x_next=x.clone()))
     del q_all
 
     # ---- layer 1: true keys, scores, Re, attention of the rows [Re, Q] --------------------------------------
@@ -97,8 +99,9 @@ def fuse_stack(layout: api.Layout, shape, layers: Sequence[Dict[str, torch.Tenso
     api.a3_attention_plan(layout, act_idx, n_act, ws_attn, stream=stream)
     api.a3_fused_attention_planned(layout, q_act, act_idx, n_act, k_l, v_l, out, ws_attn, stream=stream)
     tail(1, out, act_idx, n_act)
+    act_long = act_idx[:n_act].long()
     if keep:
-        kept.append(dict(k=k_l.clone(), v=v_l.clone(), out=out[:n_act].clone()))
+        kept.append(dict(k=k_l.clone(), v=v_l.clone(), out=out[:n_act].clone(), resid=resid[act_long], x_next=x[act_long]))
 
     # ---- layers 2 ..: Eq. 2, Eq. 5 --------------------------------------------------------------------------
     for l in range(2, n_layers):
@@ -121,6 +124,8 @@ def fuse_stack(layout: api.Layout, shape, layers: Sequence[Dict[str, torch.Tenso
             cache_stream.release(l, stream)
             cache_stream.prefetch(l + cache_stream.depth)
         tail(l, out, act_idx, n_act)
+        if keep:
+            kept[-1].update(resid=resid[act_long], x_next=x[act_long])
     return dict(sel_idx=sel_idx[:total_k], act_idx=act_idx[:n_act], n_act=n_act, scores=scores, resid=resid, hidden=x,
                 per_layer=kept)
 

@@ -326,3 +326,90 @@ def test_chunk_cache_load_and_streamed_stack():
     assert torch.equal(a["act_idx"], b["act_idx"])
     rows = a["act_idx"].long()
     assert torch.equal(a["hidden"][rows], b["hidden"][rows]) and torch.equal(a["resid"][rows], b["resid"][rows])
+
+
+def test_fuse_stack_llama_shape_16k_layer_by_layer():
+    """The schedule at full size: Llama-3-8B's block shape, one request of 32 chunks of 512 tokens and a 64-token
+    question, r = 10 %, three blocks (block 0 on every row, layer 1 with the selection, one fused layer on a
+    drawn chunk cache), in the launch configuration the benchmark times.  The float64 oracle cannot run this
+    stack whole in test time, so every step is checked on its own: the oracle gets the inputs the GPU had at that
+    step (the kept hidden states, caches and residual stream) and computes the step for sampled rows (the
+    first and last of the list always among them); each comparison is then one step deep and carries the
+    per-step bar (bf16: 2e-2 of the tensor's largest value).  The selection is compared as a set, up to near-ties."""
+    shape = synth.ModelShape("llama-3-8b-block", "bf16", 4096, 32, 8, 128, 500000.0, synth.ROPE_HALF, ffn=14336)
+    dt, n_layers, tol = "bf16", 3, 2e-2
+    w = synth.custom(shape, [[512] * 32], [64], ratio=(10, 100), seed=91)
+    T, Hkv, d = w.total_tokens, shape.n_kv_heads, shape.head_dim
+    sw = synth.draw_stack_weights(w, n_layers)
+    rng = np.random.default_rng(92)
+    cache_k = synth.round_to_storage(rng.standard_normal((T, Hkv, d), dtype=np.float32), dt)
+    cache_v = synth.round_to_storage(rng.standard_normal((T, Hkv, d), dtype=np.float32), dt)
+    lay = api.Layout.from_workload(w)
+    dev_layers = [{k: to_dev(v, dt) for k, v in lw.items()} for lw in sw["layers"]]
+    got = stack.fuse_stack(lay, shape, dev_layers, to_dev(sw["g_final"], dt), to_dev(sw["resid0"], dt),
+                           [None, None, to_dev(cache_k, dt)], [None, None, to_dev(cache_v, dt)], w.sel_start,
+                           w.question_rows(), keep=True)
+    torch.cuda.synchronize()
+    kept = [{k: to_host(v) for k, v in pl.items()} for pl in got["per_layer"]]
+    act = got["act_idx"].cpu().numpy().astype(np.int64)
+    n_act = len(act)
+    q_rows = np.asarray(w.question_rows(), dtype=np.int64)
+    assert n_act == int(w.sel_start[-1]) + len(q_rows) and np.all(np.diff(act) > 0)
+    del dev_layers
+    torch.cuda.empty_cache()
+
+    pos = np.asarray(w.token_positions())
+    proj = dict(n_q_heads=shape.n_q_heads, n_kv_heads=Hkv, head_dim=d, base=shape.rope_base,
+                layout=shape.rope_layout, storage=dt)
+    scale, eps = 1.0 / np.sqrt(d), shape.rms_eps
+    l64 = lambda l: {k: v.astype(F64) for k, v in sw["layers"][l].items()}
+    close = lambda a, b: max_abs_rel(np.asarray(a, dtype=F64), b) <= tol
+
+    # ---- block 0 on sampled rows of the whole input ------------------------------------------------------
+    lw = l64(0)
+    rows = np.unique(np.concatenate([[0, 511, 512, T - 65, T - 64, T - 1], rng.choice(T, size=42, replace=False)]))
+    r0 = sw["resid0"].astype(F64)
+    x0 = ora.store(st.rms_norm(r0[rows], lw["g_in"], eps), dt)
+    q, k, v = ora.selected_qkv_proj(x0, np.arange(len(rows)), pos[rows], lw["wq"], lw["wk"], lw["wv"], **proj)
+    assert close(kept[0]["k"][rows], k) and close(kept[0]["v"][rows], v)
+    o = ora.fused_attention(q, rows, kept[0]["k"], kept[0]["v"], w.seg_start, scale, dt)
+    assert close(kept[0]["out"][rows], o)
+    t = st.block_tail(kept[0]["out"][rows].astype(F64), r0[rows], lw, sw["layers"][1]["g_in"].astype(F64), eps, dt)
+    assert close(kept[0]["resid"][rows], t["resid"]) and close(kept[0]["x_next"][rows], t["hidden_next"])
+
+    # ---- layer 1: true keys, scores, selection, attention of the rows [Re, Q] ------------------------------------
+    lw = l64(1)
+    x1 = kept[0]["x_next"].astype(F64)
+    _, k, v = ora.selected_qkv_proj(x1, rows, pos[rows], lw["wq"], lw["wk"], lw["wv"], **proj)
+    assert close(kept[1]["k"][rows], k) and close(kept[1]["v"][rows], v)
+    qq, _, _ = ora.selected_qkv_proj(x1, q_rows, pos[q_rows], lw["wq"], lw["wk"], lw["wv"], **proj)
+    scores = ora.question_scores(qq, kept[1]["k"], w.seg_start, w.ctx_len, w.q_lens, scale)
+    ctx = w.ctx_rows(0)
+    assert max_abs_rel(to_host(got["scores"])[ctx], scores[ctx]) <= tol
+    want_sel = ora.topk_select(scores, w.seg_start, w.ctx_len, w.sel_start)
+    flips = set(got["sel_idx"].cpu().numpy().tolist()) ^ set(want_sel.tolist())
+    kth = np.sort(scores[ctx])[::-1][int(w.sel_start[1]) - 1]
+    assert len(flips) <= n_act // 25 and all(abs(scores[r] - kth) <= 1e-2 * abs(kth) for r in flips)
+    pick = np.unique(np.concatenate([[0, n_act - 65, n_act - 64, n_act - 1], rng.choice(n_act, size=44, replace=False)]))
+    q, _, _ = ora.selected_qkv_proj(x1, act[pick], pos[act[pick]], lw["wq"], lw["wk"], lw["wv"], **proj)
+    o = ora.fused_attention(q, act[pick], kept[1]["k"], kept[1]["v"], w.seg_start, scale, dt)
+    assert close(kept[1]["out"][pick], o)
+    t = st.block_tail(kept[1]["out"][pick].astype(F64), kept[0]["resid"][act[pick]].astype(F64), lw,
+                      sw["layers"][2]["g_in"].astype(F64), eps, dt)
+    assert close(kept[1]["resid"][pick], t["resid"]) and close(kept[1]["x_next"][pick], t["hidden_next"])
+
+    # ---- layer 2: Eq. 2 on the drawn cache, Eq. 5 on the rows [Re, Q] --------------------------------------------
+    lw = l64(2)
+    k_re = ora.rope_realign(cache_k, w.chunk_start, w.chunk_len, w.chunk_delta, shape.rope_base, shape.rope_layout, dt)
+    rest = np.setdiff1d(np.arange(T), act)
+    assert close(kept[2]["k"][rest], k_re[rest]) and np.array_equal(kept[2]["v"][rest], cache_v[rest])
+    x2 = kept[1]["x_next"][pick].astype(F64)
+    q, k, v = ora.selected_qkv_proj(x2, np.arange(len(pick)), pos[act[pick]], lw["wq"], lw["wk"], lw["wv"], **proj)
+    assert close(kept[2]["k"][act[pick]], k) and close(kept[2]["v"][act[pick]], v)
+    o = ora.fused_attention(q, act[pick], kept[2]["k"], kept[2]["v"], w.seg_start, scale, dt)
+    assert close(kept[2]["out"][pick], o)
+    t = st.block_tail(kept[2]["out"][pick].astype(F64), kept[1]["resid"][pick].astype(F64), lw,
+                      sw["g_final"].astype(F64), eps, dt)
+    assert close(kept[2]["resid"][pick], t["resid"]) and close(kept[2]["x_next"][pick], t["hidden_next"])
+    assert np.array_equal(to_host(got["resid"])[act[pick]], kept[2]["resid"][pick])
+    assert np.array_equal(to_host(got["hidden"])[act[pick]], kept[2]["x_next"][pick])
