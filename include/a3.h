@@ -381,7 +381,9 @@ a3_status a3_chunk_cache_load_q8(const a3_layout *layout, const int *chunk_start
  *                     calls with few rows to that kernel instead of the weight-streaming one
  *   "proj_k64"        0: the projection's main loop on 64-byte instead of 128-byte row pieces
  *   "gemm_tb", "gemm_k64"   the same two for the GEMMs of a3_block_tail
- * A value must not change between a3_attention_plan and the a3_fused_attention_planned calls that use its plan.
+ * A value must not change between a3_attention_plan and the a3_fused_attention_planned calls that use its plan:
+ * if "attn_wgs" does, the plan lies elsewhere in the workspace, the kernels of the planned call notice (the
+ * plan records the value it was made with at a fixed place) and leave `out` untouched.
  * Host only; A3_ERR_INVALID_ARG for an unknown name. */
 a3_status a3_set_tuning(const char *name, int value);
 

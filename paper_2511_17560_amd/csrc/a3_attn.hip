@@ -78,7 +78,8 @@ attn_bf16_kernel(attn_args a) {
   bf16_t *Vt = Ks + 2 * kKTile;                              // [2][128][kVStride]
 
   const int g = blockIdx.x % a.Hkv, wg = blockIdx.x / a.Hkv;
-  if (wg >= a.plan.counters[2]) return;
+  // a plan made with another number of workgroups per head lies elsewhere in the workspace: touch nothing
+  if (a.plan.counters[3] != a.plan.max_wgs || wg >= a.plan.counters[2]) return;
   const int item_begin = a.plan.wg_start[wg], item_end = a.plan.wg_start[wg + 1];
   const int G = a.Hq / a.Hkv;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -351,7 +352,7 @@ attn_bf16_kernel(attn_args a) {
 __global__ void __launch_bounds__(256)
 attn_combine_kernel(attn_args a) {
   const int t = blockIdx.x, g = blockIdx.y;
-  if (t >= a.plan.counters[0]) return;
+  if (a.plan.counters[3] != a.plan.max_wgs || t >= a.plan.counters[0]) return;
   const int2 tb = a.plan.tile_b[t];
   const int nseg = tb.y;
   if (nseg <= 1) return;

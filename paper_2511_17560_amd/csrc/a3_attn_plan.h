@@ -29,7 +29,8 @@ struct attn_plan {
   int *tile_pre;     // [max_tiles+1] key steps of all earlier tiles
   int4 *items;       // [max_items] (tile, k_begin, k_end, 0), in work order
   int *wg_start;     // [max_wgs+1] first item of each workgroup of a head
-  int *counters;     // n_tiles, n_items, P
+  int *counters;     // n_tiles, n_items, P, max_wgs the plan was made with (first in the workspace: its place
+                     // does not depend on the sizes of the other arrays)
   float *part_o;     // [Hkv * max_items][256][128] unnormalised partial O of cut tiles
   float2 *part_ml;   // [Hkv * max_items][256]      (exponent reference in the exp2 domain, sum)
   int max_tiles, max_items, max_wgs;
@@ -157,6 +158,7 @@ __device__ __forceinline__ void attn_plan_body(const attn_plan &p, const int *ac
     p.counters[0] = n_tiles;
     p.counters[1] = min(n_items, p.max_items);
     p.counters[2] = P;
+    p.counters[3] = p.max_wgs;
   }
 }
 
@@ -191,6 +193,7 @@ inline void attn_plan_carve(const a3_layout *L, int n_act, void *ws, size_t ws_b
   const int wgs_per_head = attn_wgs_per_head(L);
   const int Hkv = L->n_kv_heads;
   a3_ws_cursor cur(ws, ws_bytes);
+  p->counters = (int *)cur.take(4 * sizeof(int));
   p->a_lo = (int *)cur.take((size_t)(L->n_req + 1) * sizeof(int));
   p->tile_start = (int *)cur.take((size_t)(L->n_req + 1) * sizeof(int));
   p->tile_a = (int4 *)cur.take((size_t)max_tiles * sizeof(int4));
@@ -198,7 +201,6 @@ inline void attn_plan_carve(const a3_layout *L, int n_act, void *ws, size_t ws_b
   p->tile_pre = (int *)cur.take((size_t)(max_tiles + 1) * sizeof(int));
   p->items = (int4 *)cur.take((size_t)max_items * sizeof(int4));
   p->wg_start = (int *)cur.take((size_t)(wgs_per_head + 1) * sizeof(int));
-  p->counters = (int *)cur.take(4 * sizeof(int));
   p->part_o = (float *)cur.take((size_t)max_items * Hkv * kTM * 128 * sizeof(float));
   p->part_ml = (float2 *)cur.take((size_t)max_items * Hkv * kTM * sizeof(float2));
   p->max_tiles = max_tiles; p->max_items = max_items; p->max_wgs = wgs_per_head;

@@ -500,6 +500,27 @@ def test_full_size_config(name):
     _cache.pop(name, None)
 
 
+def test_planned_attention_leaves_out_alone_when_the_plan_was_made_with_another_tuning(tuning):
+    """The number of workgroups per head decides where the plan's tables lie in the workspace.  A planned call
+    that finds a plan made with another value must not read those tables: it leaves `out` as it was."""
+    c = ctx_of("ragged-bf16")
+    w, res, lay = c["w"], c["res"], c["lay"]
+    dt = w.shape.dtype
+    act = res["act_idx"]
+    q, k, v, idx = to_dev(res["q_act"], dt), to_dev(res["k_fused"], dt), to_dev(res["v_fused"], dt), idev(act)
+    out = torch.full((len(act), w.shape.n_q_heads, w.shape.head_dim), 3.0, dtype=api.torch_dtype(dt), device="cuda")
+    ws = lay.workspace(len(act))
+    api.a3_attention_plan(lay, idx, len(act), ws)
+    tuning("attn_wgs", 5)
+    api.a3_fused_attention_planned(lay, q, idx, len(act), k, v, out, ws)
+    torch.cuda.synchronize()
+    assert bool((out == 3.0).all())
+    tuning("attn_wgs", -1)
+    api.a3_fused_attention_planned(lay, q, idx, len(act), k, v, out, ws)
+    torch.cuda.synchronize()
+    assert max_abs_rel(to_host(out), res["out"]) <= tol(w)
+
+
 @pytest.mark.parametrize("name", ["ragged-bf16", "batched-bf16-half", "cfg2", "cfg1"])
 def test_attention_in_two_calls(name):
     """a3_attention_plan (on a second stream, ordered by events) + a3_fused_attention_planned give what
