@@ -38,7 +38,7 @@ def build(verbose: bool = True, force: bool = True) -> str:
     out_dir = os.path.join(ROOT, "_build")
     os.makedirs(out_dir, exist_ok=True)
     hipcc = _hipcc()
-    headers = [os.path.join(ROOT, "include", "a3.h"), os.path.join(CSRC, "a3_internal.h")]
+    headers = [os.path.join(ROOT, "include", "a3.h")] + [os.path.join(CSRC, f) for f in sorted(os.listdir(CSRC)) if f.endswith(".h")]
     newest_header = max(os.path.getmtime(h) for h in headers)
 
     def compile_one(src: str) -> str:

@@ -16,6 +16,7 @@
 // one lane and the activation is formed on the fp32 accumulators.
 // fp32: plain LDS-tiled FMA kernels (correctness configuration, not tuned).
 #include "a3_internal.h"
+#include "a3_gemm_tile.h"
 
 namespace {
 
@@ -57,13 +58,6 @@ rms_norm_kernel(const T *x, const int *__restrict__ in_idx, const T *__restrict_
 // ---------------------------------------------------------------------------------------
 // bf16 MFMA GEMM with the two epilogues
 // ---------------------------------------------------------------------------------------
-constexpr int kBK = 32;              // reduction slab per barrier
-constexpr int kRowBytes = kBK * 2;   // an LDS row is one 64-byte k-slab of a weight or activation row
-constexpr int gemm_stages(int tb) { return tb == 2 ? 3 : 4; }
-constexpr size_t gemm_lds_bytes(int tb) { return (size_t)gemm_stages(tb) * (256 + 64 * tb) * kRowBytes; }
-// the variant with 128-byte row pieces: 3 weight stages and 2 stages of activation rows
-constexpr size_t gemm_lds_bytes_k64(int tb) { return (size_t)3 * 256 * 128 + (size_t)2 * 64 * tb * 128; }
-
 struct gemm_args {
   const bf16_t *a;       // activation rows [*, K]
   const int *a_idx;      // row i of the product reads activation row a_idx[i] (NULL: row i)
@@ -76,16 +70,10 @@ struct gemm_args {
   int n_ftiles, n_tok_tiles;
 };
 
-constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
-
 template <int TB, int EPI, bool K64>
 __global__ void __launch_bounds__(256, (TB == 2 && !K64) ? 2 : 1)
 gemm_bf16_kernel(gemm_args a) {
   constexpr int kTokTile = 64 * TB;
-  constexpr int kStages = gemm_stages(TB);
-  constexpr int kWBytes = 256 * kRowBytes;
-  constexpr int kStageBytes = kWBytes + kTokTile * kRowBytes;
-  constexpr int kLoads = 4 + TB;
   constexpr int kFeat = EPI == EPI_RESID ? 256 : 128;        // output features per workgroup
   extern __shared__ __align__(16) unsigned char lds[];
 
@@ -97,212 +85,23 @@ gemm_bf16_kernel(gemm_args a) {
   const int l32 = lane & 31, lhi = lane >> 5;
   const int fh = wave & 1, th = wave >> 1;
 
-  // direct-to-LDS load: lane i's 16 bytes land at M0 (wave-uniform LDS byte address) + 16 i.  Inline
-  // assembly so that the compiler neither waits for all of them in front of every LDS read nor moves
-  // memory accesses across them; the waits are the explicit s_waitcnt below.
-  const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds;
-#define A3_DMA(GPTR, LDS_OFF)                                                                                 \
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"                                          \
-               :: "s"(__builtin_amdgcn_readfirstlane(lds_base + (uint32_t)(LDS_OFF))), "v"(GPTR) : "memory")
   const int tok0 = tt * kTokTile + th * 32 * TB;
 
+  // ---- the product.  EPI_RESID: weight-tile row r is weight row kFeat ft + r.  EPI_SWIGLU: rows 0..63 of a
+  // wave's half are the gate rows of its 64 features, rows 64..127 the up rows of the same features.
   f32x16 acc[4][TB];
-#pragma unroll
-  for (int fb = 0; fb < 4; ++fb)
-#pragma unroll
-    for (int tb = 0; tb < TB; ++tb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[fb][tb][r] = 0.f;
-
-  if constexpr (!K64) {
-  // loading roles: one wave instruction brings 16 rows x 64 B, lane -> (row lane/4, slot lane%4), piece
-  // slot ^ swz(row) of the row, swz(r) = (r/4) % 4 (bank-conflict-free fragment reads)
-  const int lrow = lane >> 2, slot = lane & 3;
-  const int piece = slot ^ ((lrow >> 2) & 3);
-  const char *wsrc[4];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int row = 16 * (4 * j + wave) + lrow;              // 0..255: LDS row of the weight tile
-    const bf16_t *wp;
-    if (EPI == EPI_RESID) {
-      wp = a.w0 + (size_t)min(kFeat * ft + row, a.N - 1) * a.K;
-    } else {
-      // rows 0..63 of a wave's half: gate rows of its 64 features, rows 64..127: the up rows of the same
-      const int r = row & 127;
-      const int f = min(kFeat * ft + 64 * (row >> 7) + (r & 63), a.N - 1);
-      wp = (r < 64 ? a.w0 : a.w1) + (size_t)f * a.K;
-    }
-    wsrc[j] = reinterpret_cast<const char *>(wp + piece * 8);
-  }
-  const char *xsrc[TB];
-#pragma unroll
-  for (int j = 0; j < TB; ++j) {
-    const int row = 16 * (4 * j + wave) + lrow;
-    const int m = min(tt * kTokTile + row, a.n_rows - 1);    // clamp: computed but never stored
-    const int src_row = a.a_idx ? a.a_idx[m] : m;
-    xsrc[j] = reinterpret_cast<const char *>(a.a + (size_t)src_row * a.K + piece * 8);
-  }
-#define A3_ISSUE(STAGE, K0)                                                                                   \
-  {                                                                                                           \
-    const uint32_t st_ = (STAGE) * kStageBytes;                                                               \
-    const size_t kb_ = (size_t)(K0) * sizeof(bf16_t);                                                         \
-    _Pragma("unroll") for (int j = 0; j < 4; ++j) A3_DMA(wsrc[j] + kb_, st_ + 16 * (4 * j + wave) * kRowBytes); \
-    _Pragma("unroll") for (int j = 0; j < TB; ++j)                                                            \
-      A3_DMA(xsrc[j] + kb_, st_ + kWBytes + 16 * (4 * j + wave) * kRowBytes);                                 \
-  }
-
-  const int swz = (l32 >> 2) & 3;
-  const int frag_w = (fh * 128 + l32) * kRowBytes, frag_x = kWBytes + (th * 32 * TB + l32) * kRowBytes;
-  const int slot_k0 = ((lhi) ^ swz) * 16, slot_k1 = ((2 + lhi) ^ swz) * 16;
-  // ---- main loop: loads run kStages-1 slabs ahead; one LDS read or one load behind each MFMA ------------
-  const int n_slabs = a.K / kBK;
-  const int k_last = a.K - kBK;
-#pragma unroll
-  for (int s0 = 0; s0 < kStages - 1; ++s0) A3_ISSUE(s0, min(s0 * kBK, k_last))
-  bf16x8 wf0[4], xf0[TB], wf1[4], xf1[TB];
-  __builtin_amdgcn_s_waitcnt(vmcnt_imm((kStages - 2) * kLoads));
-  __builtin_amdgcn_s_barrier();
-  A3_ISSUE(kStages - 1, min((kStages - 1) * kBK, k_last))
-#pragma unroll
-  for (int tb = 0; tb < TB; ++tb)
-    xf0[tb] = *reinterpret_cast<const bf16x8 *>(lds + frag_x + tb * 32 * kRowBytes + slot_k0);
-#pragma unroll
-  for (int fb = 0; fb < 4; ++fb)
-    wf0[fb] = *reinterpret_cast<const bf16x8 *>(lds + frag_w + fb * 32 * kRowBytes + slot_k0);
-#define A3_FENCE __builtin_amdgcn_sched_barrier(0);
-#define A3_FRAG1(I, WF, XF, ST, SLOT)                                                                          \
-  if ((I) < TB) XF[(I) < TB ? (I) : 0] = *reinterpret_cast<const bf16x8 *>((ST) + frag_x + ((I) < TB ? (I) : 0) * 32 * kRowBytes + (SLOT)); \
-  else if ((I) < TB + 4) WF[(I) - TB < 4 && (I) >= TB ? (I) - TB : 0] = *reinterpret_cast<const bf16x8 *>((ST) + frag_w + ((I) - TB < 4 && (I) >= TB ? (I) - TB : 0) * 32 * kRowBytes + (SLOT));
-  for (int sl = 0; sl < n_slabs; ++sl) {
-    const unsigned char *st = lds + (sl % kStages) * kStageBytes;
-    A3_FENCE
-#pragma unroll
-    for (int i = 0; i < 4 * TB; ++i) {
-      const int fb = i / TB, tb = i % TB;
-      acc[fb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf0[fb], xf0[tb], acc[fb][tb], 0, 0, 0);
-      A3_FENCE
-      A3_FRAG1(i, wf1, xf1, st, slot_k1)
-      A3_FENCE
-    }
-    // slab sl+1 has landed for this wave once only the younger slabs are outstanding, and for everybody
-    // after the barrier, which also says that all fragments of slab sl have been fetched
-    __builtin_amdgcn_s_waitcnt(vmcnt_imm((kStages - 2) * kLoads) & ~(15 << 8));
-    __builtin_amdgcn_s_barrier();
-    const unsigned char *sn = lds + ((sl + 1) % kStages) * kStageBytes;
-    {
-      const uint32_t st_ = ((sl + kStages) % kStages) * kStageBytes;
-      const size_t kb_ = (size_t)min((sl + kStages) * kBK, k_last) * sizeof(bf16_t);
-      A3_FENCE
-#pragma unroll
-      for (int i = 0; i < 4 * TB; ++i) {
-        const int fb = i / TB, tb = i % TB;
-        acc[fb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf1[fb], xf1[tb], acc[fb][tb], 0, 0, 0);
-        A3_FENCE
-        A3_FRAG1(i, wf0, xf0, sn, slot_k0)
-        if (i < 4) A3_DMA(wsrc[i] + kb_, st_ + 16 * (4 * i + wave) * kRowBytes);
-        else if (i < kLoads) A3_DMA(xsrc[i - 4] + kb_, st_ + kWBytes + 16 * (4 * (i - 4) + wave) * kRowBytes);
-        A3_FENCE
-      }
-    }
-  }
-#undef A3_FENCE
-#undef A3_FRAG1
-  __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));                   // drain the tail loads before LDS is reused
-#undef A3_ISSUE
-
-  } else {
-    // ---- 128-byte row pieces: a slab is 64 elements of the reduction dimension.  The L1 path moves a wave
-    // instruction of 8 rows x 128 B (whole cache lines) a third faster than one of 16 rows x 64 B, and that
-    // path sets the pace of the loop.  LDS: a ring of 3 weight stages [256 rows][128 B] (requested two slabs
-    // ahead: they come from HBM) and a ring of 2 stages of activation rows [64 TB rows][128 B] (one slab ahead:
-    // shared by all feature tiles, L2 hits).  LDS slot s of row r holds piece s ^ ((r >> 1) & 7).
-    constexpr int kRowB = 128, kWStage = 256 * kRowB, kXStage = kTokTile * kRowB, kXBase = 3 * kWStage;
-    constexpr int kLW = 8, kLX = 2 * TB;
-    const int row8 = lane >> 3, slot8 = lane & 7;
-    const int piece8 = slot8 ^ ((4 * (wave & 1) + (row8 >> 1)) & 7);
-    const char *wsrc[kLW];
-#pragma unroll
-    for (int j = 0; j < kLW; ++j) {
-      const int row = 8 * (4 * j + wave) + row8;               // 0..255: LDS row of the weight tile
-      const bf16_t *wp;
-      if (EPI == EPI_RESID) {
-        wp = a.w0 + (size_t)min(kFeat * ft + row, a.N - 1) * a.K;
-      } else {
+  gemm_tile_mainloop<TB, K64>(
+      acc, lds, a.K,
+      [&](int row) -> const bf16_t * {
+        if (EPI == EPI_RESID) return a.w0 + (size_t)min(kFeat * ft + row, a.N - 1) * a.K;
         const int r = row & 127;
         const int f = min(kFeat * ft + 64 * (row >> 7) + (r & 63), a.N - 1);
-        wp = (r < 64 ? a.w0 : a.w1) + (size_t)f * a.K;
-      }
-      wsrc[j] = reinterpret_cast<const char *>(wp + piece8 * 8);
-    }
-    const char *xsrc[kLX];
-#pragma unroll
-    for (int j = 0; j < kLX; ++j) {
-      const int row = 8 * (4 * j + wave) + row8;
-      const int m = min(tt * kTokTile + row, a.n_rows - 1);    // clamp: computed but never stored
-      const int src_row = a.a_idx ? a.a_idx[m] : m;
-      xsrc[j] = reinterpret_cast<const char *>(a.a + (size_t)src_row * a.K + piece8 * 8);
-    }
-    const int n_slabs = a.K / 64;
-#define A3_KB(SLAB) ((size_t)min((SLAB), n_slabs - 1) * 128)     /* past the end: the last slab again, unused */
-#define A3_W_LOAD(J, WOFF, SLAB) A3_DMA(wsrc[J] + A3_KB(SLAB), (WOFF) + (4 * (J) + wave) * 1024);
-#define A3_X_LOAD(J, XOFF, SLAB) A3_DMA(xsrc[J] + A3_KB(SLAB), (XOFF) + (4 * (J) + wave) * 1024);
-    const int swz8 = (l32 >> 1) & 7;
-    const int frag_w = (fh * 128 + l32) * kRowB, frag_x = (th * 32 * TB + l32) * kRowB;
-    int slot[4];
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) slot[ks] = ((2 * ks + lhi) ^ swz8) * 16;
-#define A3_FENCE __builtin_amdgcn_sched_barrier(0);
-#define A3_FRAG8(I, WF, XF, WOFF, XOFF, SLOT)                                                                   \
-    if ((I) < TB) XF[(I) < TB ? (I) : 0] = *reinterpret_cast<const bf16x8 *>(lds + (XOFF) + frag_x + ((I) < TB ? (I) : 0) * 32 * kRowB + (SLOT)); \
-    else if ((I) < TB + 4) WF[(I) >= TB && (I) - TB < 4 ? (I) - TB : 0] = *reinterpret_cast<const bf16x8 *>(lds + (WOFF) + frag_w + ((I) >= TB && (I) - TB < 4 ? (I) - TB : 0) * 32 * kRowB + (SLOT));
-#define A3_KSTEP(WA, XA, WB, XB, WOFF, XOFF, SLOT, LOADS)                                                       \
-    A3_FENCE                                                                                                    \
-    _Pragma("unroll") for (int i = 0; i < 4 * TB; ++i) {                                                        \
-      const int fb = i / TB, tb = i % TB;                                                                       \
-      acc[fb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(WA[fb], XA[tb], acc[fb][tb], 0, 0, 0);              \
-      A3_FENCE                                                                                                  \
-      A3_FRAG8(i, WB, XB, WOFF, XOFF, SLOT)                                                                     \
-      LOADS                                                                                                     \
-      A3_FENCE                                                                                                  \
-    }
-    // request order: W(0) X(0) W(1) X(1), then per slab sl: W(sl+2) under its first k-step and X(sl+2) under
-    // its last one, so that at the barrier of slab sl only the 8 loads of W(sl+2) may still be on their way
-    int w_cur = 0, w_nxt = kWStage, w_nn = 2 * kWStage;
-    int x_cur = kXBase, x_nxt = kXBase + kXStage;
-#pragma unroll
-    for (int j = 0; j < kLW; ++j) A3_W_LOAD(j, w_cur, 0)
-#pragma unroll
-    for (int j = 0; j < kLX; ++j) A3_X_LOAD(j, x_cur, 0)
-#pragma unroll
-    for (int j = 0; j < kLW; ++j) A3_W_LOAD(j, w_nxt, 1)
-#pragma unroll
-    for (int j = 0; j < kLX; ++j) A3_X_LOAD(j, x_nxt, 1)
-    bf16x8 wf0[4], xf0[TB], wf1[4], xf1[TB];
-    __builtin_amdgcn_s_waitcnt(vmcnt_imm(kLW + kLX));
-    __builtin_amdgcn_s_barrier();
-#pragma unroll
-    for (int i = 0; i < TB + 4; ++i) { A3_FRAG8(i, wf0, xf0, w_cur, x_cur, slot[0]) }
-    for (int sl = 0; sl < n_slabs; ++sl) {
-      A3_KSTEP(wf0, xf0, wf1, xf1, w_cur, x_cur, slot[1], if (i < kLW) A3_W_LOAD(i, w_nn, sl + 2))
-      A3_KSTEP(wf1, xf1, wf0, xf0, w_cur, x_cur, slot[2], )
-      A3_KSTEP(wf0, xf0, wf1, xf1, w_cur, x_cur, slot[3], )
-      // slab sl + 1 is complete once only the 8 youngest loads (W(sl+2)) are outstanding; the barrier also says
-      // that every wave has fetched its last fragments of slab sl (LDS counter at zero first)
-      __builtin_amdgcn_s_waitcnt(vmcnt_imm(kLW) & ~(15 << 8));
-      __builtin_amdgcn_s_barrier();
-      A3_KSTEP(wf1, xf1, wf0, xf0, w_nxt, x_nxt, slot[0], if (i < kLX) A3_X_LOAD(i, x_cur, sl + 2))
-      { const int t = w_cur; w_cur = w_nxt; w_nxt = w_nn; w_nn = t; }
-      { const int t = x_cur; x_cur = x_nxt; x_nxt = t; }
-    }
-#undef A3_KSTEP
-#undef A3_FRAG8
-#undef A3_FENCE
-#undef A3_W_LOAD
-#undef A3_X_LOAD
-#undef A3_KB
-    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));                  // drain the tail loads before LDS is reused
-  }
-#undef A3_DMA
+        return (r < 64 ? a.w0 : a.w1) + (size_t)f * a.K;
+      },
+      [&](int row) -> const bf16_t * {
+        const int m = min(tt * kTokTile + row, a.n_rows - 1);    // clamp: computed but never stored
+        return a.a + (size_t)(a.a_idx ? a.a_idx[m] : m) * a.K;
+      });
 
   // ---- epilogue ----------------------------------------------------------------------------------------
   // Each wave turns its fp32 tile through its own piece of the now free LDS, one 32-row block at a time
@@ -468,23 +267,23 @@ a3_status gemm_bf16_launch(const gemm_args &a0, hipStream_t st, const char *who)
   if (a3_knob(A3_KNOB_GEMM_K64) == 0) k64 = false;
   static a3_once_per_device lds_once;
   const hipError_t once_err = a3_once(lds_once, []() {
-    hipError_t e1 = hipFuncSetAttribute((const void *)gemm_bf16_kernel<2, EPI, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes(2));
-    hipError_t e2 = hipFuncSetAttribute((const void *)gemm_bf16_kernel<3, EPI, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes(3));
-    hipError_t e3 = hipFuncSetAttribute((const void *)gemm_bf16_kernel<4, EPI, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes(4));
-    hipError_t e4 = hipFuncSetAttribute((const void *)gemm_bf16_kernel<3, EPI, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes_k64(3));
-    hipError_t e5 = hipFuncSetAttribute((const void *)gemm_bf16_kernel<4, EPI, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes_k64(4));
-    hipError_t e6 = hipFuncSetAttribute((const void *)gemm_bf16_kernel<2, EPI, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes_k64(2));
+    hipError_t e1 = hipFuncSetAttribute((const void *)gemm_bf16_kernel<2, EPI, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_tile_lds_bytes(2));
+    hipError_t e2 = hipFuncSetAttribute((const void *)gemm_bf16_kernel<3, EPI, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_tile_lds_bytes(3));
+    hipError_t e3 = hipFuncSetAttribute((const void *)gemm_bf16_kernel<4, EPI, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_tile_lds_bytes(4));
+    hipError_t e4 = hipFuncSetAttribute((const void *)gemm_bf16_kernel<3, EPI, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_tile_lds_bytes_k64(3));
+    hipError_t e5 = hipFuncSetAttribute((const void *)gemm_bf16_kernel<4, EPI, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_tile_lds_bytes_k64(4));
+    hipError_t e6 = hipFuncSetAttribute((const void *)gemm_bf16_kernel<2, EPI, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_tile_lds_bytes_k64(2));
     for (hipError_t e : {e1, e2, e3, e4, e5, e6}) if (e != hipSuccess) return e;
     return hipSuccess;
   });
   if (once_err != hipSuccess) return a3_fail(A3_ERR_HIP, "%s: cannot raise the dynamic LDS limit", who);
   const unsigned grid = 8u * (unsigned)((a.n_ftiles + 7) / 8) * (unsigned)a.n_tok_tiles;
-  if (tb == 2 && k64) hipLaunchKernelGGL((gemm_bf16_kernel<2, EPI, true>), dim3(grid), dim3(256), gemm_lds_bytes_k64(2), st, a);
-  else if (tb == 2) hipLaunchKernelGGL((gemm_bf16_kernel<2, EPI, false>), dim3(grid), dim3(256), gemm_lds_bytes(2), st, a);
-  else if (tb == 3 && k64) hipLaunchKernelGGL((gemm_bf16_kernel<3, EPI, true>), dim3(grid), dim3(256), gemm_lds_bytes_k64(3), st, a);
-  else if (tb == 3) hipLaunchKernelGGL((gemm_bf16_kernel<3, EPI, false>), dim3(grid), dim3(256), gemm_lds_bytes(3), st, a);
-  else if (k64) hipLaunchKernelGGL((gemm_bf16_kernel<4, EPI, true>), dim3(grid), dim3(256), gemm_lds_bytes_k64(4), st, a);
-  else hipLaunchKernelGGL((gemm_bf16_kernel<4, EPI, false>), dim3(grid), dim3(256), gemm_lds_bytes(4), st, a);
+  if (tb == 2 && k64) hipLaunchKernelGGL((gemm_bf16_kernel<2, EPI, true>), dim3(grid), dim3(256), gemm_tile_lds_bytes_k64(2), st, a);
+  else if (tb == 2) hipLaunchKernelGGL((gemm_bf16_kernel<2, EPI, false>), dim3(grid), dim3(256), gemm_tile_lds_bytes(2), st, a);
+  else if (tb == 3 && k64) hipLaunchKernelGGL((gemm_bf16_kernel<3, EPI, true>), dim3(grid), dim3(256), gemm_tile_lds_bytes_k64(3), st, a);
+  else if (tb == 3) hipLaunchKernelGGL((gemm_bf16_kernel<3, EPI, false>), dim3(grid), dim3(256), gemm_tile_lds_bytes(3), st, a);
+  else if (k64) hipLaunchKernelGGL((gemm_bf16_kernel<4, EPI, true>), dim3(grid), dim3(256), gemm_tile_lds_bytes_k64(4), st, a);
+  else hipLaunchKernelGGL((gemm_bf16_kernel<4, EPI, false>), dim3(grid), dim3(256), gemm_tile_lds_bytes(4), st, a);
   A3_CHECK_LAUNCH(who);
   return A3_OK;
 }
