@@ -91,12 +91,11 @@ def fuse_stack(layout: api.Layout, shape, layers: Sequence[Dict[str, torch.Tenso
     api.a3_selected_qkv_proj(layout, x, q_rows_d, nq, lw["wq"], None, None, bq=lw.get("bq"), q_out=q_question,
                              stream=stream)
     api.a3_question_scores(layout, q_question, k_l, scores, ws_attn, stream=stream)
-    api.a3_topk_select(layout, scores, sel_start_d, total_k, sel_idx, stream=stream)
-    api.a3_active_rows(layout, sel_idx, sel_start_d, n_act, act_idx, stream=stream)
+    # selection, the row list [Re, Q] and the layout of the attention's work in one call.  The rows stay the same
+    # from here on: the plan is made once and reused by every layer
+    api.a3_topk_select_plan(layout, scores, sel_start_d, total_k, sel_idx, n_act, act_idx, ws_attn, stream=stream)
     api.a3_selected_qkv_proj(layout, x, act_idx, n_act, lw["wq"], None, None, bq=lw.get("bq"), q_out=q_act,
                              stream=stream)
-    # the rows [Re, Q] stay the same from here on: their attention work is laid out once and reused by every layer
-    api.a3_attention_plan(layout, act_idx, n_act, ws_attn, stream=stream)
     api.a3_fused_attention_planned(layout, q_act, act_idx, n_act, k_l, v_l, out, ws_attn, stream=stream)
     tail(1, out, act_idx, n_act)
     act_long = act_idx[:n_act].long()
