@@ -123,9 +123,12 @@ attn_bf16_kernel(attn_args a) {
     const int mc = valid ? m : m_end - 1;
     const int arow = a0 + mc / G, hq = g * G + mc % G;
     const int limit = a.act_idx[arow] - base;              // last visible key (request-relative)
-    int wave_min_limit = limit;
+    int wave_min_limit = limit, wave_max_limit = limit;
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) wave_min_limit = min(wave_min_limit, __shfl_xor(wave_min_limit, off, 64));
+    for (int off = 32; off > 0; off >>= 1) {
+      wave_min_limit = min(wave_min_limit, __shfl_xor(wave_min_limit, off, 64));
+      wave_max_limit = max(wave_max_limit, __shfl_xor(wave_max_limit, off, 64));
+    }
 
     bf16x8 qf[kD / 16];
     {
@@ -209,6 +212,9 @@ attn_bf16_kernel(attn_args a) {
         A3_GLOAD(k0 + kTK)                                   // next tile: in flight during everything below
         if (more) { A3_KDMA(buf ^ 1, k0 + kTK) }
       }
+      // The tile's keys run up to the last row of the workgroup's 256; a wave whose own rows all end before
+      // the tile has nothing in it (every P would be 0) and only takes part in the staging and the barrier.
+      if (k0 <= wave_max_limit) {
       const unsigned char *kt = reinterpret_cast<const unsigned char *>(Ks) + buf * (kKTile * 2) + kfrag;
       const bf16_t *vt = Vt + buf * kVTile + l32 * kVStride + lhi * 8;
 
@@ -299,6 +305,7 @@ attn_bf16_kernel(attn_args a) {
 #pragma unroll
         for (int db = 0; db < 4; ++db)
           o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[step & 1][db], pf, o[db], 0, 0, 0);
+      }
       }
       if (more) {
         if (wave < 4) {
