@@ -197,9 +197,8 @@ struct row_map {
   }
 };
 
-// MULTI: more than 256 rows per KV head may occur (the host then makes runs of 256 keys, which stay in slots 0-3
-// while the row chunks pass by).
-template <int PASS, bool REALIGN, bool MULTI>
+// At most 256 rows per KV head (longer questions and wide groups go to scores_rows_bf16_kernel below).
+template <int PASS, bool REALIGN>
 __global__ void __launch_bounds__(kScoreThreads, 2)
 scores_bf16_kernel(scores_args a) {
   extern __shared__ __align__(16) unsigned char lds_raw[];
@@ -216,7 +215,6 @@ scores_bf16_kernel(scores_args a) {
   const int G = a.Hq / a.Hkv;
   const int Mg = (a.one_ctx_len >= 0 ? a.one_q_len : a.q_len[r]) * G;   // rows of this KV head: m = j * G + hh
   if (Mg <= 0) return;
-  const int n_row_chunks = MULTI ? (Mg + kChunkRows - 1) / kChunkRows : 1;
   const int s = a.one_ctx_len >= 0 ? 0 : a.seg_start[r], qrow0 = a.one_ctx_len >= 0 ? 0 : a.q_start[r];
   const row_map row_of{G, a.Hq, g, qrow0, a.inv_G};
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -265,14 +263,9 @@ scores_bf16_kernel(scores_args a) {
                  :: "s"(__builtin_amdgcn_readfirstlane(lds_base + kLdsQ + 4 * (4 * j + wave) * kKRowBytes)), "v"(gp_) \
                  : "memory");                                                                                  \
   }
-  for (int chunk = 0; chunk < n_row_chunks; ++chunk) {
-  const int m_base = chunk * kChunkRows;
-  const bool first = !MULTI || chunk == 0;                      // later chunks find the keys in the ring and their Q tile on its way
-  // (what only the first chunk needs, the addresses of the keys, is formed from these copies: the compiler then
-  // leaves that arithmetic inside the iteration instead of keeping dozens of registers alive across the loop)
-  int i0k = i0, total_rows = a.total_rows;
-  if (MULTI) asm volatile("" : "+s"(i0k), "+s"(total_rows));
-  if (loads && first) {
+  const int i0k = i0, total_rows = a.total_rows;
+  constexpr int m_base = 0;
+  if (loads) {
     if (!REALIGN) { A3_KDMA(0) }
     A3_QDMA(0)
     if (!REALIGN) {
@@ -394,9 +387,7 @@ scores_bf16_kernel(scores_args a) {
   }
 
   // ---- slot 0 and the Q tile have landed -------------------------------------------------------------
-  if (!first) {
-    if (loads) A3_VMCNT(0);                                    // the Q tile requested during the previous chunk
-  } else if (REALIGN) {
+  if (REALIGN) {
     // (in waves 0-3 the Q tile's loads are older than these: the compiler's wait for the keys of slot 0 covers them)
     A3_RLOAD(0, 0)
     if (nQ > 1) { A3_RLOAD(1, 1) }
@@ -422,10 +413,9 @@ scores_bf16_kernel(scores_args a) {
 #pragma unroll
     for (int x = 0; x < 16; ++x)     // PASS 1 lane: key; registers: rows 8 (x / 4) + 4 lhi + x % 4 of row block b
       acc0[b][x] = PASS == 1 ? -St[rg * 64 + b * 32 + 8 * (x >> 2) + 4 * lhi + (x & 3)] * a.inv_scale2 : 0.f;
-  if (nQ > 4 || n_row_chunks > 1) {
+  if (nQ > 4) {
     A3_LDS_BARRIER();                                          // everybody has its Q fragments: their place is free
-    if (loads && chunk + 1 < n_row_chunks) { A3_QDMA(m_base + kChunkRows) }
-    if (!REALIGN && loads && first && nQ > 4) {                // ... and joins the ring
+    if (!REALIGN && loads) {                                   // ... and joins the ring
       A3_KDMA(4)
       if (nQ > 5) { A3_KDMA(5) }
       if (nQ > 6) { A3_KDMA(6) }
@@ -482,10 +472,7 @@ scores_bf16_kernel(scores_args a) {
         p1 += fast_exp2(acc[b][x + 1] * a.scale2);                                                             \
       }                                                                                                        \
       const float part_ = halves_sum(p0 + p1);                                                                 \
-      if (lhi == 0) {                                            /* this wave's own entries: chunk after chunk */ \
-        float *r_ = &red[rg * a.tile_keys + (I) * kSlotKeys + kh * 32 + l32];                                  \
-        *r_ = first ? part_ : *r_ + part_;                                                                     \
-      }                                                                                                        \
+      if (lhi == 0) red[rg * a.tile_keys + (I) * kSlotKeys + kh * 32 + l32] = part_;                           \
     }                                                                                                          \
   }
 
@@ -493,13 +480,11 @@ scores_bf16_kernel(scores_args a) {
   A3_LOGITS()
   if (kh == 0) { A3_FOLD(0) }
   for (int i = 0; i + 1 < nQ; ++i) {
-    if (first) {                                               // (a later chunk: every slot is in the ring already)
-      if (REALIGN) { A3_RSTEP_STORE(i) } else if (loads) { A3_WAIT_SLOT(i) }
-      A3_LDS_BARRIER();                                        // slot i + 1 is in the ring
-      if (REALIGN) { A3_RSTEP_LOAD(i) }
-      // every wave has read slot i (its MFMAs were issued before the barrier): refill its place
-      else if (loads && i + kSlots < nQ) { A3_KDMA(i + kSlots) }
-    }
+    if (REALIGN) { A3_RSTEP_STORE(i) } else if (loads) { A3_WAIT_SLOT(i) }
+    A3_LDS_BARRIER();                                          // slot i + 1 is in the ring
+    if (REALIGN) { A3_RSTEP_LOAD(i) }
+    // every wave has read slot i (its MFMAs were issued before the barrier): refill its place
+    else if (loads && i + kSlots < nQ) { A3_KDMA(i + kSlots) }
     A3_KFRAGS(i + 1)
     if (kh == 0) {
       A3_LOGITS()
@@ -538,7 +523,6 @@ scores_bf16_kernel(scores_args a) {
       }
     }
   }
-  }   // row chunks
 #undef A3_QDMA
 #undef A3_WAIT_SLOT
 #undef A3_RSTEP_LOAD
@@ -557,6 +541,277 @@ scores_bf16_kernel(scores_args a) {
 }
 #undef A3_VMCNT
 #undef A3_LDS_BARRIER
+
+// ---------------------------------------------------------------------------------------
+// bf16 MFMA kernel for more than 256 rows per KV head (long questions, wide query groups, batches of them).
+// Workgroup (4 waves) = all rows of one KV head of one request against a tile of 256 keys, which stays in LDS
+// (64 KB, so two workgroups share a CU and one loads while the other multiplies) while the waves walk the rows
+// in groups of 64 with their Q fragments straight from global memory (L2).  The tile arrives in four quarters
+// of 64 keys, all requested up front; the logits of a wave's first 64 rows against a quarter are formed as soon
+// as it has landed.  PASS 0 leaves (max, sum exp) per (tile, row), a small kernel merges them per row, PASS 1
+// forms the column sums of exp2(l - stat).  Same results layout as the kernel above.
+// ---------------------------------------------------------------------------------------
+constexpr int kRowsTileKeys = 256;
+constexpr size_t kScoresRowsLds = (size_t)kRowsTileKeys * kKRowBytes + 4 * 64 * sizeof(float) +
+                                  4 * kRowsTileKeys * sizeof(float);
+
+template <int PASS, bool REALIGN>
+__global__ void __launch_bounds__(256, 2)
+scores_rows_bf16_kernel(scores_args a) {
+  extern __shared__ __align__(16) unsigned char lds_raw[];
+  float *St = reinterpret_cast<float *>(lds_raw + kRowsTileKeys * kKRowBytes);      // after the K tile; [4 waves][64 rows]
+  float *red = reinterpret_cast<float *>(St + 4 * 64);                                // [4 waves][256 keys]
+
+  const int r = blockIdx.z, g = blockIdx.y;
+  const int N = a.ctx_len[r];
+  const int i0 = blockIdx.x * kRowsTileKeys;
+  if (i0 >= N) return;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, lhi = lane >> 5;
+  const int s = a.seg_start[r];
+  const int nq = a.q_len[r];
+  const int G = a.Hq / a.Hkv;
+  const int Mg = nq * G;                // rows of this KV head: m = j*G + hh
+  const int qrow0 = a.q_start[r];
+  const bf16_t *__restrict__ Q = (const bf16_t *)a.q;
+  const bf16_t *__restrict__ K = (const bf16_t *)a.k;
+
+  // Q fragments of this wave's first 64 rows: requested before the K tile so that both latencies overlap
+  // (rows past Mg are clamped and ignored later)
+  bf16x8 qf[2][kD / 16];
+  int row_id[2];
+#define A3_LOAD_Q(RB0)                                                                                 \
+  _Pragma("unroll") for (int b = 0; b < 2; ++b) {                                                      \
+    const int m_ = min((RB0) + b * 32 + l32, Mg - 1);                                                  \
+    row_id[b] = (qrow0 + m_ / G) * a.Hq + g * G + m_ % G;      /* row of the [sum q_len * Hq] row space */ \
+    const bf16_t *qp_ = Q + (size_t)row_id[b] * kD + lhi * 8;                                          \
+    _Pragma("unroll") for (int ks = 0; ks < kD / 16; ++ks) qf[b][ks] = *reinterpret_cast<const bf16x8 *>(qp_ + ks * 16); \
+  }
+  if (Mg > 0) { A3_LOAD_Q(min(wave * 64, Mg - 1)) }
+  const bool have_rows = wave * 64 < Mg;                       // this wave has a first group of rows
+  if (PASS == 1) {
+    // max + log2(sum) of this wave's 64 rows, read back as broadcasts below; rows past Mg contribute 0
+    const int m = wave * 64 + lane;
+    float st = INFINITY;                                       // exp2(x - inf) = 0
+    if (m < Mg) st = a.stats[(qrow0 + m / G) * a.Hq + g * G + m % G].x;
+    St[wave * 64 + lane] = st;                                 // same-wave write/read: no barrier needed
+  }
+
+  // The K tile arrives in four quarters of 64 keys.  Every load of the tile is issued up front; the logits
+  // of the wave's first 64 rows against quarter q are formed as soon as that quarter is in LDS, while the
+  // later quarters are still on their way, so the arithmetic runs under the memory time instead of after it.
+  constexpr int kQuarters = 4;
+  constexpr int kKB = kRowsTileKeys / 32;                      // 32-key blocks per tile
+  const int n_kb = min(kKB, (N - i0 + 31) / 32);               // key blocks with at least one real key
+  // fragment read: key 32 kb + l32, piece 2 ks + lhi -> slot (2 ks + lhi) ^ (l32 % 16)
+  const unsigned char *kt = lds_raw + l32 * kKRowBytes;
+  const int kswz = (lhi ^ (l32 & 15)) * 16;
+  float colsum[kKB];
+#pragma unroll
+  for (int kb = 0; kb < kKB; ++kb) colsum[kb] = 0.f;
+  float run_max[2] = {-INFINITY, -INFINITY}, run_sum[2] = {0.f, 0.f};
+
+  // logits of the current 64 rows (fragments in qf) against key block KB, folded into the running row
+  // statistics (pass A) or into the column sums (pass B)
+#define A3_KEY_BLOCK(KB)                                                                                       \
+  {                                                                                                            \
+    f32x16 acc[2];                                                                                             \
+    _Pragma("unroll") for (int b = 0; b < 2; ++b)                                                              \
+      _Pragma("unroll") for (int x = 0; x < 16; ++x) acc[b][x] = 0.f;                                          \
+    _Pragma("unroll") for (int ks = 0; ks < kD / 16; ++ks) {                                                   \
+      const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(kt + (KB) * 32 * kKRowBytes + ((32 * ks) ^ kswz));   \
+      _Pragma("unroll") for (int b = 0; b < 2; ++b) {                                                          \
+        if (PASS == 0) acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[b][ks], acc[b], 0, 0, 0); /* C[key][row] */ \
+        else           acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[b][ks], kf, acc[b], 0, 0, 0); /* C[row][key] */ \
+      }                                                                                                        \
+    }                                                                                                          \
+    if (PASS == 0) {                                                                                           \
+      /* lane: row (column l32 of block b); registers: keys i0 + 32 kb + 8(x/4) + 4 lhi + x%4 */               \
+      const bool tail = i0 + 32 * (KB) + 31 >= N;                                                              \
+      _Pragma("unroll") for (int b = 0; b < 2; ++b) {                                                          \
+        if (tail) {                                                                                            \
+          /* (the empty statement keeps the 16 comparisons of each of the unrolled blocks here: gathered at */ \
+          /* the top of the kernel their lane masks do not fit the scalar registers)                        */ \
+          int n_real = N - i0 - 32 * (KB) - 4 * lhi;                                                           \
+          asm volatile("" : "+v"(n_real));                                                                     \
+          _Pragma("unroll") for (int x = 0; x < 16; ++x)                                                       \
+            if (8 * (x >> 2) + (x & 3) >= n_real) acc[b][x] = -INFINITY;                                       \
+        }                                                                                                      \
+        float mx = acc[b][0];                                                                                  \
+        _Pragma("unroll") for (int x = 1; x < 16; ++x) mx = fmaxf(mx, acc[b][x]);                              \
+        mx = halves_max(mx) * a.scale2;                        /* block 0 of a tile always has a real key */   \
+        const float new_max = fmaxf(run_max[b], mx);                                                           \
+        float sum = 0.f;                                                                                       \
+        _Pragma("unroll") for (int x = 0; x < 16; ++x) sum += fast_exp2(fmaf(acc[b][x], a.scale2, -new_max));  \
+        run_sum[b] = run_sum[b] * fast_exp2(run_max[b] - new_max) + sum;   /* per lane half */                 \
+        run_max[b] = new_max;                                                                                  \
+      }                                                                                                        \
+    } else {                                                                                                   \
+      /* lane: key l32 of block kb; registers: rows 8(x/4) + 4 lhi + x%4 of row block b */                     \
+      float part = 0.f;                                                                                        \
+      _Pragma("unroll") for (int b = 0; b < 2; ++b)                                                            \
+        _Pragma("unroll") for (int x = 0; x < 16; ++x) {                                                       \
+          const float st = St[wave * 64 + b * 32 + 8 * (x >> 2) + 4 * lhi + (x & 3)];                          \
+          part += fast_exp2(fmaf(acc[b][x], a.scale2, -st));                                                   \
+        }                                                                                                      \
+      colsum[KB] += part;                                                                                      \
+    }                                                                                                          \
+  }
+  // the 64 rows are done: pass A leaves their (max, sum) over this tile
+#define A3_ROWS_DONE(RB0)                                                                                      \
+  if (PASS == 0) {                                                                                             \
+    _Pragma("unroll") for (int b = 0; b < 2; ++b) {                                                            \
+      const float z = halves_sum(run_sum[b]);                                                                  \
+      if (lhi == 0 && (RB0) + b * 32 + l32 < Mg)                                                               \
+        a.part[(size_t)blockIdx.x * a.total_rows + row_id[b]] = make_float2(run_max[b], z);                    \
+    }                                                                                                          \
+  }
+
+  // ---- K tile: 256 keys x 128 dims of head g, global memory -> LDS directly (16 bytes per lane, lane i
+  // lands at base + 16 i).  One wave instruction brings 4 keys x 256 B; instruction j of wave w covers
+  // keys 4 (4 j + w) .. +3, so the instructions 4 q .. 4 q + 3 of the four waves bring quarter q.  The lane
+  // fetches piece (slot ^ key % 16) of its key, so LDS slot s of key r holds piece s ^ (r % 16) and the 16
+  // keys a quarter wave reads at one piece index touch all 64 banks once.  Inline assembly: the compiler
+  // then does not track these as LDS writes (it would wait for all of them before every LDS read); the
+  // explicit waits below cover them.
+  if (!REALIGN) {
+    // The compiler's own wait for the Q fragments and the row statistics would, counted by the hardware, also
+    // wait for everything issued before them; they are therefore awaited first, then the tile is requested.
+    __builtin_amdgcn_s_waitcnt(0);
+    const int drow = 4 * wave + (lane >> 4);                   // key of the lane in instruction 0
+    const int dpiece = (lane & 15) ^ (drow & 15);              // (4 (4 j + w) + lane/16) % 16 does not depend on j
+    const uint32_t lds_k = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds_raw;
+#pragma unroll
+    for (int j = 0; j < kRowsTileKeys / 16; ++j) {
+      const int row = min(s + i0 + drow + 16 * j, a.T - 1);    // tail rows: loaded, masked below
+      const bf16_t *gp = K + ((size_t)row * a.Hkv + g) * kD + dpiece * 8;
+      asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
+                   :: "s"(__builtin_amdgcn_readfirstlane(lds_k + 4 * (4 * j + wave) * kKRowBytes)), "v"(gp) : "memory");
+    }
+    // at most the 4 (3 - QT) younger instructions of this wave are still in flight: its part of quarter QT
+    // has landed; after the barrier everybody's has.  (vmcnt in bits 3:0 and 15:14, the other counters open.)
+#define A3_QUARTER(QT)                                                                                         \
+    __builtin_amdgcn_s_waitcnt((4 * (kQuarters - 1 - (QT))) | (7 << 4) | (15 << 8));                           \
+    __builtin_amdgcn_s_barrier();                                                                              \
+    if (have_rows) {                                                                                           \
+      if (2 * (QT) < n_kb) A3_KEY_BLOCK(2 * (QT))                                                              \
+      if (2 * (QT) + 1 < n_kb) A3_KEY_BLOCK(2 * (QT) + 1)                                                      \
+    }
+    A3_QUARTER(0)
+    A3_QUARTER(1)
+    A3_QUARTER(2)
+    A3_QUARTER(3)
+#undef A3_QUARTER
+  } else {
+    // Position recovery (Eq. 2) on the way in: the tile comes from the stale cache through registers,
+    // every pair is turned by its chunk's offset, and the rounded result goes both to the realigned cache
+    // and, in the same swizzled layout as above, to LDS.  A lane owns the 16-byte pieces c and c + 8 of
+    // a key: in either pairing (adjacent coordinates, or i with i + 64) it then holds whole pairs.
+    const bf16_t *Kc = (const bf16_t *)a.k_cat;               // may be the same buffer as k_out
+    bf16_t *Ko = (bf16_t *)a.k_out;
+    const int c = tid & 7, kr0 = tid >> 3;                     // 32 keys per round, 8 rounds: 2 per quarter
+    constexpr int kRounds = kRowsTileKeys / 32;
+    // all loads of the stale keys and of their chunk numbers are issued before the first rotation
+    bf16x8 lo[kRounds], hi[kRounds];
+    int chunk[kRounds];
+#pragma unroll
+    for (int j = 0; j < kRounds; ++j) {
+      const int key = kr0 + 32 * j;
+      const int row = min(s + i0 + key, a.T - 1);              // tail rows: loaded, never stored to the cache
+      const size_t off = ((size_t)row * a.Hkv + g) * kD;
+      lo[j] = *reinterpret_cast<const bf16x8 *>(Kc + off + 8 * c);
+      hi[j] = *reinterpret_cast<const bf16x8 *>(Kc + off + 64 + 8 * c);
+      chunk[j] = i0 + key < N ? a.tok_chunk[row] : -1;
+    }
+    // the eight (cos, sin) pairs of this lane's coordinates are reloaded only when the chunk changes
+    // from one of its keys to the next (rarely: a tile spans few chunks)
+    const bool inter = a.rope_layout == A3_ROPE_INTERLEAVED;
+    float2 csr[8];
+    int cur = -1;
+#pragma unroll
+    for (int j = 0; j < kRounds; ++j) {
+      const int key = kr0 + 32 * j;
+      const bool real = i0 + key < N;
+      const int row = min(s + i0 + key, a.T - 1);
+      const size_t off = ((size_t)row * a.Hkv + g) * kD;
+      bf16x8 rlo = lo[j], rhi = hi[j];
+      if (chunk[j] >= 0) {
+        if (chunk[j] != cur) {
+          const float2 *cs = a.chunk_cs + (size_t)chunk[j] * (kD / 2);
+#pragma unroll
+          for (int e = 0; e < 8; ++e)                          // interleaved: pairs 4c..4c+3 and 32+4c..; half: 8c..8c+7
+            csr[e] = inter ? cs[(e < 4 ? 4 * c : 28 + 4 * c) + e] : cs[8 * c + e];
+          cur = chunk[j];
+        }
+        if (inter) {
+#pragma unroll
+          for (int p2 = 0; p2 < 4; ++p2) {
+            float y0, y1;
+            a3_rotate_pair(a3_bf2f(lo[j][2 * p2]), a3_bf2f(lo[j][2 * p2 + 1]), csr[p2], y0, y1);
+            rlo[2 * p2] = a3_f2bf(y0); rlo[2 * p2 + 1] = a3_f2bf(y1);
+            a3_rotate_pair(a3_bf2f(hi[j][2 * p2]), a3_bf2f(hi[j][2 * p2 + 1]), csr[4 + p2], y0, y1);
+            rhi[2 * p2] = a3_f2bf(y0); rhi[2 * p2 + 1] = a3_f2bf(y1);
+          }
+        } else {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {                        // coordinate 8c+e pairs with 64+8c+e
+            float y0, y1;
+            a3_rotate_pair(a3_bf2f(lo[j][e]), a3_bf2f(hi[j][e]), csr[e], y0, y1);
+            rlo[e] = a3_f2bf(y0); rhi[e] = a3_f2bf(y1);
+          }
+        }
+      }
+      if (real) {
+        *reinterpret_cast<bf16x8 *>(Ko + off + 8 * c) = rlo;
+        *reinterpret_cast<bf16x8 *>(Ko + off + 64 + 8 * c) = rhi;
+      }
+      unsigned char *ld = lds_raw + key * kKRowBytes;
+      *reinterpret_cast<bf16x8 *>(ld + ((c ^ (key & 15)) * 16)) = rlo;
+      *reinterpret_cast<bf16x8 *>(ld + (((c + 8) ^ (key & 15)) * 16)) = rhi;
+      if (j & 1) {
+        // quarter j / 2 is in LDS once everybody's two rounds are written (this wave's writes first: the
+        // LDS counter only; a full fence would also wait for the keys still on their way)
+        __builtin_amdgcn_s_waitcnt(15 | (3 << 14) | (7 << 4) | (0 << 8));
+        __builtin_amdgcn_s_barrier();
+        if (have_rows) {
+          if (j - 1 < n_kb) A3_KEY_BLOCK(j - 1)
+          if (j < n_kb) A3_KEY_BLOCK(j)
+        }
+      }
+    }
+  }
+  if (have_rows) { A3_ROWS_DONE(wave * 64) }
+
+  // ---- the wave's further rows (more than 256 rows per KV head): the whole tile is in LDS by now --------------
+  for (int rb0 = wave * 64 + 256; rb0 < Mg; rb0 += 256) {      // this wave's rows rb0 .. rb0+63
+    A3_LOAD_Q(rb0)
+    if (PASS == 1) {
+      const int m = rb0 + lane;
+      float st = INFINITY;
+      if (m < Mg) st = a.stats[(qrow0 + m / G) * a.Hq + g * G + m % G].x;
+      St[wave * 64 + lane] = st;
+    }
+    run_max[0] = run_max[1] = -INFINITY;
+    run_sum[0] = run_sum[1] = 0.f;
+    for (int kb = 0; kb < n_kb; ++kb) A3_KEY_BLOCK(kb)
+    A3_ROWS_DONE(rb0)
+  }
+#undef A3_KEY_BLOCK
+#undef A3_ROWS_DONE
+#undef A3_LOAD_Q
+  if (PASS == 1) {
+#pragma unroll
+    for (int kb = 0; kb < kKB; ++kb) {
+      const float v = halves_sum(colsum[kb]);
+      if (lhi == 0) red[wave * kRowsTileKeys + kb * 32 + l32] = v;
+    }
+    __syncthreads();
+    const int key = i0 + tid;
+    if (tid < kRowsTileKeys && key < N)
+      a.part_scores[(size_t)g * a.T + s + key] = (red[tid] + red[kRowsTileKeys + tid]) +
+                                                 (red[2 * kRowsTileKeys + tid] + red[3 * kRowsTileKeys + tid]);
+  }
+}
 
 // scores[t] = sum over KV heads of their column sums, in head order; question rows get -inf
 __global__ void __launch_bounds__(256)
@@ -644,7 +899,7 @@ scores_f32_kernel(scores_args a) {
 
 }  // namespace
 
-// bf16 path: rows of the score matrix per KV head come in chunks of 256 (one workgroup each)
+// bf16 path: rows of the score matrix per KV head, in chunks of 256 (one chunk: the ring kernel)
 static int scores_row_chunks(const a3_layout *L) {
   const int G = L->n_q_heads / L->n_kv_heads;
   const int c = (int)(((long long)L->max_q_len * G + kChunkRows - 1) / kChunkRows);
@@ -655,9 +910,8 @@ static int scores_row_chunks(const a3_layout *L) {
 // workgroups (one per CU at a time: 150 KB of LDS) fill the 256 CUs in as few, as full rounds as possible; a
 // workgroup's fixed cost (its Q tile, the merge of the partials, the start-up of the ring) is worth about 192 keys.
 static int scores_tile_keys_bf16(const a3_layout *L) {
-  // more than 256 rows per KV head: the keys of a run have to stay in four slots of the ring while the row chunks
-  // pass by
-  if (scores_row_chunks(L) > 1) return kMinTileKeys;
+  // more than 256 rows per KV head: the kernel that keeps a 256-key tile in LDS and walks the rows
+  if (scores_row_chunks(L) > 1) return kRowsTileKeys;
   const long long per_tile = (long long)L->n_req * L->n_kv_heads;
   long long best_cost = -1;
   int best = kMinTileKeys;
@@ -738,11 +992,16 @@ static a3_status scores_launch(const a3_layout *L, const void *q_question, const
   if (bf16) {
     static a3_once_per_device lds_once;
     const hipError_t e = a3_once(lds_once, []() {
-      const void *fns[] = {(const void *)scores_bf16_kernel<0, false, false>, (const void *)scores_bf16_kernel<1, false, false>,
-                           (const void *)scores_bf16_kernel<0, true, false>, (const void *)scores_bf16_kernel<0, false, true>,
-                           (const void *)scores_bf16_kernel<1, false, true>, (const void *)scores_bf16_kernel<0, true, true>};
+      const void *fns[] = {(const void *)scores_bf16_kernel<0, false>, (const void *)scores_bf16_kernel<1, false>,
+                           (const void *)scores_bf16_kernel<0, true>};
       for (const void *fn : fns) {
         const hipError_t e_ = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kScoresLds);
+        if (e_ != hipSuccess) return e_;
+      }
+      const void *rows_fns[] = {(const void *)scores_rows_bf16_kernel<0, false>, (const void *)scores_rows_bf16_kernel<1, false>,
+                                (const void *)scores_rows_bf16_kernel<0, true>};
+      for (const void *fn : rows_fns) {
+        const hipError_t e_ = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kScoresRowsLds);
         if (e_ != hipSuccess) return e_;
       }
       return hipSuccess;
@@ -753,15 +1012,17 @@ static a3_status scores_launch(const a3_layout *L, const void *q_question, const
     A3_REQUIRE(wgs < (1LL << 31), A3_ERR_UNSUPPORTED, "a3_question_scores: batch too large");
     const dim3 grid((unsigned)wgs);
     if (scores_row_chunks(L) > 1) {
-      if (fuse) hipLaunchKernelGGL((scores_bf16_kernel<0, true, true>), grid, dim3(kScoreThreads), kScoresLds, st, a);
-      else hipLaunchKernelGGL((scores_bf16_kernel<0, false, true>), grid, dim3(kScoreThreads), kScoresLds, st, a);
+      // (tile_keys is kRowsTileKeys here; every row of a KV head in one workgroup)
+      const dim3 rgrid((unsigned)n_tiles, (unsigned)L->n_kv_heads, (unsigned)L->n_req);
+      if (fuse) hipLaunchKernelGGL((scores_rows_bf16_kernel<0, true>), rgrid, dim3(256), kScoresRowsLds, st, a);
+      else hipLaunchKernelGGL((scores_rows_bf16_kernel<0, false>), rgrid, dim3(256), kScoresRowsLds, st, a);
       hipLaunchKernelGGL(scores_combine_kernel, dim3((unsigned)((total_rows + 15) / 16)), dim3(256), 0, st, a);
-      hipLaunchKernelGGL((scores_bf16_kernel<1, false, true>), grid, dim3(kScoreThreads), kScoresLds, st, a);
+      hipLaunchKernelGGL((scores_rows_bf16_kernel<1, false>), rgrid, dim3(256), kScoresRowsLds, st, a);
     } else {
-      if (fuse) hipLaunchKernelGGL((scores_bf16_kernel<0, true, false>), grid, dim3(kScoreThreads), kScoresLds, st, a);
-      else hipLaunchKernelGGL((scores_bf16_kernel<0, false, false>), grid, dim3(kScoreThreads), kScoresLds, st, a);
+      if (fuse) hipLaunchKernelGGL((scores_bf16_kernel<0, true>), grid, dim3(kScoreThreads), kScoresLds, st, a);
+      else hipLaunchKernelGGL((scores_bf16_kernel<0, false>), grid, dim3(kScoreThreads), kScoresLds, st, a);
       if (a.merged) hipLaunchKernelGGL(scores_combine_kernel, dim3((unsigned)((total_rows + 15) / 16)), dim3(256), 0, st, a);
-      hipLaunchKernelGGL((scores_bf16_kernel<1, false, false>), grid, dim3(kScoreThreads), kScoresLds, st, a);
+      hipLaunchKernelGGL((scores_bf16_kernel<1, false>), grid, dim3(kScoreThreads), kScoresLds, st, a);
     }
     if (scores)
       hipLaunchKernelGGL(scores_head_sum_kernel, dim3((L->total_tokens + 255) / 256), dim3(256), 0, st, a, L->tok_chunk);
