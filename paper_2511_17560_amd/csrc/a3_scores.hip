@@ -10,8 +10,11 @@
 //   head sum per token: the KV heads in order                      -> scores
 // Rows, then heads, are reduced in a fixed order, so the result is deterministic (no atomics).
 //
-// bf16: logits on the matrix cores (32x32x16 bf16 MFMA), keys and the rows' Q tile brought to LDS by
-// direct-to-LDS loads; see the kernel below.  exp2 with log2(e) folded into the scale.
+// bf16: logits on the matrix cores (32x32x16 bf16 MFMA), two kernels.  Up to 256 rows per KV head (a question of
+// 64 tokens at 4 query heads per KV head): keys and the rows' Q tile stream through LDS by direct-to-LDS loads,
+// one workgroup per CU with its whole run of keys in flight (scores_bf16_kernel).  More rows: a 256-key tile
+// stays in LDS and the waves walk the rows, two workgroups per CU (scores_rows_bf16_kernel).  exp2 with log2(e)
+// folded into the scale.
 // fp32: plain FMA kernels (correctness configuration).
 #include <mutex>
 
