@@ -38,7 +38,8 @@ __global__ void __launch_bounds__(kPlanThreads)
 attn_plan_kernel(attn_plan p, const int *__restrict__ act_idx, int n_act, const int *__restrict__ seg_start,
                  int n_req, int G, int wgs_per_head, int item_cost) {
   __shared__ int wave_tot[kPlanThreads / 64];
-  attn_plan_body(p, act_idx, n_act, seg_start, n_req, G, wgs_per_head, item_cost, wave_tot);
+  __shared__ int small[kPlanLdsInts];
+  attn_plan_body(p, act_idx, n_act, seg_start, n_req, G, wgs_per_head, item_cost, wave_tot, small, kPlanLdsInts);
 }
 
 struct attn_args {

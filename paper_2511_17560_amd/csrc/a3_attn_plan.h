@@ -11,6 +11,7 @@ namespace {
 constexpr int kTM = 256;            // packed (row, head) pairs per work item: 32 per wave of the attention kernel
 constexpr int kTK = 64;             // keys per tile
 constexpr int kPlanThreads = 1024;
+constexpr int kPlanLdsInts = 4096;  // LDS the plan kernel sets aside for the plan's small arrays (16 KB)
 
 // Work decomposition written by the plan kernel.
 //   tile  = 256 consecutive packed (row, head) pairs of one request and one KV head group; it needs
@@ -72,24 +73,39 @@ __device__ __forceinline__ int plan_scan(int v, int *wave_tot, int *total) {
 }
 
 // The whole plan, by one workgroup of kPlanThreads threads.  wave_tot: [kPlanThreads / 64] ints of LDS.
+// lds: lds_ints ints of LDS.  The searches below each are a chain of dependent reads; when the small arrays they
+// run over (row range and first tile of each request, running cost and key count of each tile) fit there, they
+// are kept in LDS beside their copies in the workspace (which the attention kernels read) and the chains run
+// at LDS latency instead of a round trip to the L2 per step.
 __device__ __forceinline__ void attn_plan_body(const attn_plan &p, const int *act_idx, int n_act,
                                                const int *__restrict__ seg_start, int n_req, int G, int wgs_per_head,
-                                               int item_cost, int *wave_tot) {
+                                               int item_cost, int *wave_tot, int *lds, int lds_ints) {
   const int tid = threadIdx.x;
-  // active rows are ascending, so the rows of request r are a contiguous range found by bisection
-  for (int r = tid; r <= n_req; r += kPlanThreads)
-    p.a_lo[r] = r == n_req ? n_act : lower_bound_i32(act_idx, n_act, seg_start[r]);
+  const bool in_lds = 2 * (n_req + 1) + 2 * p.max_tiles + 1 <= lds_ints;
+  int *a_lo = in_lds ? lds : p.a_lo;
+  int *tile_start = in_lds ? lds + (n_req + 1) : p.tile_start;
+  int *tile_pre = in_lds ? lds + 2 * (n_req + 1) : p.tile_pre;
+  int *tile_kv = in_lds ? lds + 2 * (n_req + 1) + p.max_tiles + 1 : nullptr;
+  // active rows are ascending, so the rows of request r are a contiguous range found by bisection (a batch of one
+  // request: all of them)
+  for (int r = tid; r <= n_req; r += kPlanThreads) {
+    const int v = r == n_req ? n_act : (r == 0 && n_req == 1 ? 0 : lower_bound_i32(act_idx, n_act, seg_start[r]));
+    a_lo[r] = v;
+    if (in_lds) p.a_lo[r] = v;
+  }
   __syncthreads();
   if (tid == 0) {
     int t = 0;
     for (int r = 0; r < n_req; ++r) {
-      p.tile_start[r] = t;
-      t += ((p.a_lo[r + 1] - p.a_lo[r]) * G + kTM - 1) / kTM;
+      tile_start[r] = t;
+      if (in_lds) p.tile_start[r] = t;
+      t += ((a_lo[r + 1] - a_lo[r]) * G + kTM - 1) / kTM;
     }
-    p.tile_start[n_req] = t;
+    tile_start[n_req] = t;
+    if (in_lds) p.tile_start[n_req] = t;
   }
   __syncthreads();
-  const int n_tiles = min(p.tile_start[n_req], p.max_tiles);
+  const int n_tiles = min(tile_start[n_req], p.max_tiles);
 
   // ---- tiles and their running cost -------------------------------------------------------
   // A tile is laid out as `item_cost` units of start-up (fetching its queries and first keys, storing its
@@ -99,22 +115,29 @@ __device__ __forceinline__ void attn_plan_body(const attn_plan &p, const int *ac
     const int t = base + tid;
     int steps = 0;
     if (t < n_tiles) {
-      const int r = upper_bound_i32(p.tile_start, n_req, t) - 1;     // last r with tile_start[r] <= t
-      const int j = t - p.tile_start[r];
-      const int nr = p.a_lo[r + 1] - p.a_lo[r];
+      const int r = upper_bound_i32(tile_start, n_req, t) - 1;       // last r with tile_start[r] <= t
+      const int j = t - tile_start[r];
+      const int nr = a_lo[r + 1] - a_lo[r];
       int last = ((j + 1) * kTM - 1) / G;
       if (last > nr - 1) last = nr - 1;
-      const int kv = act_idx[p.a_lo[r] + last] - seg_start[r] + 1;
+      const int kv = act_idx[a_lo[r] + last] - seg_start[r] + 1;
       steps = (kv + kTK - 1) / kTK;
       p.tile_a[t] = make_int4(r, j * kTM, kv, nr * G);
+      if (in_lds) tile_kv[t] = kv;
     }
     int total;
     const int before = plan_scan(t < n_tiles ? steps + item_cost : 0, wave_tot, &total);
-    if (t < n_tiles) p.tile_pre[t] = carry + before;
+    if (t < n_tiles) {
+      tile_pre[t] = carry + before;
+      if (in_lds) p.tile_pre[t] = carry + before;
+    }
     carry += total;
   }
   const int W = carry;                                       // cost of one head, >= n_tiles
-  if (tid == 0) p.tile_pre[n_tiles] = W;
+  if (tid == 0) {
+    tile_pre[n_tiles] = W;
+    if (in_lds) p.tile_pre[n_tiles] = W;
+  }
   __syncthreads();
 
   // ---- equal shares ------------------------------------------------------------------------
@@ -128,10 +151,10 @@ __device__ __forceinline__ void attn_plan_body(const attn_plan &p, const int *ac
     s_beg = (long long)tid * W / P;
     s_end = (long long)(tid + 1) * W / P;
     if (s_end > s_beg) {
-      t0 = upper_bound_i32(p.tile_pre, n_tiles + 1, (int)s_beg) - 1;    // tile that holds position s_beg
-      const int t1 = lower_bound_i32(p.tile_pre, n_tiles + 1, (int)s_end) - 1;   // ... and position s_end - 1
+      t0 = upper_bound_i32(tile_pre, n_tiles + 1, (int)s_beg) - 1;      // tile that holds position s_beg
+      const int t1 = lower_bound_i32(tile_pre, n_tiles + 1, (int)s_end) - 1;     // ... and position s_end - 1
       // the last tile only counts if the share reaches past its start-up units
-      cnt = t1 - t0 + 1 - (s_end <= (long long)p.tile_pre[t1] + item_cost ? 1 : 0);
+      cnt = t1 - t0 + 1 - (s_end <= (long long)tile_pre[t1] + item_cost ? 1 : 0);
     }
   }
   int n_items;
@@ -141,15 +164,15 @@ __device__ __forceinline__ void attn_plan_body(const attn_plan &p, const int *ac
   for (int i = 0; i < cnt; ++i) {
     const int t = t0 + i, idx = first + i;
     if (idx >= p.max_items) break;
-    const int pre = p.tile_pre[t] + item_cost, nxt = p.tile_pre[t + 1];  // key step s of the tile sits at pre + s
+    const int pre = tile_pre[t] + item_cost, nxt = tile_pre[t + 1];      // key step s of the tile sits at pre + s
     const int it_b = (int)(s_beg > pre ? s_beg - pre : 0), it_e = (int)((s_end < nxt ? s_end : nxt) - pre);
-    const int kv = p.tile_a[t].z;
+    const int kv = in_lds ? tile_kv[t] : p.tile_a[t].z;
     p.items[idx] = make_int4(t, it_b * kTK, min(kv, it_e * kTK), 0);
     if (it_b == 0) p.tile_b[t].x = idx;
   }
   // items of a tile = share boundaries strictly inside it + 1; boundary q lies at floor(q W / P)
   for (int t = tid; t < n_tiles; t += kPlanThreads) {
-    const long long x = (long long)p.tile_pre[t] + item_cost, y = p.tile_pre[t + 1];
+    const long long x = (long long)tile_pre[t] + item_cost, y = tile_pre[t + 1];
     const long long ub = ((x + 1) * P + W - 1) / W;          // first q with floor(q W / P) > x
     const long long lb = (y * P + W - 1) / W;                // first q with floor(q W / P) >= y
     p.tile_b[t].y = (int)(lb > ub ? lb - ub : 0) + 1;

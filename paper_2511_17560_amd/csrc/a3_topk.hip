@@ -317,7 +317,8 @@ topk_select_reg_kernel(const float *__restrict__ scores, topk_problem prob, int 
 template <int KPT>
 __global__ void __launch_bounds__(kBlock)
 topk_select_plan_kernel(const float *__restrict__ scores, topk_problem prob, int *__restrict__ sel_idx,
-                        int *act_idx, int n_act, attn_plan plan, int G, int wgs_per_head, int item_cost) {
+                        int *act_idx, int n_act, attn_plan plan, int G, int wgs_per_head, int item_cost,
+                        int lds_ints /* ints of dynamic LDS */) {
   extern __shared__ uint32_t keys[];
   __shared__ int wave_tot[kPlanThreads / 64];
   static_assert(kPlanThreads == kBlock, "one workgroup shape for both parts");
@@ -329,7 +330,9 @@ topk_select_plan_kernel(const float *__restrict__ scores, topk_problem prob, int
   for (int i = threadIdx.x; k + i < n_act; i += kBlock) act_idx[k + i] = s + N + i;   // the question rows
   __threadfence_block();
   __syncthreads();
-  attn_plan_body(plan, act_idx, n_act, prob.seg_start, 1, G, wgs_per_head, item_cost, wave_tot);
+  // (the keys' LDS is free now: it serves as the plan's scratch)
+  attn_plan_body(plan, act_idx, n_act, prob.seg_start, 1, G, wgs_per_head, item_cost, wave_tot,
+                 reinterpret_cast<int *>(keys), lds_ints);
 }
 
 constexpr int kMaxLdsKeys = 36 * 1024;   // 148.5 KB of padded keys next to the small static arrays
@@ -540,11 +543,11 @@ extern "C" a3_status a3_topk_select_plan(const a3_layout *L, const float *scores
   const int G = L->n_q_heads / L->n_kv_heads, wgs = plan.max_wgs, cost = attn_item_cost();
   const int per = (L->max_ctx_len + kBlock - 1) / kBlock;
   if (per <= 4)
-    hipLaunchKernelGGL(topk_select_plan_kernel<4>, dim3(1), dim3(kBlock), lds, st, scores, prob, sel_idx, act_idx, n_act, plan, G, wgs, cost);
+    hipLaunchKernelGGL(topk_select_plan_kernel<4>, dim3(1), dim3(kBlock), lds, st, scores, prob, sel_idx, act_idx, n_act, plan, G, wgs, cost, (int)(lds / sizeof(int)));
   else if (per <= 16)
-    hipLaunchKernelGGL(topk_select_plan_kernel<16>, dim3(1), dim3(kBlock), lds, st, scores, prob, sel_idx, act_idx, n_act, plan, G, wgs, cost);
+    hipLaunchKernelGGL(topk_select_plan_kernel<16>, dim3(1), dim3(kBlock), lds, st, scores, prob, sel_idx, act_idx, n_act, plan, G, wgs, cost, (int)(lds / sizeof(int)));
   else
-    hipLaunchKernelGGL(topk_select_plan_kernel<36>, dim3(1), dim3(kBlock), lds, st, scores, prob, sel_idx, act_idx, n_act, plan, G, wgs, cost);
+    hipLaunchKernelGGL(topk_select_plan_kernel<36>, dim3(1), dim3(kBlock), lds, st, scores, prob, sel_idx, act_idx, n_act, plan, G, wgs, cost, (int)(lds / sizeof(int)));
   A3_CHECK_LAUNCH("a3_topk_select_plan");
   return A3_OK;
 }
