@@ -87,14 +87,22 @@ struct topk_problem {
   const int *seg_start, *ctx_len, *sel_start;
   const int *skip, *q_len;
   long score_stride, out_stride;
+  // a batch of one request whose lengths the host knows (the layout's maxima add up to its rows): its context
+  // length and count, so that the kernel starts without a chain of loads; otherwise -1
+  int one_N = -1, one_k = -1;
 };
 
 struct topk_range { int s, N, k; const float *sc; int *out; };
 
 __device__ __forceinline__ topk_range topk_range_of(const topk_problem &p, const float *scores, int *sel_idx) {
+  topk_range t;
+  if (p.one_N >= 0) {
+    t.s = 0; t.N = p.one_N; t.k = min(p.one_k, p.one_N);
+    t.sc = scores; t.out = sel_idx;
+    return t;
+  }
   const int r = blockIdx.x;
   const int sk = p.skip ? p.skip[r] : 0;
-  topk_range t;
   t.s = p.seg_start[r] + sk;
   t.N = max(p.ctx_len[r] - sk, 0);
   t.k = p.sel_start[r + 1] - p.sel_start[r] - (p.skip ? sk + p.q_len[r] : 0);
@@ -324,7 +332,8 @@ topk_select_plan_kernel(const float *__restrict__ scores, topk_problem prob, int
   static_assert(kPlanThreads == kBlock, "one workgroup shape for both parts");
   topk_select_reg_body<KPT>(scores, prob, sel_idx, keys);
   __syncthreads();                                           // the selection is written (and has left this CU's L1 path)
-  const int k = prob.sel_start[1] - prob.sel_start[0], s = prob.seg_start[0], N = prob.ctx_len[0];
+  const int k = prob.one_N >= 0 ? prob.one_k : prob.sel_start[1] - prob.sel_start[0];
+  const int s = prob.one_N >= 0 ? 0 : prob.seg_start[0], N = prob.one_N >= 0 ? prob.one_N : prob.ctx_len[0];
   if (sel_idx != act_idx)
     for (int i = threadIdx.x; i < k; i += kBlock) act_idx[i] = sel_idx[i];
   for (int i = threadIdx.x; k + i < n_act; i += kBlock) act_idx[k + i] = s + N + i;   // the question rows
@@ -528,7 +537,11 @@ extern "C" a3_status a3_topk_select_plan(const a3_layout *L, const float *scores
              "a3_topk_select_plan: workspace %zu bytes, need %zu", ws_bytes, a3_attn_ws_bytes(L, n_act));
   attn_plan plan;
   attn_plan_carve(L, n_act, ws, ws_bytes, &plan);
-  const topk_problem prob{L->seg_start, L->ctx_len, sel_start, nullptr, nullptr, 0, 0};
+  topk_problem prob{L->seg_start, L->ctx_len, sel_start, nullptr, nullptr, 0, 0};
+  if (L->max_ctx_len + L->max_q_len == L->total_tokens) {   // the one request's lengths are the layout's maxima
+    prob.one_N = L->max_ctx_len;
+    prob.one_k = total_k;
+  }
   const size_t lds = ((size_t)L->max_ctx_len + L->max_ctx_len / 32 + 1) * sizeof(uint32_t);
   static a3_once_per_device lds_once;
   const hipError_t once_err = a3_once(lds_once, []() {
