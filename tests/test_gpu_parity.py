@@ -49,6 +49,9 @@ def _workload(name):
         return synth.custom(SMALL_BF16, [[300, 129, 260]], [90], ratio=(10, 100), n_planted=2, seed=48)
     if name == "manyq-g7-bf16":  # the same with 7 query heads per KV head, two requests, one of them with a single row chunk
         return synth.custom(SMALL_G7, [[140, 200], [90]], [40, 11], ratio=(20, 100), seed=49)
+    if name == "longq-bf16":     # a question far longer than the context: 19 row chunks in the scoring step, and more row tiles
+        # in the attention plan than the selection kernel's LDS (sized by the context) can hold next to each other
+        return synth.custom(SMALL_BF16, [[20, 12]], [1200], ratio=(25, 100), seed=50)
     if name == "cfg3-layer0":    # the 16K benchmark configuration, first and last of its 32 independent layers
         return synth.config(3, layer=0)
     if name in ("cfg3-layer1", "cfg3-layer15", "cfg3-layer31"):
@@ -70,7 +73,7 @@ def _workload(name):
 
 
 NAMES = ["cfg1", "cfg1-half", "ragged-bf16", "batched-bf16-half", "g7-bf16", "batched-f32-d128", "cfg2", "long-bf16",
-         "manyq-bf16", "manyq-g7-bf16"]
+         "manyq-bf16", "manyq-g7-bf16", "longq-bf16"]
 # full-size configurations: one oracle layer each takes tens of seconds, so each is built once and runs
 # the chained test and the teacher-forced tests of the three kernels whose behaviour depends on scale
 BIG_NAMES = ["cfg3-layer0", "cfg3-layer1", "cfg3-layer15", "cfg3-layer31", "cfg4", "cfg5"]
