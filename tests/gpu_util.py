@@ -23,6 +23,9 @@ def max_elem_rel(got: np.ndarray, want: np.ndarray, floor: float = 1e-3) -> floa
     """Worst element-wise relative error, max |a - b| / max(|b|, floor * max |b|): an element is measured against
     its own size, down to a floor of one thousandth of the tensor's largest entry."""
     want = np.asarray(want, dtype=np.float64)
+    assert np.shape(got) == want.shape, (np.shape(got), want.shape)
+    if want.size == 0:                 # nothing selected (ratio 0) or nothing left stale (ratio 1)
+        return 0.0
     scale = float(np.abs(want).max())
     if scale == 0.0:
         return float(np.abs(got - want).max())
@@ -31,5 +34,8 @@ def max_elem_rel(got: np.ndarray, want: np.ndarray, floor: float = 1e-3) -> floa
 
 def max_abs_rel(got: np.ndarray, want: np.ndarray) -> float:
     """max |a - b| / max |b| over the tensor."""
+    assert np.shape(got) == np.shape(want), (np.shape(got), np.shape(want))
+    if np.size(want) == 0:
+        return 0.0
     denom = float(np.abs(want).max())
     return float(np.abs(got - want).max()) / (denom if denom > 0 else 1.0)

@@ -52,6 +52,10 @@ def _workload(name):
     if name == "longq-bf16":     # a question far longer than the context: 19 row chunks in the scoring step, and more row tiles
         # in the attention plan than the selection kernel's LDS (sized by the context) can hold next to each other
         return synth.custom(SMALL_BF16, [[20, 12]], [1200], ratio=(25, 100), seed=50)
+    if name == "ratio0-bf16":    # nothing recomputed but the question (the concatenation with recovered positions)
+        return synth.custom(SMALL_BF16, [[120, 3, 211], [64]], [21, 2], ratio=(0, 100), seed=51)
+    if name == "ratio100-g7":    # everything recomputed (the full prefill), with one-token and two-token chunks
+        return synth.custom(SMALL_G7, [[183, 1, 112, 2], [93]], [5, 40], ratio=(100, 100), seed=52)
     if name == "cfg3-layer0":    # the 16K benchmark configuration, first and last of its 32 independent layers
         return synth.config(3, layer=0)
     if name in ("cfg3-layer1", "cfg3-layer15", "cfg3-layer31"):
@@ -73,7 +77,7 @@ def _workload(name):
 
 
 NAMES = ["cfg1", "cfg1-half", "ragged-bf16", "batched-bf16-half", "g7-bf16", "batched-f32-d128", "cfg2", "long-bf16",
-         "manyq-bf16", "manyq-g7-bf16", "longq-bf16"]
+         "manyq-bf16", "manyq-g7-bf16", "longq-bf16", "ratio0-bf16", "ratio100-g7"]
 # full-size configurations: one oracle layer each takes tens of seconds, so each is built once and runs
 # the chained test and the teacher-forced tests of the three kernels whose behaviour depends on scale
 BIG_NAMES = ["cfg3-layer0", "cfg3-layer1", "cfg3-layer15", "cfg3-layer31", "cfg4", "cfg5"]
