@@ -32,6 +32,29 @@ SMALL_G7 = synth.ModelShape("small-g7", "bf16", 192, 7, 1, 128, 1000000.0)
 SMALL_F32_D128 = synth.ModelShape("small-f32-d128", "f32", 96, 4, 2, 128, 10000.0, synth.ROPE_HALF)
 
 
+RANDOM_SHAPES = [SMALL_BF16, SMALL_BF16_HALF, SMALL_G7, SMALL_F32_D128,
+                 synth.ModelShape("small-g8", "bf16", 128, 8, 1, 128, 10000.0),
+                 synth.ModelShape("small-g1", "bf16", 128, 2, 2, 128, 10000.0, synth.ROPE_HALF),
+                 synth.ModelShape("small-g2", "bf16", 192, 8, 4, 128, 500000.0)]
+
+
+def _random_workload(seed):
+    """A seeded draw over what the fixed cases hold constant: the model shape (G = 1, 2, 4, 7, 8), 1-6 requests of 1-5
+    chunks, chunk and question lengths from one token up to a few hundred (now and then a couple of thousand), and
+    the ratio, the degenerate 0 and 1 included."""
+    rng = np.random.default_rng(seed)
+    shape = RANDOM_SHAPES[rng.integers(len(RANDOM_SHAPES))]
+    long_chunks = rng.random() < 0.3
+    chunk_lens, q_lens = [], []
+    for _ in range(int(rng.integers(1, 7))):
+        hi = 2000 if long_chunks else 300
+        chunk_lens.append([int(rng.integers(1, hi)) if rng.random() < 0.8 else int(rng.integers(1, 4))
+                           for _ in range(int(rng.integers(1, 6)))])
+        q_lens.append(int(rng.integers(1, 150)) if rng.random() < 0.8 else int(rng.integers(1, 4)))
+    num = int(rng.choice([0, 1, 5, 10, 15, 25, 50, 99, 100]))
+    return synth.custom(shape, chunk_lens, q_lens, ratio=(num, 100), seed=seed, name=f"random-{seed}")
+
+
 def _workload(name):
     if name == "cfg1":
         return synth.config(1)
@@ -56,6 +79,8 @@ def _workload(name):
         return synth.custom(SMALL_BF16, [[120, 3, 211], [64]], [21, 2], ratio=(0, 100), seed=51)
     if name == "ratio100-g7":    # everything recomputed (the full prefill), with one-token and two-token chunks
         return synth.custom(SMALL_G7, [[183, 1, 112, 2], [93]], [5, 40], ratio=(100, 100), seed=52)
+    if name.startswith("random-"):
+        return _random_workload(int(name[len("random-"):]))
     if name == "cfg3-layer0":    # the 16K benchmark configuration, first and last of its 32 independent layers
         return synth.config(3, layer=0)
     if name in ("cfg3-layer1", "cfg3-layer15", "cfg3-layer31"):
@@ -441,6 +466,23 @@ def test_chained_layer(name, fused_scatter=True, fused_realign=True, fused_plan=
     stale = np.setdiff1d(np.arange(w.total_tokens), np.union1d(got_act, want_act))
     assert max_abs_rel(to_host(bufs.k_fused)[stale], res["k_fused"][stale]) <= (1e-5 if dt == "f32" else 2.0 ** -7)
     assert np.array_equal(to_host(v_cache)[stale], res["v_fused"][stale])
+
+
+@pytest.mark.parametrize("seed", range(7000, 7024))
+def test_random_workloads(seed):
+    """Every step against the oracle, the merged calls against the separate ones, and the chained layer in both call
+    sequences, on seeded random batches."""
+    name = f"random-{seed}"
+    try:
+        for check in (test_layout_tables, test_question_scores, test_topk_select_bit_exact_on_oracle_scores,
+                      test_selected_qkv_proj, test_kv_scatter_and_active_rows, test_fused_attention,
+                      test_topk_select_plan_equals_the_three_calls, test_attention_in_two_calls, test_chained_layer,
+                      test_chained_layer_plain_six_call_sequence):
+            check(name)
+        test_rope_realign(name, True)
+        test_realign_scores_single_call(name, False)
+    finally:
+        _cache.pop(name, None)
 
 
 @pytest.mark.parametrize("case", ["ties", "all-equal", "k-zero-and-full", "long-global-path", "negatives", "vector-tail-4k",
