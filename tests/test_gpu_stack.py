@@ -170,6 +170,14 @@ STACK_CASES = {
                    [[100, 37, 300, 65]], [19], (15, 100), 4),
     "batched-bf16": (synth.ModelShape("small-stack", "bf16", 256, 8, 2, 128, 500000.0, synth.ROPE_HALF, ffn=384),
                      [[130, 70], [33], [257, 64, 90]], [5, 33, 12], (20, 100), 3),
+    # seven query heads on one KV head, a feed-forward width that is no multiple of a tile, one-token chunks
+    "g7-bf16": (synth.ModelShape("g7-stack", "bf16", 256, 7, 1, 128, 1000000.0, synth.ROPE_INTERLEAVED, ffn=320),
+                [[90, 1, 120, 2], [50]], [11, 30], (25, 100), 3),
+    # the two ends of the ratio: everything recomputed (the schedule is then the plain prefill), nothing but the question
+    "all-rows-bf16": (synth.ModelShape("small-stack", "bf16", 256, 4, 2, 128, 500000.0, synth.ROPE_HALF, ffn=512),
+                      [[70, 45], [80]], [9, 4], (100, 100), 3),
+    "question-only-f32": (synth.ModelShape("tiny-stack", "f32", 128, 4, 2, 64, 10000.0, synth.ROPE_HALF, ffn=192),
+                          [[60, 41], [33]], [9, 14], (0, 100), 3),
 }
 
 
