@@ -549,6 +549,89 @@ def test_full_size_config(name):
     _cache.pop(name, None)
 
 
+def test_layer_at_128k_context():
+    """One layer on 131072 context tokens (256 chunks of 512) and a 64-token question in the Llama-3-8B shape, r = 5 %:
+    eight times the benchmark's context, a gigabyte of hidden states, 2048 key tiles per row of the attention, the
+    selection's path for inputs that do not fit its LDS.  The inputs are drawn on the device; the oracle then gets
+    what each step read on the GPU: the realigned cache for all of Eq. 3 (every score is compared), the GPU's scores
+    for the selection (bit-exact), and sampled rows for Eq. 2, Eq. 5 and Eq. 4."""
+    shape = synth.ModelShape("llama-3-8b", "bf16", 4096, 32, 8, 128, 500000.0)
+    dt, n_ctx, nq = "bf16", 131072, 64
+    w = synth.custom(shape, [[512] * (n_ctx // 512)], [nq], ratio=(5, 100), seed=93)
+    T, h, Hq, Hkv, d = w.total_tokens, shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim
+    g = torch.Generator(device="cuda")
+    g.manual_seed(93)
+    draw = lambda *sz, std: (torch.randn(sz, generator=g, device="cuda", dtype=torch.float32) * std).to(torch.bfloat16)
+    x = draw(T, h, std=1.0)
+    k_cat, v_cache = draw(T, Hkv, d, std=0.02 * h ** 0.5), draw(T, Hkv, d, std=0.02 * h ** 0.5)
+    # wider query/key weights than 0.02, so that the scores are not all alike and the ranking means something
+    wq, wk, wv = draw(Hq * d, h, std=0.04), draw(Hkv * d, h, std=0.04), draw(Hkv * d, h, std=0.02)
+    v_stale = v_cache.clone()
+    lay = api.Layout.from_workload(w)
+    bufs = layer.make_buffers(lay, w.sel_start, w.question_rows(), shape)
+    layer.fuse_layer(lay, bufs, x, k_cat, v_cache, wq, wk, wv)
+    torch.cuda.synchronize()
+    n_act, total_k = bufs.n_act, int(w.sel_start[-1])
+    assert total_k == 6553 and n_act == total_k + nq
+    act = bufs.act_idx.cpu().numpy()[:n_act].astype(np.int64)
+    q_rows = np.asarray(w.question_rows(), dtype=np.int64)
+    assert np.all(np.diff(act) > 0) and np.array_equal(act[total_k:], q_rows)
+    rng = np.random.default_rng(94)
+    pos = np.asarray(w.token_positions())
+    proj = dict(n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, base=shape.rope_base, layout=shape.rope_layout, storage=dt)
+    scale = 1.0 / np.sqrt(d)
+    host = lambda t, rows: to_host(t[torch.as_tensor(rows, device="cuda")])
+    wq_h, wk_h, wv_h = to_host(wq), to_host(wk), to_host(wv)
+    k_fused = to_host(bufs.k_fused)
+
+    # Eq. 2: the cache the scores were taken on is the realign kernel's output bit for bit (checked at small sizes
+    # for every element); here on the rows nobody recomputed, and against the oracle on sampled rows, chunk edges
+    # among them (rotation by the chunk's offset, one rounding)
+    k_re = torch.empty_like(k_cat)
+    api.a3_rope_realign(lay, k_cat, k_re)
+    torch.cuda.synchronize()
+    rest = np.setdiff1d(np.arange(T), act)
+    rest_d = torch.as_tensor(rest, device="cuda")
+    assert torch.equal(bufs.k_fused[rest_d], k_re[rest_d]) and torch.equal(v_cache[rest_d], v_stale[rest_d])
+    rows = np.unique(np.concatenate([[0, 1, 511, 512, 513, 130559, 130560, n_ctx - 1], rng.choice(n_ctx, size=56, replace=False)]))
+    want = ora.store(ora.rope_rotate(host(k_cat, rows), (rows // 512) * 512, shape.rope_base, shape.rope_layout), dt)
+    assert max_abs_rel(host(k_re, rows), want) <= 2.0 ** -7
+
+    # Eq. 3, first line: every score, on that cache
+    k_scored = to_host(k_re)
+    del k_re
+    # (with the Q the layer pass scored with: its first call, repeated here; the question rows of q_act hold the
+    # second projection's Q by now, which may differ from it in a last bit)
+    q_scored = torch.empty((nq, Hq, d), dtype=torch.bfloat16, device="cuda")
+    api.a3_selected_qkv_proj(lay, x, bufs.q_rows, nq, wq, None, None, q_out=q_scored)
+    torch.cuda.synchronize()
+    qq, _, _ = ora.selected_qkv_proj(host(x, q_rows), np.arange(nq), pos[q_rows], wq_h, wk_h, wv_h, **proj)
+    assert max_abs_rel(to_host(q_scored), qq) <= 2e-2 and max_abs_rel(to_host(bufs.q_act)[total_k:], qq) <= 2e-2
+    want_scores = ora.question_scores(to_host(q_scored), k_scored, w.seg_start, w.ctx_len, w.q_lens, scale)
+    got_scores = to_host(bufs.scores)
+    assert max_abs_rel(got_scores[:n_ctx], want_scores[:n_ctx]) <= 1e-4
+    assert max_elem_rel(got_scores[:n_ctx], want_scores[:n_ctx]) <= 1e-3
+    assert abs(got_scores[:n_ctx].sum() - Hq * nq) <= 1e-3 * Hq * nq and np.all(np.isneginf(got_scores[n_ctx:]))
+
+    # Eq. 3, second line: exactly the 6553 best of the GPU's own scores, ties to the lower row
+    want_sel = ora.topk_select(got_scores.astype(np.float32), w.seg_start, w.ctx_len, w.sel_start)
+    assert np.array_equal(act[:total_k], want_sel)
+    overlap = len(set(want_sel.tolist()) & set(ora.topk_select(want_scores, w.seg_start, w.ctx_len, w.sel_start).tolist()))
+    assert overlap >= 0.98 * total_k
+
+    # Eq. 5 on sampled active rows (the first and last selected row and the question's ends among them)
+    pick = np.unique(np.concatenate([[0, 1, total_k - 1, total_k, n_act - 1], rng.choice(n_act, size=19, replace=False)]))
+    q, k, v = ora.selected_qkv_proj(host(x, act[pick]), np.arange(len(pick)), pos[act[pick]], wq_h, wk_h, wv_h, **proj)
+    assert max_abs_rel(to_host(bufs.q_act)[pick], q) <= 2e-2
+    assert max_abs_rel(k_fused[act[pick]], k) <= 2e-2 and max_abs_rel(host(v_cache, act[pick]), v) <= 2e-2
+    # Eq. 4 for those rows over up to 131136 keys each, on the caches the GPU attended
+    o = ora.fused_attention(to_host(bufs.q_act)[pick], act[pick], k_fused, to_host(v_cache), w.seg_start, scale, dt)
+    got_o = to_host(bufs.out)[pick]
+    assert max_abs_rel(got_o, o) <= 2e-2
+    vmax = float(torch.abs(v_cache.float()).max())
+    assert np.all(np.abs(got_o - o) <= 2.0 ** -8 * np.abs(o) + 2.0 ** -8 * vmax)
+
+
 def test_planned_attention_leaves_out_alone_when_the_plan_was_made_with_another_tuning(tuning):
     """The number of workgroups per head decides where the plan's tables lie in the workspace.  A planned call
     that finds a plan made with another value must not read those tables: it leaves `out` as it was."""
