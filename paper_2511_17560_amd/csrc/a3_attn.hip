@@ -165,7 +165,7 @@ attn_bf16_kernel(attn_args a) {
 #define A3_KDMA(BUF, K0)                                                                                     \
     _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                          \
       const char *gp_ = kb + min(ko_0 + ((uint32_t)(K0) + 16u * j) * pitch_b, k_last);                       \
-      asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"                                     \
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"                                     \
                    :: "s"(__builtin_amdgcn_readfirstlane(lds_k + (BUF) * (kKTile * 2) + 4 * (4 * j + dwave) * kKRowBytes)), \
                       "v"(gp_) : "memory");                                                                  \
     }

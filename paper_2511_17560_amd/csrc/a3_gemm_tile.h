@@ -47,10 +47,12 @@ __device__ __forceinline__ void gemm_tile_mainloop(f32x16 (&acc)[4][TB], unsigne
   // inline assembly on purpose: the compiler then neither tracks these as LDS writes (it would put
   // a full vmcnt(0) in front of every LDS read and undo the lookahead) nor reorders memory accesses
   // across them; the waits for them are the explicit s_waitcnt below.  M0 is not used by anything
-  // else in these kernels (LDS instructions need no M0 on gfx9 and later).
+  // else in these kernels (LDS instructions need no M0 on gfx9 and later).  The s_nop is the wait state this
+  // chip wants between a scalar write of M0 and a direct-to-LDS load that reads it (the compiler puts the same
+  // one behind its own M0 writes; it does not look into an asm statement).
   const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds;
 #define A3_DMA(GPTR, LDS_OFF)                                                                                 \
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"                                          \
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"                                \
                :: "s"(__builtin_amdgcn_readfirstlane(lds_base + (uint32_t)(LDS_OFF))), "v"(GPTR) : "memory")
   // A wave that issues an LDS read or a vector-memory instruction is held until the unit takes it, and
   // with one wave per SIMD nothing else fills that time: a batch of seven reads in front of twelve

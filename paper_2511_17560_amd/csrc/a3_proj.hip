@@ -316,11 +316,11 @@ proj_small_dma_bf16_kernel(proj_args a) {
 #define A3_SM_ISSUE(SLOT, K0)                                                                                  \
   {                                                                                                            \
     _Pragma("unroll") for (int j = 0; j < 4; ++j)                                                              \
-      asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"                                       \
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"                                       \
                    :: "s"(__builtin_amdgcn_readfirstlane(lds_ring + (SLOT) * kSmStageBytes + 1024 * j)),       \
                       "v"(wsrc[j] + 2 * (K0)) : "memory");                                                     \
     _Pragma("unroll") for (int j = 0; j < 4 * RB; ++j)                                                         \
-      asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"                                       \
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"                                       \
                    :: "s"(__builtin_amdgcn_readfirstlane(lds_ring + (SLOT) * kSmStageBytes + 4096 + 1024 * j)), \
                       "v"(xsrc[j] + 2 * (K0)) : "memory");                                                     \
   }

@@ -253,7 +253,7 @@ scores_bf16_kernel(scores_args a) {
   _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                              \
     const int row_ = min(s + i0k + (I) * kSlotKeys + drow + 16 * j, a.T - 1);  /* past the run: loaded, masked */ \
     const bf16_t *gp_ = K + ((size_t)row_ * a.Hkv + g) * kD + dpiece * 8;                                      \
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"                                         \
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"                                         \
                  :: "s"(__builtin_amdgcn_readfirstlane(lds_base + ((I) & (kSlots - 1)) * kSlotBytes +           \
                                                        4 * (4 * j + (wave & 3)) * kKRowBytes)), "v"(gp_) : "memory"); \
   }
@@ -262,7 +262,7 @@ scores_bf16_kernel(scores_args a) {
   _Pragma("unroll") for (int j = 0; j < 16; ++j) {                                                             \
     const int m_ = min((MBASE) + drow + 16 * j, Mg - 1);                                                       \
     const bf16_t *gp_ = Q + (size_t)row_of(m_) * kD + dpiece * 8;                                              \
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"                                         \
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"                                         \
                  :: "s"(__builtin_amdgcn_readfirstlane(lds_base + kLdsQ + 4 * (4 * j + wave) * kKRowBytes)), "v"(gp_) \
                  : "memory");                                                                                  \
   }
@@ -688,7 +688,7 @@ scores_rows_bf16_kernel(scores_args a) {
     for (int j = 0; j < kRowsTileKeys / 16; ++j) {
       const int row = min(s + i0 + drow + 16 * j, a.T - 1);    // tail rows: loaded, masked below
       const bf16_t *gp = K + ((size_t)row * a.Hkv + g) * kD + dpiece * 8;
-      asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
                    :: "s"(__builtin_amdgcn_readfirstlane(lds_k + 4 * (4 * j + wave) * kKRowBytes)), "v"(gp) : "memory");
     }
     // at most the 4 (3 - QT) younger instructions of this wave are still in flight: its part of quarter QT
